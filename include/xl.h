@@ -1,0 +1,207 @@
+/*
+ * xl -- cross-layer fused CNN blocks for AMD MI355X (gfx950 / CDNA4).
+ *
+ * C ABI of libxl.so.  Plain C types only: no C++ objects, no torch types, no
+ * HIP types (a stream is passed as `void*` holding a hipStream_t).
+ *
+ * What the library does.  A convolutional network is given as a small layer
+ * graph plus a list of fusion blocks.  Each block is one of the paper's three
+ * fusion modes (section 3.1, Fig. 4): straight (Layer1 -> Layer2), split
+ * (Layer1 -> {Layer2, Layer3}) or merge (two producers -> one consumer).  For
+ * every block `xl_plan_create` picks an output tile and the halo ("redundant
+ * data", section 3.2) each workgroup must recompute so that the block's
+ * intermediate feature map can stay in LDS, against the LDS capacity of one
+ * compute unit (section 3.2: shared memory is the bottleneck resource, keep the
+ * share per block well below the whole).  `xl_run` then executes the network:
+ * one fused kernel per block (intermediate in LDS, section 2.2 Fig. 3b:
+ * LD.G, CONV1, ST.S, barrier, LD.S, CONV2, ST.G) or, for comparison, one
+ * kernel per layer with every intermediate written to and re-read from HBM
+ * (Fig. 3a).  Both paths use the same tiled implicit-GEMM convolution
+ * (section 3.2) on the fp32 matrix cores.
+ *
+ * Data.  All tensors are dense fp32 NCHW in DEVICE memory owned by the caller
+ * (e.g. allocated by PyTorch).  Filters are [Cout, Cin, K, K] fp32 (section 4.1
+ * notation), per-channel scale/shift/bias vectors are [Cout] fp32.  The library
+ * allocates no device memory; intermediates and re-laid-out filters live in a
+ * caller-provided workspace of `xl_plan_workspace_bytes` bytes, 256-byte
+ * aligned.  A plan owns host metadata only.
+ *
+ * Calls never throw or abort.  `xl_prepare` and `xl_run` only enqueue work on
+ * the given stream and return without synchronising.  Every function returns
+ * XL_OK (0) or a negative xl_status; `xl_strerror` names it, and
+ * `xl_plan_last_error` gives a longer message for the last failure on a plan
+ * handle (or of the last failed `xl_plan_create` when passed NULL).
+ */
+#ifndef XL_H
+#define XL_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int xl_status;
+#define XL_OK              0
+#define XL_E_NULL        (-1)   /* a required pointer was NULL                          */
+#define XL_E_SHAPE       (-2)   /* tensor shapes do not fit the layer parameters        */
+#define XL_E_UNSUPPORTED (-3)   /* layer or fusion block outside what the kernels cover */
+#define XL_E_LDS_BUDGET  (-4)   /* no tile fits the LDS budget (paper section 3.2: the
+                                   kernel would fail for resource limitation)           */
+#define XL_E_DEVICE      (-5)   /* device is not gfx950 or cannot be queried            */
+#define XL_E_ALIGN       (-6)   /* workspace or tensor pointer not aligned              */
+#define XL_E_LAUNCH      (-7)   /* a kernel launch was rejected by the runtime          */
+#define XL_E_GRAPH       (-8)   /* graph wiring invalid (ids, order, group membership)  */
+#define XL_E_STATE       (-9)   /* xl_run before xl_prepare on this workspace           */
+
+/* Layer kinds (paper section 2.2: convolution, pooling, activation, element-wise
+ * addition and concatenation are the basic operations; activation rides in the
+ * producing layer's epilogue). */
+enum { XL_CONV = 0, XL_MAXPOOL = 1, XL_GLOBAL_AVGPOOL = 2, XL_ADD = 3, XL_CONCAT = 4 };
+
+/* Fusion modes (paper section 3.1, Fig. 4).  XL_SINGLE is a block of one layer. */
+enum { XL_SINGLE = 0, XL_STRAIGHT = 1, XL_SPLIT = 2, XL_MERGE = 3 };
+
+typedef struct xl_shape { int n, c, h, w; } xl_shape;        /* dense NCHW fp32 */
+
+/*
+ * One layer.  `in` / `out` are tensor ids (indices into the shapes array);
+ * in[1] is used by XL_ADD and XL_CONCAT only (-1 otherwise).
+ * XL_CONV:   y = act(scale * corr(x, filter) + shift); square K x K filter,
+ *            zero padding, groups must be 1.  Slots index the `weights` array of
+ *            xl_prepare; scale_slot / shift_slot may be -1 (scale 1 / shift 0).
+ *            A bias is a shift with no scale; a folded batch-norm is both.
+ * XL_MAXPOOL: K x K window, stride, pad; out-of-image taps are ignored.
+ * XL_GLOBAL_AVGPOOL: mean over H x W -> [N, C, 1, 1].
+ * XL_ADD:    y = act(in[0] + in[1]).
+ * XL_CONCAT: channels of in[0] then in[1]; costs nothing: the producers write
+ *            straight into the concatenated tensor at their channel offset.
+ */
+typedef struct xl_layer {
+    int op;
+    int in[2];
+    int out;
+    int cin, cout;
+    int k, stride, pad, groups;
+    int relu;
+    int w_slot, scale_slot, shift_slot;
+} xl_layer;
+
+/* A fusion block: `mode` and the layer indices it covers, in graph order.
+ *   XL_STRAIGHT: conv -> conv, or conv -> maxpool
+ *   XL_SPLIT:    conv -> {conv, conv} [-> concat]
+ *   XL_MERGE:    conv -> conv -> add(., block input)          (residual block)
+ *   XL_SINGLE:   any one layer
+ * Layers not listed in any block are planned as XL_SINGLE. */
+typedef struct xl_group {
+    int mode;
+    int nlayers;
+    const int *layer_ids;
+} xl_group;
+
+/* Planner knobs; zero-initialise for defaults. */
+typedef struct xl_options {
+    int lds_budget_bytes;   /* LDS one workgroup may use; 0 = device limit (160 KB on gfx950) */
+    int num_cus;            /* compute units to fill; 0 = query device (256 when device < 0)  */
+    int force_tile_h;       /* >0: fix the output tile of every fused block (tests, tuning)   */
+    int force_tile_w;
+    int force_cout_split;   /* >0: fix how many workgroups share one tile's output channels   */
+    int paper_tuner_only;   /* 1: restrict candidates to the paper's square common-factor
+                               (tile, grid) pairs (section 3.2)                               */
+} xl_options;
+
+/* What the planner decided for one block (all sizes in elements unless named bytes). */
+typedef struct xl_group_info {
+    int mode;
+    int first_layer, nlayers;
+    int tile_h, tile_w;         /* output tile of the block's last spatial layer            */
+    int mid_h, mid_w;           /* on-chip intermediate tile incl. halo (0 for XL_SINGLE)   */
+    int in_h, in_w;             /* input tile incl. halo                                    */
+    int tiles_y, tiles_x;       /* grid over the output image (paper: "grid size")          */
+    int cout_split;             /* workgroups sharing a tile, each a slice of Cout          */
+    int workgroups;             /* tiles_y * tiles_x * cout_split * N                       */
+    int threads;                /* workgroup size                                           */
+    int lds_bytes;              /* LDS per workgroup                                        */
+    int workgroups_per_cu;      /* co-resident workgroups the LDS share allows              */
+    int chunk_channels;         /* input channels staged through LDS per pipeline step      */
+    long long bytes_fused;      /* algorithmic HBM bytes: block input + filters + output    */
+    long long bytes_unfused;    /* same with every layer reading/writing HBM                */
+    long long stores_fused;     /* elements written to HBM, fused   (paper Table 2)         */
+    long long stores_unfused;   /* elements written to HBM, unfused (paper Table 2)         */
+    long long flops;            /* 2*MAC, no halo recompute                                 */
+    long long flops_executed;   /* 2*MAC the fused kernel issues incl. halo and tile padding */
+    double redundancy;          /* intermediate elements computed / unique elements         */
+} xl_group_info;
+
+typedef struct xl_plan xl_plan;
+
+/*
+ * Validate the graph and blocks, choose tiles, build launch descriptors.
+ * Host only; touches the device solely to query its properties when
+ * device >= 0 (device < 0 plans for a nominal gfx950: 256 CUs, 160 KB LDS,
+ * and works on a machine without a GPU).  `opts` may be NULL.
+ * On success *out holds a plan to be freed with xl_plan_destroy.
+ */
+xl_status xl_plan_create(const xl_layer *layers, int nlayers,
+                         const xl_shape *shapes, int ntensors,
+                         const xl_group *groups, int ngroups,
+                         int device, const xl_options *opts, xl_plan **out);
+
+void xl_plan_destroy(xl_plan *plan);
+
+int xl_plan_num_groups(const xl_plan *plan);
+
+xl_status xl_plan_query(const xl_plan *plan, int group, xl_group_info *out);
+
+/* Bytes of caller-provided device workspace (filters re-laid out for the matrix
+ * cores + every intermediate tensor of the unfused path). */
+size_t xl_plan_workspace_bytes(const xl_plan *plan);
+
+/*
+ * Re-lay the filters into `workspace` (device) for the matrix-core kernels and
+ * record the scale/shift pointers.  `weights[slot]` are DEVICE pointers indexed
+ * by the slots named in xl_layer; they must stay valid and unchanged until the
+ * last xl_run that uses this workspace has finished.  Call once per workspace,
+ * and again whenever filter values change.  Enqueues on `stream`; returns
+ * without synchronising.
+ */
+xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights,
+                     void *workspace, void *stream);
+
+/*
+ * Execute the network once.  `tensors[id]` are DEVICE pointers by tensor id;
+ * only tensors that no layer produces (graph inputs) and tensors that no layer
+ * consumes (graph outputs) are read from this array -- every other entry may be
+ * NULL and lives in the workspace.  fused = 1: one kernel per fusion block;
+ * fused = 0: one kernel per layer (concat still free).  Stream-ordered,
+ * asynchronous; results are complete when the stream reaches this point.
+ * Two xl_run calls that share a workspace must be ordered on one stream.
+ */
+xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
+                 void *workspace, void *stream, int fused);
+
+/* Number of kernel launches one xl_run issues in the given mode. */
+int xl_plan_num_launches(const xl_plan *plan, int fused);
+
+/*
+ * The paper's tuner search space (section 3.2): square tiles whose size and
+ * grid are complementary non-trivial factors of the output size; a prime size
+ * is replaced by the next larger non-prime.  Writes up to `cap` (tile, grid)
+ * pairs into tile[] / grid[] and returns how many exist.
+ */
+int xl_tuner_candidates(int out_size, int *tile, int *grid, int cap);
+
+/* Halo arithmetic of section 3.2: input extent needed for `t` outputs of a
+ * K-wide, stride-s window: (t - 1) * s + K. */
+int xl_required_extent(int t, int k, int stride);
+
+const char *xl_strerror(xl_status st);
+const char *xl_plan_last_error(const xl_plan *plan);
+
+/* Version / build string, e.g. "xl 0.1 gfx950". */
+const char *xl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XL_H */

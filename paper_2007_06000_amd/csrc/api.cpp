@@ -1,0 +1,250 @@
+// C ABI of libxl (see include/xl.h).
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "plan.h"
+
+namespace xl {
+xl_status build_plan(xl_plan &pl, const xl_group *groups, int ngroups);
+int tuner_candidates(int out_size, int *tile, int *grid, int cap);
+int required_extent(int t, int k, int s);
+}  // namespace xl
+
+static thread_local std::string g_create_error;
+
+static constexpr int GFX950_LDS_BYTES = 160 * 1024;
+static constexpr int GFX950_CUS = 256;
+
+extern "C" {
+
+const char *xl_version(void) { return "xl 0.1 gfx950"; }
+
+const char *xl_strerror(xl_status st)
+{
+    switch (st) {
+    case XL_OK: return "ok";
+    case XL_E_NULL: return "null pointer";
+    case XL_E_SHAPE: return "tensor shapes do not fit the layer parameters";
+    case XL_E_UNSUPPORTED: return "layer or fusion block not supported";
+    case XL_E_LDS_BUDGET: return "no tile fits the LDS budget";
+    case XL_E_DEVICE: return "device is not gfx950 or cannot be queried";
+    case XL_E_ALIGN: return "pointer not aligned";
+    case XL_E_LAUNCH: return "kernel launch failed";
+    case XL_E_GRAPH: return "invalid graph wiring";
+    case XL_E_STATE: return "xl_prepare has not been called for this workspace";
+    }
+    return "unknown status";
+}
+
+const char *xl_plan_last_error(const xl_plan *plan) { return plan ? plan->error.c_str() : g_create_error.c_str(); }
+
+int xl_tuner_candidates(int out_size, int *tile, int *grid, int cap) { return xl::tuner_candidates(out_size, tile, grid, cap); }
+
+int xl_required_extent(int t, int k, int stride) { return xl::required_extent(t, k, stride); }
+
+xl_status xl_plan_create(const xl_layer *layers, int nlayers, const xl_shape *shapes, int ntensors,
+                         const xl_group *groups, int ngroups, int device, const xl_options *opts, xl_plan **out)
+{
+    g_create_error.clear();
+    if (!out) return XL_E_NULL;
+    *out = nullptr;
+    if (!layers || !shapes || (ngroups > 0 && !groups)) {
+        g_create_error = "layers, shapes or groups is NULL";
+        return XL_E_NULL;
+    }
+    if (nlayers < 1 || ntensors < 1 || ngroups < 0) {
+        g_create_error = "empty graph";
+        return XL_E_GRAPH;
+    }
+    xl_plan *pl = new (std::nothrow) xl_plan;
+    if (!pl) return XL_E_NULL;
+    pl->layers.assign(layers, layers + nlayers);
+    pl->shapes.assign(shapes, shapes + ntensors);
+    if (opts) pl->opts = *opts;
+    pl->device = device;
+    pl->lds_per_cu = GFX950_LDS_BYTES;
+    pl->num_cus = GFX950_CUS;
+    if (device >= 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, device) != hipSuccess || strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+            g_create_error = "device is not a gfx950 GPU";
+            delete pl;
+            return XL_E_DEVICE;
+        }
+        pl->num_cus = prop.multiProcessorCount;
+    }
+    if (pl->opts.num_cus > 0) pl->num_cus = pl->opts.num_cus;
+    pl->lds_budget = pl->lds_per_cu;
+    if (pl->opts.lds_budget_bytes > 0) pl->lds_budget = std::min(pl->opts.lds_budget_bytes, pl->lds_per_cu);
+    xl_status st = xl::build_plan(*pl, groups, ngroups);
+    if (st != XL_OK) {
+        g_create_error = pl->error;
+        delete pl;
+        return st;
+    }
+    *out = pl;
+    return XL_OK;
+}
+
+void xl_plan_destroy(xl_plan *plan) { delete plan; }
+
+int xl_plan_num_groups(const xl_plan *plan) { return plan ? (int)plan->groups.size() : 0; }
+
+xl_status xl_plan_query(const xl_plan *plan, int group, xl_group_info *out)
+{
+    if (!plan || !out) return XL_E_NULL;
+    if (group < 0 || group >= (int)plan->groups.size()) return XL_E_GRAPH;
+    *out = plan->groups[group].info;
+    return XL_OK;
+}
+
+size_t xl_plan_workspace_bytes(const xl_plan *plan) { return plan ? plan->workspace_bytes : 0; }
+
+int xl_plan_num_launches(const xl_plan *plan, int fused)
+{
+    if (!plan) return 0;
+    return (int)(fused ? plan->fused_steps.size() : plan->unfused_steps.size());
+}
+
+static xl_status configure_once(xl_plan *plan)
+{
+    static std::mutex mu;
+    static bool done[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        plan->error = "no current HIP device";
+        return XL_E_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!done[dev]) {
+        hipError_t e = xl::configure_kernels(GFX950_LDS_BYTES);
+        if (e != hipSuccess) {
+            plan->error = std::string("cannot raise the dynamic LDS limit: ") + hipGetErrorString(e);
+            return XL_E_DEVICE;
+        }
+        done[dev] = true;
+    }
+    return XL_OK;
+}
+
+xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, void *workspace, void *stream)
+{
+    if (!plan || !weights || !workspace) return XL_E_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) {
+        plan->error = "workspace must be 256-byte aligned";
+        return XL_E_ALIGN;
+    }
+    xl_status st = configure_once(plan);
+    if (st != XL_OK) return st;
+    const int nl = (int)plan->layers.size();
+    plan->scale_ptr.assign(nl, nullptr);
+    plan->shift_ptr.assign(nl, nullptr);
+    auto slot = [&](int s, const void **p) -> bool {
+        *p = nullptr;
+        if (s < 0) return true;
+        if (s >= nweights || !weights[s]) return false;
+        *p = weights[s];
+        return true;
+    };
+    for (int li = 0; li < nl; ++li) {
+        const xl_layer &L = plan->layers[li];
+        if (L.op != XL_CONV) continue;
+        const void *w, *sc, *sh;
+        if (!slot(L.w_slot, &w) || !w || !slot(L.scale_slot, &sc) || !slot(L.shift_slot, &sh)) {
+            plan->error = "layer " + std::to_string(li) + ": weight slot missing or NULL";
+            return XL_E_NULL;
+        }
+        plan->scale_ptr[li] = static_cast<const float *>(sc);
+        plan->shift_ptr[li] = static_cast<const float *>(sh);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    for (const xl::PackedFilter &p : plan->packed) {
+        const xl_layer &L = plan->layers[p.layer];
+        hipError_t e = xl::launch_pack_filter(static_cast<const float *>(weights[L.w_slot]),
+                                              reinterpret_cast<xl::f32x4 *>(ws + p.offset), L.cout, L.cin, L.k, p.mf,
+                                              p.nkg, p.nrt, s);
+        if (e != hipSuccess) {
+            plan->error = std::string("filter re-layout launch failed: ") + hipGetErrorString(e);
+            return XL_E_LAUNCH;
+        }
+    }
+    plan->prepared_ws = workspace;
+    return XL_OK;
+}
+
+xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors, void *workspace, void *stream,
+                 int fused)
+{
+    if (!plan || !tensors || !workspace) return XL_E_NULL;
+    if (plan->prepared_ws != workspace) return XL_E_STATE;
+    if (ntensors < (int)plan->shapes.size()) return XL_E_GRAPH;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    xl_plan *mp = const_cast<xl_plan *>(plan);       // only the error string is written
+    auto base = [&](int t) -> char * {
+        const xl::Storage &st = plan->storage[t];
+        if (st.external) return static_cast<char *>(const_cast<void *>(tensors[st.root]));
+        return ws + st.offset;
+    };
+    const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
+    for (const xl::Step &st : steps) {
+        char *x = base(st.x_id), *y = base(st.y_id);
+        if (!x || !y) {
+            mp->error = "a graph input or output pointer is NULL";
+            return XL_E_NULL;
+        }
+        if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) % 16) {
+            mp->error = "tensor pointers must be 16-byte aligned";
+            return XL_E_ALIGN;
+        }
+        hipError_t e = hipSuccess;
+        if (st.type == xl::STEP_BLOCK) {
+            xl::BlockParams p = st.bp;
+            p.x = reinterpret_cast<const float *>(x);
+            p.y = reinterpret_cast<float *>(y);
+            p.sc = nullptr;
+            if (st.sc_id >= 0) {
+                p.sc = reinterpret_cast<const float *>(base(st.sc_id));
+                if (!p.sc) return XL_E_NULL;
+            }
+            xl::ConvW *cw[3] = {&p.c1, &p.c2[0], &p.c2[1]};
+            for (int i = 0; i < 3; ++i) {
+                if (st.conv_layer[i] < 0) continue;
+                cw[i]->wp = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].offset);
+                cw[i]->scale = plan->scale_ptr[st.conv_layer[i]];
+                cw[i]->shift = plan->shift_ptr[st.conv_layer[i]];
+            }
+            e = xl::launch_block(st.variant, p, st.threads, (size_t)st.lds_bytes, s);
+        } else if (st.type == xl::STEP_MAXPOOL) {
+            const xl::Storage &ys = plan->storage[st.y_id];
+            e = xl::launch_maxpool(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N, st.C, st.H,
+                                   st.W, st.Ho, st.Wo, st.k, st.stride, st.pad, ys.ctot, ys.coff, s);
+        } else if (st.type == xl::STEP_ADD) {
+            char *b = base(st.b_id);
+            if (!b) return XL_E_NULL;
+            if (plan->storage[st.y_id].root != st.y_id) {
+                mp->error = "add writing into a concat slice is not supported";
+                return XL_E_UNSUPPORTED;
+            }
+            e = xl::launch_add(reinterpret_cast<const float *>(x), reinterpret_cast<const float *>(b),
+                               reinterpret_cast<float *>(y), st.count, st.relu, s);
+        } else if (st.type == xl::STEP_GAP) {
+            if (plan->storage[st.y_id].root != st.y_id) {
+                mp->error = "global pooling writing into a concat slice is not supported";
+                return XL_E_UNSUPPORTED;
+            }
+            e = xl::launch_gap(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N * st.C,
+                               st.H * st.W, s);
+        }
+        if (e != hipSuccess) {
+            mp->error = std::string("kernel launch failed: ") + hipGetErrorString(e);
+            return XL_E_LAUNCH;
+        }
+    }
+    return XL_OK;
+}
+
+}  // extern "C"

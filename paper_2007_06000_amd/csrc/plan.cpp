@@ -1,0 +1,803 @@
+// Host planner of libxl: graph validation, storage map, tile / halo selection
+// against the LDS budget (paper section 3.2), launch descriptors.
+#include "plan.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <set>
+
+namespace xl {
+
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Extent of the producing layer's output that `t` consecutive outputs of a
+// K-wide window at stride s depend on (paper section 3.2: every output pixel
+// depends on all inputs inside the filter window).
+int required_extent(int t, int k, int s) { return (t - 1) * s + k; }
+
+static bool is_prime(int v)
+{
+    if (v < 2) return false;
+    for (int d = 2; d * d <= v; ++d)
+        if (v % d == 0) return false;
+    return true;
+}
+
+// Paper section 3.2, tuner: complementary non-trivial factors of the output
+// size; a prime size is replaced by the next larger non-prime.
+int tuner_candidates(int out_size, int *tile, int *grid, int cap)
+{
+    if (out_size < 1) return 0;
+    int base = out_size;
+    while (base > 3 && is_prime(base)) ++base;
+    int n = 0;
+    for (int t = 2; t < base; ++t) {
+        if (base % t) continue;
+        if (n < cap && tile && grid) {
+            tile[n] = t;
+            grid[n] = base / t;
+        }
+        ++n;
+    }
+    return n;
+}
+
+// ----------------------------------------------------------------------------
+// Block description handed to the tile search
+// ----------------------------------------------------------------------------
+struct ConvSpec {
+    int layer = -1;
+    int cin = 0, cout = 0, k = 1, stride = 1, pad = 0, relu = 0;
+};
+
+struct BlockSpec {
+    int kind = KIND_SINGLE;
+    ConvSpec c1;
+    int n2 = 0;
+    ConvSpec c2[2];
+    int coff2[2] = {0, 0};
+    int pool_k = 0, pool_s = 1, pool_p = 0;
+    int N = 0, Cin = 0, H = 0, W = 0;
+    int H1 = 0, W1 = 0, Ho = 0, Wo = 0;
+    int relu_out = 0;
+    bool shortcut = false;
+    long long alg_bytes = 0;        // algorithmic HBM bytes of the fused block
+};
+
+struct Choice {
+    bool ok = false;
+    double cost = 0;
+    Variant v{};
+    int threads = 0, waves_r1 = 0, csplit = 1;
+    int th = 0, tw = 0, mh = 0, mw = 0, ih = 0, iw = 0;
+    int tiles_y = 0, tiles_x = 0;
+    int chunk_kg = 0, nchunks = 0;
+    int lds_bytes = 0, occ = 1;
+    long long flops_exec = 0;
+    bool lds_rejected = false;
+};
+
+static std::vector<int> tile_candidates(int extent)
+{
+    std::set<int> s;
+    for (int g = 1; g <= extent; ++g) s.insert(ceil_div(extent, g));
+    return std::vector<int>(s.begin(), s.end());
+}
+
+static double mfma_clk(int mf) { return mf == 32 ? 64.0 : 32.0; }
+
+// Model of one candidate.  Times in seconds on a nominal MI355X (2.4 GHz, 8 TB/s).
+static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
+{
+    const Variant &v = c.v;
+    const int nw = c.threads / 64;
+    const int mf1 = v.mf1;
+    const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
+    const int taps1 = b.c1.k * b.c1.k;
+    const int npx1 = c.mh * c.mw;
+    const int wg_rt = c.waves_r1 * v.nrt1;
+    const double wave1 = (double)v.nrt1 * v.npt1 * nkg1 * taps1 * 4 * mfma_clk(mf1);
+    double simd[4] = {0, 0, 0, 0};
+    for (int w = 0; w < nw; ++w) {
+        const int wr = w % c.waves_r1, wp = w / c.waves_r1;
+        const int rt0 = wr * v.nrt1, pt0 = wp * v.npt1;
+        const int rt_end = std::min(nrt1, wg_rt);
+        if (rt0 < rt_end && pt0 * mf1 < npx1) simd[w % 4] += wave1;
+    }
+    double t1 = *std::max_element(simd, simd + 4);
+    double t2 = 0;
+    long long flops2 = 0;
+    if (b.kind == KIND_FUSED2) {
+        const int mf2 = v.mf2, NRT2 = nrt2_of(mf2), NPT2 = npt2_of(mf2);
+        const int npx2 = c.th * c.tw;
+        const int nptg = ceil_div(ceil_div(npx2, mf2), NPT2);
+        std::vector<double> wl(nw, 0.0);
+        int item = 0;       // running item counter, same order as the kernel's round-robin
+        for (int ci = 0; ci < b.n2; ++ci) {
+            const ConvSpec &s = b.c2[ci];
+            const int nrt = ceil_div(s.cout, mf2), nkg = ceil_div(s.cin, kc_of(mf2));
+            const int per = ceil_div(nrt, c.csplit);
+            const int nrtg = ceil_div(std::min(per, nrt), NRT2);
+            const double ic = (double)NRT2 * NPT2 * nkg * s.k * s.k * 4 * mfma_clk(mf2);
+            for (int i = 0; i < nrtg * nptg; ++i, ++item) wl[item % nw] += ic;
+            flops2 += 2LL * nrtg * NRT2 * mf2 * nptg * NPT2 * mf2 * nkg * kc_of(mf2) * s.k * s.k;
+        }
+        double s2[4] = {0, 0, 0, 0};
+        for (int w = 0; w < nw; ++w) s2[w % 4] += wl[w];
+        t2 = *std::max_element(s2, s2 + 4);
+    } else if (b.kind == KIND_POOL) {
+        t2 = (double)ceil_div(b.c1.cout, 4) * c.th * c.tw * b.pool_k * b.pool_k * 8.0 / c.threads * 4;
+    }
+    const double ovh = 5000.0 + 800.0 * c.nchunks;
+    const double wg_clk = t1 + t2 + ovh;
+    const long long nwg = (long long)c.tiles_x * c.tiles_y * c.csplit * b.N;
+    const double rounds = std::ceil((double)nwg / pl.num_cus);
+    const double t_mfma = rounds * wg_clk * (c.occ >= 2 ? 1.0 : 1.2) / 2.4e9;
+
+    // memory side: algorithmic bytes at HBM speed plus per-workgroup cache-line traffic at L2 speed
+    auto lines = [](int w) { return (double)((w * 4 + 64 + 127) / 128) * 128.0; };
+    const double in_wg = (double)b.Cin * c.ih * lines(c.iw) * c.csplit;
+    const double out_ch = b.kind == KIND_FUSED2 ? (double)(b.c2[0].cout + (b.n2 > 1 ? b.c2[1].cout : 0)) : b.c1.cout;
+    const double out_wg = out_ch * c.th * lines(c.tw) * (b.shortcut ? 2.0 : 1.0);
+    const double t_mem = (double)b.alg_bytes / 8.0e12 + (in_wg + out_wg) * c.tiles_x * c.tiles_y * b.N / 24.0e12;
+    c.cost = std::max(t_mfma, t_mem) + 0.15 * std::min(t_mfma, t_mem);
+    // executed multiply-adds: stage 1 covers every row tile once per tile (per cout slice when fused),
+    // with pixels and channels rounded up to whole matrix-core tiles
+    const long long tiles = (long long)c.tiles_x * c.tiles_y * b.N;
+    const long long s1 = 2LL * nrt1 * mf1 * ceil_div(npx1, mf1) * mf1 * nkg1 * kc_of(mf1) * taps1;
+    c.flops_exec = tiles * (b.kind == KIND_SINGLE ? 1 : c.csplit) * s1 + tiles * c.csplit * flops2;
+}
+
+static Choice search(const BlockSpec &b, const xl_plan &pl)
+{
+    Choice best;
+    const std::vector<int> ths = tile_candidates(b.Ho), tws = tile_candidates(b.Wo);
+    std::vector<std::pair<int, int>> tiles;
+    if (pl.opts.force_tile_h > 0 && pl.opts.force_tile_w > 0) {
+        tiles.push_back({std::min(pl.opts.force_tile_h, b.Ho), std::min(pl.opts.force_tile_w, b.Wo)});
+    } else if (pl.opts.paper_tuner_only) {
+        int t[64], g[64];
+        const int n = std::min(64, tuner_candidates(std::max(b.Ho, b.Wo), t, g, 64));
+        for (int i = 0; i < n; ++i) tiles.push_back({std::min(t[i], b.Ho), std::min(t[i], b.Wo)});
+        if (tiles.empty()) tiles.push_back({b.Ho, b.Wo});
+    } else {
+        for (int th : ths)
+            for (int tw : tws) tiles.push_back({th, tw});
+    }
+    bool any_lds_reject = false;
+    for (const Variant &v : variants()) {
+        if (v.kind != b.kind || v.k1 != b.c1.k) continue;
+        const int mf1 = v.mf1;
+        const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
+        for (int threads : {256, 512}) {
+            const int nw = threads / 64;
+            for (int wr = 1; wr <= nw; wr *= 2) {
+                const int wg_rt = wr * v.nrt1;
+                if (b.kind != KIND_SINGLE && wg_rt < nrt1) continue;            // stage 1 must produce every channel
+                if (wr > 1 && (wr / 2) * v.nrt1 >= nrt1) continue;              // more row waves than row tiles
+                const int px_cap = (nw / wr) * v.npt1 * mf1;
+                for (auto [th, tw] : tiles) {
+                    Choice c;
+                    c.v = v;
+                    c.threads = threads;
+                    c.waves_r1 = wr;
+                    c.th = th;
+                    c.tw = tw;
+                    if (b.kind == KIND_SINGLE) {
+                        c.mh = th;
+                        c.mw = tw;
+                    } else if (b.kind == KIND_POOL) {
+                        c.mh = required_extent(th, b.pool_k, b.pool_s);
+                        c.mw = required_extent(tw, b.pool_k, b.pool_s);
+                    } else {
+                        int P = 0, ext = 0;
+                        for (int i = 0; i < b.n2; ++i) P = std::max(P, b.c2[i].pad);
+                        for (int i = 0; i < b.n2; ++i) ext = std::max(ext, b.c2[i].k - b.c2[i].pad);
+                        const int s2 = b.c2[0].stride;
+                        c.mh = (th - 1) * s2 + ext + P;
+                        c.mw = (tw - 1) * s2 + ext + P;
+                    }
+                    if (c.mh * c.mw > px_cap) continue;
+                    c.ih = required_extent(c.mh, b.c1.k, b.c1.stride);
+                    c.iw = required_extent(c.mw, b.c1.k, b.c1.stride);
+                    c.tiles_y = ceil_div(b.Ho, th);
+                    c.tiles_x = ceil_div(b.Wo, tw);
+                    // input chunk: as many K steps as one pass of the stager can hold
+                    const int per_kg = gps_of(mf1) * c.ih * c.iw;
+                    int chunk = std::min(nkg1, (STAGE_ITEMS * threads) / per_kg);
+                    if (chunk < 1) continue;
+                    c.nchunks = ceil_div(nkg1, chunk);
+                    chunk = ceil_div(nkg1, c.nchunks);                          // balance the chunks
+                    c.chunk_kg = chunk;
+                    const int in_bytes = chunk * per_kg * 16;
+                    int mid_bytes = 0;
+                    if (b.kind != KIND_SINGLE) mid_bytes = nrt1 * mf1 / 4 * c.mh * c.mw * 16;
+                    c.lds_bytes = mid_bytes + in_bytes;
+                    if (c.lds_bytes > pl.lds_budget) {
+                        any_lds_reject = true;
+                        continue;
+                    }
+                    c.occ = std::max(1, std::min({pl.lds_per_cu / std::max(c.lds_bytes, 1), 2048 / threads, 16 / nw}));
+                    std::vector<int> splits;
+                    if (b.kind == KIND_SINGLE) {
+                        splits.push_back(ceil_div(nrt1, wg_rt));
+                    } else if (b.kind == KIND_POOL) {
+                        splits.push_back(1);
+                    } else if (pl.opts.force_cout_split > 0) {
+                        splits.push_back(pl.opts.force_cout_split);
+                    } else {
+                        int min_nrt = 1 << 30;
+                        for (int i = 0; i < b.n2; ++i) min_nrt = std::min(min_nrt, ceil_div(b.c2[i].cout, v.mf2));
+                        for (int s = 1; s <= 8 && s <= min_nrt; s *= 2) splits.push_back(s);
+                    }
+                    for (int cs : splits) {
+                        c.csplit = cs;
+                        evaluate(b, pl, c);
+                        c.ok = true;
+                        if (!best.ok || c.cost < best.cost) best = c;
+                    }
+                }
+            }
+        }
+    }
+    if (!best.ok) best.lds_rejected = any_lds_reject;
+    return best;
+}
+
+// ----------------------------------------------------------------------------
+// Plan construction
+// ----------------------------------------------------------------------------
+struct Builder {
+    xl_plan &pl;
+    std::vector<int> producer;                    // tensor -> layer
+    std::vector<std::vector<int>> consumers;      // tensor -> layers
+    explicit Builder(xl_plan &p) : pl(p) {}
+
+    xl_status fail(xl_status st, const std::string &msg)
+    {
+        pl.error = msg;
+        return st;
+    }
+
+    xl_status validate()
+    {
+        const int nt = (int)pl.shapes.size(), nl = (int)pl.layers.size();
+        producer.assign(nt, -1);
+        consumers.assign(nt, {});
+        for (int t = 0; t < nt; ++t) {
+            const xl_shape &s = pl.shapes[t];
+            if (s.n < 0 || s.c <= 0 || s.h <= 0 || s.w <= 0) return fail(XL_E_SHAPE, "tensor " + std::to_string(t) + ": non-positive extent");
+        }
+        for (int li = 0; li < nl; ++li) {
+            const xl_layer &L = pl.layers[li];
+            const std::string at = "layer " + std::to_string(li) + ": ";
+            const int nin = (L.op == XL_ADD || L.op == XL_CONCAT) ? 2 : 1;
+            for (int i = 0; i < nin; ++i) {
+                if (L.in[i] < 0 || L.in[i] >= nt) return fail(XL_E_GRAPH, at + "input tensor id out of range");
+            }
+            if (L.out < 0 || L.out >= nt) return fail(XL_E_GRAPH, at + "output tensor id out of range");
+            if (producer[L.out] >= 0) return fail(XL_E_GRAPH, at + "tensor written twice");
+            for (int i = 0; i < nin; ++i)
+                if (L.in[i] == L.out) return fail(XL_E_GRAPH, at + "in-place layers are not supported");
+            const xl_shape &x = pl.shapes[L.in[0]], &y = pl.shapes[L.out];
+            if (x.n != y.n) return fail(XL_E_SHAPE, at + "batch differs between input and output");
+            switch (L.op) {
+            case XL_CONV: {
+                if (L.groups != 1) return fail(XL_E_UNSUPPORTED, at + "grouped convolution is not supported");
+                if (L.k != 1 && L.k != 3) return fail(XL_E_UNSUPPORTED, at + "filter size must be 1 or 3");
+                if (L.stride < 1 || L.pad < 0 || L.pad > L.k) return fail(XL_E_SHAPE, at + "bad stride/pad");
+                if (L.k == 1 && L.pad != 0) return fail(XL_E_UNSUPPORTED, at + "1x1 convolution with padding");
+                if (L.cin != x.c || L.cout != y.c) return fail(XL_E_SHAPE, at + "channel counts do not match tensors");
+                if (x.h + 2 * L.pad < L.k || x.w + 2 * L.pad < L.k) return fail(XL_E_SHAPE, at + "window larger than padded input");
+                if (y.h != (x.h + 2 * L.pad - L.k) / L.stride + 1 || y.w != (x.w + 2 * L.pad - L.k) / L.stride + 1)
+                    return fail(XL_E_SHAPE, at + "output extent does not follow floor((H+2p-k)/s)+1");
+                if (L.w_slot < 0) return fail(XL_E_GRAPH, at + "convolution without a filter slot");
+                break;
+            }
+            case XL_MAXPOOL:
+                if (L.k < 1 || L.stride < 1 || L.pad < 0 || L.pad >= L.k) return fail(XL_E_SHAPE, at + "bad pooling window");
+                if (x.c != y.c) return fail(XL_E_SHAPE, at + "pooling changes channels");
+                if (x.h + 2 * L.pad < L.k || x.w + 2 * L.pad < L.k) return fail(XL_E_SHAPE, at + "window larger than padded input");
+                if (y.h != (x.h + 2 * L.pad - L.k) / L.stride + 1 || y.w != (x.w + 2 * L.pad - L.k) / L.stride + 1)
+                    return fail(XL_E_SHAPE, at + "output extent does not follow floor((H+2p-k)/s)+1");
+                break;
+            case XL_GLOBAL_AVGPOOL:
+                if (x.c != y.c || y.h != 1 || y.w != 1) return fail(XL_E_SHAPE, at + "global pooling output must be [N,C,1,1]");
+                break;
+            case XL_ADD: {
+                const xl_shape &b = pl.shapes[L.in[1]];
+                if (memcmp(&x, &b, sizeof x) || memcmp(&x, &y, sizeof x)) return fail(XL_E_SHAPE, at + "add operands differ in shape");
+                break;
+            }
+            case XL_CONCAT: {
+                const xl_shape &b = pl.shapes[L.in[1]];
+                if (x.n != b.n || x.h != b.h || x.w != b.w || y.h != x.h || y.w != x.w || y.c != x.c + b.c)
+                    return fail(XL_E_SHAPE, at + "concat shapes do not line up");
+                break;
+            }
+            default:
+                return fail(XL_E_UNSUPPORTED, at + "unknown op");
+            }
+            for (int i = 0; i < nin; ++i) {
+                // inputs must already exist: a graph input (never produced) or produced by an earlier layer
+                bool produced_later = false;
+                for (int lj = li; lj < nl; ++lj)
+                    if (pl.layers[lj].out == L.in[i]) produced_later = true;
+                if (produced_later) return fail(XL_E_GRAPH, at + "layers are not in topological order");
+                consumers[L.in[i]].push_back(li);
+            }
+            producer[L.out] = li;
+        }
+        return XL_OK;
+    }
+
+    xl_status resolve_storage()
+    {
+        const int nt = (int)pl.shapes.size();
+        pl.storage.assign(nt, Storage{});
+        for (int t = 0; t < nt; ++t) pl.storage[t] = Storage{t, 0, pl.shapes[t].c, false, 0};
+        // a concat input becomes a channel slice of the concat output (walk in reverse so nesting resolves)
+        for (int li = (int)pl.layers.size() - 1; li >= 0; --li) {
+            const xl_layer &L = pl.layers[li];
+            if (L.op != XL_CONCAT) continue;
+            const Storage out = pl.storage[L.out];
+            int coff = out.coff;
+            for (int i = 0; i < 2; ++i) {
+                const int t = L.in[i];
+                if (producer[t] < 0) return fail(XL_E_UNSUPPORTED, "concat of a graph input");
+                if (consumers[t].size() != 1) return fail(XL_E_UNSUPPORTED, "a concat operand has another consumer");
+                if (L.in[0] == L.in[1]) return fail(XL_E_UNSUPPORTED, "concat of a tensor with itself");
+                pl.storage[t] = Storage{out.root, coff, out.ctot, false, 0};
+                coff += pl.shapes[t].c;
+            }
+        }
+        // consumers that read a channel slice are not supported (inputs are dense tensors)
+        for (size_t li = 0; li < pl.layers.size(); ++li) {
+            const xl_layer &L = pl.layers[li];
+            if (L.op == XL_CONCAT) continue;
+            const int nin = L.op == XL_ADD ? 2 : 1;
+            for (int i = 0; i < nin; ++i)
+                if (pl.storage[L.in[i]].root != L.in[i]) return fail(XL_E_UNSUPPORTED, "layer reads a concat operand directly");
+        }
+        return XL_OK;
+    }
+
+    void conv_spec(int li, ConvSpec &c) const
+    {
+        const xl_layer &L = pl.layers[li];
+        c.layer = li;
+        c.cin = L.cin;
+        c.cout = L.cout;
+        c.k = L.k;
+        c.stride = L.stride;
+        c.pad = L.pad;
+        c.relu = L.relu;
+    }
+
+    long long tensor_bytes(int t) const
+    {
+        const xl_shape &s = pl.shapes[t];
+        return 4LL * s.n * s.c * s.h * s.w;
+    }
+    long long tensor_elems(int t) const { return tensor_bytes(t) / 4; }
+    long long weight_bytes(int li) const
+    {
+        const xl_layer &L = pl.layers[li];
+        if (L.op != XL_CONV) return 0;
+        long long b = 4LL * L.cout * L.cin * L.k * L.k;
+        if (L.scale_slot >= 0) b += 4LL * L.cout;
+        if (L.shift_slot >= 0) b += 4LL * L.cout;
+        return b;
+    }
+    long long layer_flops(int li) const
+    {
+        const xl_layer &L = pl.layers[li];
+        if (L.op != XL_CONV) return 0;
+        const xl_shape &y = pl.shapes[L.out];
+        return 2LL * y.n * y.c * y.h * y.w * L.cin * L.k * L.k;
+    }
+    // HBM bytes / stored elements of one layer run on its own
+    void layer_traffic(int li, long long &bytes, long long &stores) const
+    {
+        const xl_layer &L = pl.layers[li];
+        bytes = stores = 0;
+        if (L.op == XL_CONCAT) return;
+        bytes = tensor_bytes(L.in[0]) + tensor_bytes(L.out) + weight_bytes(li);
+        if (L.op == XL_ADD) bytes += tensor_bytes(L.in[1]);
+        stores = tensor_elems(L.out);
+    }
+
+    int packed_index(int layer, int mf)
+    {
+        for (size_t i = 0; i < pl.packed.size(); ++i)
+            if (pl.packed[i].layer == layer && pl.packed[i].mf == mf) return (int)i;
+        const xl_layer &L = pl.layers[layer];
+        PackedFilter p;
+        p.layer = layer;
+        p.mf = mf;
+        p.nkg = ceil_div(L.cin, kc_of(mf));
+        p.nrt = ceil_div(L.cout, mf);
+        p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16;
+        p.offset = 0;
+        pl.packed.push_back(p);
+        return (int)pl.packed.size() - 1;
+    }
+
+    // Turn a searched choice into a launch step.
+    xl_status make_block_step(const BlockSpec &b, int x_id, int y_id, int sc_id, int coff1, Step &st, Choice &ch,
+                              const std::string &what)
+    {
+        ch = search(b, pl);
+        if (!ch.ok)
+            return fail(ch.lds_rejected ? XL_E_LDS_BUDGET : XL_E_UNSUPPORTED,
+                        what + (ch.lds_rejected ? ": no tile fits the LDS budget" : ": no kernel variant covers this block"));
+        st = Step{};
+        st.type = STEP_BLOCK;
+        st.variant = ch.v.id;
+        st.threads = ch.threads;
+        st.lds_bytes = ch.lds_bytes;
+        st.x_id = x_id;
+        st.y_id = y_id;
+        st.sc_id = sc_id;
+        st.conv_layer[0] = b.c1.layer;
+        st.conv_layer[1] = st.conv_layer[2] = -1;
+        st.packed[0] = packed_index(b.c1.layer, ch.v.mf1);
+        st.packed[1] = st.packed[2] = -1;
+        BlockParams &p = st.bp;
+        memset(&p, 0, sizeof p);
+        p.N = b.N;
+        p.Cin = b.Cin;
+        p.H = b.H;
+        p.W = b.W;
+        p.H1 = b.H1;
+        p.W1 = b.W1;
+        p.Ho = b.Ho;
+        p.Wo = b.Wo;
+        const Storage &ys = pl.storage[y_id];
+        p.Cy = ys.ctot;
+        p.Csc = sc_id >= 0 ? pl.shapes[sc_id].c : 0;
+        auto fill = [&](ConvW &w, const ConvSpec &s, int mf) {
+            w.wp = nullptr;
+            w.scale = w.shift = nullptr;
+            w.cin = s.cin;
+            w.cout = s.cout;
+            w.k = s.k;
+            w.stride = s.stride;
+            w.pad = s.pad;
+            w.relu = s.relu;
+            w.nkg = ceil_div(s.cin, kc_of(mf));
+            w.nrt = ceil_div(s.cout, mf);
+        };
+        fill(p.c1, b.c1, ch.v.mf1);
+        p.coff1 = ys.coff + coff1;
+        p.n2 = b.kind == KIND_FUSED2 ? b.n2 : 0;
+        int P2 = 0;
+        for (int i = 0; i < p.n2; ++i) {
+            fill(p.c2[i], b.c2[i], ch.v.mf2);
+            p.coff2[i] = ys.coff + b.coff2[i];
+            st.conv_layer[1 + i] = b.c2[i].layer;
+            st.packed[1 + i] = packed_index(b.c2[i].layer, ch.v.mf2);
+            P2 = std::max(P2, b.c2[i].pad);
+        }
+        p.s2 = b.kind == KIND_FUSED2 ? b.c2[0].stride : (b.kind == KIND_POOL ? b.pool_s : 1);
+        p.P2 = b.kind == KIND_FUSED2 ? P2 : (b.kind == KIND_POOL ? b.pool_p : 0);
+        p.pool_k = b.pool_k;
+        p.relu_out = b.relu_out;
+        p.th = ch.th;
+        p.tw = ch.tw;
+        p.mh = ch.mh;
+        p.mw = ch.mw;
+        p.ih = ch.ih;
+        p.iw = ch.iw;
+        p.tiles_x = ch.tiles_x;
+        p.tiles_y = ch.tiles_y;
+        p.csplit = ch.csplit;
+        p.nblocks = ch.tiles_x * ch.tiles_y * ch.csplit * b.N;
+        p.chunk_kg = ch.chunk_kg;
+        p.nchunks = ch.nchunks;
+        p.waves_r1 = ch.waves_r1;
+        p.mid_gstride = ch.mh * ch.mw * 4;
+        p.in_gstride = ch.ih * ch.iw * 4;
+        p.lds_in_off = b.kind == KIND_SINGLE ? 0 : p.c1.nrt * ch.v.mf1 / 4 * p.mid_gstride;
+        return XL_OK;
+    }
+
+    void fill_info(xl_group_info &gi, const BlockSpec &b, const Choice &ch) const
+    {
+        gi.tile_h = ch.th;
+        gi.tile_w = ch.tw;
+        gi.mid_h = b.kind == KIND_SINGLE ? 0 : ch.mh;
+        gi.mid_w = b.kind == KIND_SINGLE ? 0 : ch.mw;
+        gi.in_h = ch.ih;
+        gi.in_w = ch.iw;
+        gi.tiles_y = ch.tiles_y;
+        gi.tiles_x = ch.tiles_x;
+        gi.cout_split = ch.csplit;
+        gi.workgroups = ch.tiles_x * ch.tiles_y * ch.csplit * b.N;
+        gi.threads = ch.threads;
+        gi.lds_bytes = ch.lds_bytes;
+        gi.workgroups_per_cu = ch.occ;
+        gi.chunk_channels = ch.chunk_kg * kc_of(ch.v.mf1);
+        gi.flops_executed = ch.flops_exec;
+        if (b.kind == KIND_SINGLE) {
+            gi.redundancy = 1.0;
+        } else {
+            const double unique = (double)b.H1 * b.W1;
+            gi.redundancy = (double)ch.mh * ch.mw * ch.tiles_x * ch.tiles_y * ch.csplit / unique;
+        }
+    }
+
+    // ---- single layers (also the unfused path) ---------------------------------
+    xl_status single_step(int li, Step &st, xl_group_info *gi)
+    {
+        const xl_layer &L = pl.layers[li];
+        const xl_shape &x = pl.shapes[L.in[0]], &y = pl.shapes[L.out];
+        st = Step{};
+        st.x_id = L.in[0];
+        st.y_id = L.out;
+        st.sc_id = st.b_id = -1;
+        st.N = x.n;
+        st.C = x.c;
+        st.H = x.h;
+        st.W = x.w;
+        st.Ho = y.h;
+        st.Wo = y.w;
+        st.k = L.k;
+        st.stride = L.stride;
+        st.pad = L.pad;
+        st.relu = L.relu;
+        if (L.op == XL_CONV) {
+            BlockSpec b;
+            b.kind = KIND_SINGLE;
+            conv_spec(li, b.c1);
+            b.N = x.n;
+            b.Cin = x.c;
+            b.H = x.h;
+            b.W = x.w;
+            b.H1 = b.Ho = y.h;
+            b.W1 = b.Wo = y.w;
+            long long by, stv;
+            layer_traffic(li, by, stv);
+            b.alg_bytes = by;
+            Choice ch;
+            xl_status s = make_block_step(b, L.in[0], L.out, -1, 0, st, ch, "layer " + std::to_string(li));
+            if (s != XL_OK) return s;
+            if (gi) fill_info(*gi, b, ch);
+        } else if (L.op == XL_MAXPOOL) {
+            st.type = STEP_MAXPOOL;
+        } else if (L.op == XL_GLOBAL_AVGPOOL) {
+            st.type = STEP_GAP;
+        } else if (L.op == XL_ADD) {
+            st.type = STEP_ADD;
+            st.b_id = L.in[1];
+            st.count = tensor_elems(L.out);
+        }
+        return XL_OK;
+    }
+
+    bool only_consumers(int tensor, std::initializer_list<int> ls) const
+    {
+        for (int c : consumers[tensor])
+            if (std::find(ls.begin(), ls.end(), c) == ls.end()) return false;
+        return !consumers[tensor].empty();
+    }
+
+    // ---- fused blocks -------------------------------------------------------------
+    xl_status fused_group(const std::vector<int> &ids, int mode, GroupPlan &gp)
+    {
+        const std::string at = "block starting at layer " + std::to_string(ids[0]) + ": ";
+        for (size_t i = 1; i < ids.size(); ++i)
+            if (ids[i] <= ids[i - 1]) return fail(XL_E_GRAPH, at + "layer ids must ascend");
+        const xl_layer &L1 = pl.layers[ids[0]];
+        if (L1.op != XL_CONV) return fail(XL_E_UNSUPPORTED, at + "first layer of a fused block must be a convolution");
+        const int t_in = L1.in[0], t_mid = L1.out;
+        const xl_shape &xs = pl.shapes[t_in], &ms = pl.shapes[t_mid];
+        BlockSpec b;
+        conv_spec(ids[0], b.c1);
+        b.N = xs.n;
+        b.Cin = xs.c;
+        b.H = xs.h;
+        b.W = xs.w;
+        b.H1 = ms.h;
+        b.W1 = ms.w;
+        int y_id = -1, sc_id = -1;
+        if (mode == XL_STRAIGHT) {
+            if (ids.size() != 2) return fail(XL_E_UNSUPPORTED, at + "straight mode fuses exactly two layers");
+            const xl_layer &L2 = pl.layers[ids[1]];
+            if (L2.in[0] != t_mid) return fail(XL_E_GRAPH, at + "second layer does not read the first layer's output");
+            if (!only_consumers(t_mid, {ids[1]})) return fail(XL_E_UNSUPPORTED, at + "the intermediate has a consumer outside the block");
+            y_id = L2.out;
+            if (L2.op == XL_CONV) {
+                b.kind = KIND_FUSED2;
+                b.n2 = 1;
+                conv_spec(ids[1], b.c2[0]);
+            } else if (L2.op == XL_MAXPOOL) {
+                b.kind = KIND_POOL;
+                b.pool_k = L2.k;
+                b.pool_s = L2.stride;
+                b.pool_p = L2.pad;
+            } else {
+                return fail(XL_E_UNSUPPORTED, at + "straight mode: second layer must be a convolution or max pooling");
+            }
+        } else if (mode == XL_SPLIT) {
+            if (ids.size() != 3 && ids.size() != 4) return fail(XL_E_UNSUPPORTED, at + "split mode is conv -> {conv, conv} [-> concat]");
+            const xl_layer &A = pl.layers[ids[1]], &B = pl.layers[ids[2]];
+            if (A.op != XL_CONV || B.op != XL_CONV || A.in[0] != t_mid || B.in[0] != t_mid)
+                return fail(XL_E_GRAPH, at + "split mode: both siblings must be convolutions reading the first layer's output");
+            if (!only_consumers(t_mid, {ids[1], ids[2]})) return fail(XL_E_UNSUPPORTED, at + "the intermediate has a consumer outside the block");
+            if (A.stride != B.stride) return fail(XL_E_UNSUPPORTED, at + "split siblings must share a stride");
+            if (pl.shapes[A.out].h != pl.shapes[B.out].h || pl.shapes[A.out].w != pl.shapes[B.out].w)
+                return fail(XL_E_UNSUPPORTED, at + "split siblings must produce the same extent");
+            const Storage &sa = pl.storage[A.out], &sb = pl.storage[B.out];
+            if (sa.root != sb.root || sa.root == A.out) return fail(XL_E_UNSUPPORTED, at + "split siblings must feed one concat");
+            if (ids.size() == 4) {
+                const xl_layer &C = pl.layers[ids[3]];
+                if (C.op != XL_CONCAT || C.out != sa.root) return fail(XL_E_GRAPH, at + "fourth layer must be the siblings' concat");
+            }
+            b.kind = KIND_FUSED2;
+            b.n2 = 2;
+            // heavier sibling first so the round-robin over waves starts with the long items
+            const bool a_first = (long long)A.k * A.k * A.cout >= (long long)B.k * B.k * B.cout;
+            const int first = a_first ? ids[1] : ids[2], second = a_first ? ids[2] : ids[1];
+            conv_spec(first, b.c2[0]);
+            conv_spec(second, b.c2[1]);
+            b.coff2[0] = pl.storage[pl.layers[first].out].coff - pl.storage[sa.root].coff;
+            b.coff2[1] = pl.storage[pl.layers[second].out].coff - pl.storage[sa.root].coff;
+            y_id = sa.root;
+        } else if (mode == XL_MERGE) {
+            if (ids.size() != 3) return fail(XL_E_UNSUPPORTED, at + "merge mode is conv -> conv -> add(., block input)");
+            const xl_layer &L2 = pl.layers[ids[1]], &L3 = pl.layers[ids[2]];
+            if (L2.op != XL_CONV || L3.op != XL_ADD || L2.in[0] != t_mid) return fail(XL_E_GRAPH, at + "merge mode wiring");
+            const int other = L3.in[0] == L2.out ? L3.in[1] : (L3.in[1] == L2.out ? L3.in[0] : -1);
+            if (other < 0) return fail(XL_E_GRAPH, at + "the add does not read the second convolution");
+            if (!only_consumers(t_mid, {ids[1]}) || !only_consumers(L2.out, {ids[2]}))
+                return fail(XL_E_UNSUPPORTED, at + "an intermediate has a consumer outside the block");
+            if (pl.storage[other].root != other) return fail(XL_E_UNSUPPORTED, at + "shortcut is a concat operand");
+            b.kind = KIND_FUSED2;
+            b.n2 = 1;
+            conv_spec(ids[1], b.c2[0]);
+            b.relu_out = L3.relu;
+            b.shortcut = true;
+            sc_id = other;
+            y_id = L3.out;
+        } else {
+            return fail(XL_E_UNSUPPORTED, at + "unknown fusion mode");
+        }
+        if (b.kind == KIND_FUSED2) {
+            for (int i = 0; i < b.n2; ++i)
+                if (b.c2[i].cin != b.c1.cout) return fail(XL_E_SHAPE, at + "channel mismatch inside the block");
+        }
+        const xl_shape &ys = pl.shapes[y_id];
+        b.Ho = ys.h;
+        b.Wo = ys.w;
+
+        // algorithmic traffic (paper Table 2 counts stored elements the same way)
+        xl_group_info &gi = gp.info;
+        long long wbytes = 0;
+        for (int li : ids) {
+            long long by, stv;
+            layer_traffic(li, by, stv);
+            gi.bytes_unfused += by;
+            gi.stores_unfused += stv;
+            gi.flops += layer_flops(li);
+            wbytes += weight_bytes(li);
+        }
+        gi.bytes_fused = tensor_bytes(t_in) + wbytes + tensor_bytes(y_id);
+        if (sc_id >= 0 && sc_id != t_in) gi.bytes_fused += tensor_bytes(sc_id);
+        gi.stores_fused = tensor_elems(y_id);
+        b.alg_bytes = gi.bytes_fused;
+
+        Step st;
+        Choice ch;
+        xl_status s = make_block_step(b, t_in, y_id, sc_id, 0, st, ch, at.substr(0, at.size() - 2));
+        if (s != XL_OK) return s;
+        fill_info(gi, b, ch);
+        pl.fused_steps.push_back(st);
+        return XL_OK;
+    }
+
+    xl_status build(const xl_group *groups, int ngroups)
+    {
+        xl_status s = validate();
+        if (s != XL_OK) return s;
+        s = resolve_storage();
+        if (s != XL_OK) return s;
+        const int nl = (int)pl.layers.size();
+
+        // unfused path: one step per layer
+        for (int li = 0; li < nl; ++li) {
+            if (pl.layers[li].op == XL_CONCAT) continue;
+            Step st;
+            s = single_step(li, st, nullptr);
+            if (s != XL_OK) return s;
+            pl.unfused_steps.push_back(st);
+        }
+
+        // fused path: blocks in graph order, uncovered layers become singles
+        std::vector<int> owner(nl, -1);
+        for (int g = 0; g < ngroups; ++g) {
+            if (groups[g].nlayers < 1 || !groups[g].layer_ids) return fail(XL_E_GRAPH, "empty fusion block");
+            for (int i = 0; i < groups[g].nlayers; ++i) {
+                const int li = groups[g].layer_ids[i];
+                if (li < 0 || li >= nl) return fail(XL_E_GRAPH, "fusion block names a layer that does not exist");
+                if (owner[li] >= 0) return fail(XL_E_GRAPH, "layer " + std::to_string(li) + " is in two fusion blocks");
+                owner[li] = g;
+            }
+        }
+        std::vector<bool> done(std::max(ngroups, 1), false);
+        for (int li = 0; li < nl; ++li) {
+            const int g = owner[li];
+            if (g >= 0 && done[g]) continue;
+            GroupPlan gp;
+            memset(&gp.info, 0, sizeof gp.info);
+            if (g < 0 || groups[g].mode == XL_SINGLE) {
+                if (g >= 0 && groups[g].nlayers != 1) return fail(XL_E_UNSUPPORTED, "XL_SINGLE block with more than one layer");
+                if (g >= 0) done[g] = true;
+                gp.layers = {li};
+                gp.info.mode = XL_SINGLE;
+                gp.info.first_layer = li;
+                gp.info.nlayers = 1;
+                layer_traffic(li, gp.info.bytes_unfused, gp.info.stores_unfused);
+                gp.info.bytes_fused = gp.info.bytes_unfused;
+                gp.info.stores_fused = gp.info.stores_unfused;
+                gp.info.flops = gp.info.flops_executed = layer_flops(li);
+                gp.info.redundancy = 1.0;
+                if (pl.layers[li].op != XL_CONCAT) {
+                    Step st;
+                    s = single_step(li, st, &gp.info);
+                    if (s != XL_OK) return s;
+                    pl.fused_steps.push_back(st);
+                }
+            } else {
+                done[g] = true;
+                gp.layers.assign(groups[g].layer_ids, groups[g].layer_ids + groups[g].nlayers);
+                if (gp.layers[0] != li) return fail(XL_E_GRAPH, "fusion block layers must be listed in graph order");
+                gp.info.mode = groups[g].mode;
+                gp.info.first_layer = li;
+                gp.info.nlayers = groups[g].nlayers;
+                s = fused_group(gp.layers, groups[g].mode, gp);
+                if (s != XL_OK) return s;
+            }
+            pl.groups.push_back(gp);
+        }
+
+        // workspace: packed filters, then every tensor some layer both produces and consumes
+        size_t off = 0;
+        for (PackedFilter &p : pl.packed) {
+            p.offset = off;
+            off = align_up(off + p.bytes, 256);
+        }
+        for (size_t t = 0; t < pl.shapes.size(); ++t) {
+            Storage &st = pl.storage[t];
+            if (st.root != (int)t) continue;
+            // a root is external when nothing produces it (graph input) or nothing consumes it (graph output)
+            bool consumed = !consumers[t].empty();
+            bool produced = producer[t] >= 0;
+            st.external = !(consumed && produced);
+            if (!st.external) {
+                st.offset = off;
+                off = align_up(off + (size_t)tensor_bytes((int)t), 256);
+            }
+        }
+        for (size_t t = 0; t < pl.shapes.size(); ++t) {
+            Storage &st = pl.storage[t];
+            if (st.root != (int)t) {
+                st.external = pl.storage[st.root].external;
+                st.offset = pl.storage[st.root].offset;
+            }
+        }
+        pl.workspace_bytes = std::max<size_t>(off, 256);
+        return XL_OK;
+    }
+};
+
+xl_status build_plan(xl_plan &pl, const xl_group *groups, int ngroups)
+{
+    Builder b(pl);
+    return b.build(groups, ngroups);
+}
+
+}  // namespace xl

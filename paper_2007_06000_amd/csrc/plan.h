@@ -1,0 +1,73 @@
+// Host-side plan: validated graph, storage map, and one launch descriptor per
+// kernel for both execution modes.  Not part of the C ABI.
+#pragma once
+
+#include <string>
+#include <vector>
+
+#include "xl_internal.h"
+
+namespace xl {
+
+enum StepType { STEP_BLOCK = 0, STEP_MAXPOOL = 1, STEP_ADD = 2, STEP_GAP = 3 };
+
+// A filter re-laid out for one matrix-core tile size.
+struct PackedFilter {
+    int layer;
+    int mf;
+    int nkg, nrt;
+    size_t offset;      // bytes into the workspace
+    size_t bytes;
+};
+
+// Where a tensor lives: itself, or a channel slice of a concatenated tensor.
+struct Storage {
+    int root;           // tensor id that owns memory
+    int coff;           // channel offset inside root
+    int ctot;           // channels of root
+    bool external;      // root pointer comes from the caller's tensors[] array
+    size_t offset;      // bytes into the workspace when !external
+};
+
+struct Step {
+    int type;
+    // STEP_BLOCK
+    int variant;
+    BlockParams bp;     // pointers filled at run time
+    int threads;
+    int lds_bytes;
+    int conv_layer[3];  // layer index of c1, c2[0], c2[1] (-1 unused)
+    int packed[3];      // index into Plan::packed
+    // tensors
+    int x_id, y_id, sc_id;
+    // element-wise steps
+    int N, C, H, W, Ho, Wo, k, stride, pad, relu;
+    int b_id;
+    long long count;
+};
+
+struct GroupPlan {
+    xl_group_info info;
+    std::vector<int> layers;
+};
+
+}  // namespace xl
+
+struct xl_plan {
+    std::vector<xl_layer> layers;
+    std::vector<xl_shape> shapes;
+    std::vector<xl::GroupPlan> groups;
+    std::vector<xl::Storage> storage;
+    std::vector<xl::PackedFilter> packed;
+    std::vector<xl::Step> fused_steps, unfused_steps;
+    size_t workspace_bytes = 0;
+    int device = -1;
+    int lds_budget = 160 * 1024;
+    int lds_per_cu = 160 * 1024;
+    int num_cus = 256;
+    xl_options opts{};
+    // bound by xl_prepare
+    const void *prepared_ws = nullptr;
+    std::vector<const float *> scale_ptr, shift_ptr;   // per layer
+    std::string error;
+};

@@ -1,0 +1,136 @@
+// Internal descriptors shared by the host planner and the HIP kernels of libxl.
+// Not part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "xl.h"
+
+namespace xl {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Matrix-core tile geometry.  MF = 32 uses V_MFMA_F32_32X32X2_F32 (one K step of
+// the packed filter covers 8 input channels: 2 lane halves x 4 components),
+// MF = 16 uses V_MFMA_F32_16X16X4_F32 (16 channels: 4 lane quarters x 4).
+constexpr int kc_of(int mf) { return mf == 32 ? 8 : 16; }       // channels per K step
+constexpr int gps_of(int mf) { return mf == 32 ? 2 : 4; }       // 4-channel groups per K step
+
+// One convolution as the kernels see it.
+struct ConvW {
+    const f32x4 *wp;        // filter re-laid out as [K step][tap][row tile][lane] of float4
+    const float *scale;     // per output channel, or nullptr (= 1)
+    const float *shift;     // per output channel, or nullptr (= 0)
+    int cin, cout;
+    int k, stride, pad;
+    int relu;
+    int nkg;                // K steps  = ceil(cin / kc)
+    int nrt;                // row tiles = ceil(cout / MF)
+};
+
+enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2 };
+
+// Kernel argument of every convolution-stage kernel.
+//   KIND_SINGLE: stage 1 writes its result to global memory (one layer, the
+//                unfused primitive).
+//   KIND_FUSED2: stage 1 writes a halo-extended tile of the intermediate into
+//                LDS; stage 2 runs one or two sibling convolutions from that
+//                tile (straight / split), optionally adding a shortcut tensor
+//                in the epilogue (merge).
+//   KIND_POOL:   stage 1 as above; stage 2 is a max pooling from the LDS tile.
+struct BlockParams {
+    const float *x;         // block input  [N, Cin, H, W]
+    float *y;               // tensor the block writes into [N, Cy, Ho, Wo]
+    const float *sc;        // shortcut [N, Csc, Ho, Wo] or nullptr
+    int N, Cin, H, W;
+    int H1, W1;             // extent of the stage-1 output (the intermediate)
+    int Ho, Wo;             // extent of the block output
+    int Cy, Csc;
+    ConvW c1;
+    int coff1;              // channel offset into y when stage 1 writes global
+    int n2;                 // stage-2 convolutions (0 for SINGLE / POOL)
+    ConvW c2[2];
+    int coff2[2];
+    int s2;                 // stride shared by the stage-2 windows
+    int P2;                 // halo of the LDS tile on the top/left = largest stage-2 pad
+    int pool_k;             // KIND_POOL: window size (stride s2, pad P2)
+    int relu_out;           // applied after the shortcut add (merge)
+    int th, tw;             // output tile of the block
+    int mh, mw;             // stage-1 output tile (incl. halo) -- equals th, tw for SINGLE
+    int ih, iw;             // input tile (incl. halo)
+    int tiles_x, tiles_y, csplit;
+    int nblocks;            // logical workgroups = N * csplit * tiles_y * tiles_x
+    int chunk_kg, nchunks;  // K steps staged per pipeline step; number of steps
+    int waves_r1;           // stage-1 waves along the row-tile (Cout) direction
+    int mid_gstride;        // floats between consecutive 4-channel groups of the LDS tile
+    int in_gstride;         // same for the staged input
+    int lds_in_off;         // float offset of the input staging area in LDS
+};
+
+// A compiled kernel variant.
+struct Variant {
+    int id;
+    int kind;
+    int mf1, k1, nrt1, npt1;    // stage 1: matrix-core tile, filter size, tiles per wave
+    int mf2;                    // stage 2 matrix-core tile (0 when unused)
+};
+
+// id, kind, MF1, K1, NRT1, NPT1, MF2
+#define XL_VARIANT_LIST(X)                       \
+    X(0, KIND_SINGLE, 32, 1, 1, 1, 0)            \
+    X(1, KIND_SINGLE, 32, 1, 2, 1, 0)            \
+    X(2, KIND_SINGLE, 32, 1, 2, 2, 0)            \
+    X(3, KIND_SINGLE, 32, 3, 1, 1, 0)            \
+    X(4, KIND_SINGLE, 32, 3, 2, 1, 0)            \
+    X(5, KIND_SINGLE, 32, 3, 2, 2, 0)            \
+    X(6, KIND_SINGLE, 16, 1, 1, 1, 0)            \
+    X(7, KIND_SINGLE, 16, 1, 1, 2, 0)            \
+    X(8, KIND_SINGLE, 16, 1, 3, 2, 0)            \
+    X(9, KIND_SINGLE, 16, 3, 1, 1, 0)            \
+    X(10, KIND_SINGLE, 16, 3, 1, 2, 0)           \
+    X(11, KIND_FUSED2, 32, 1, 1, 1, 32)          \
+    X(12, KIND_FUSED2, 32, 1, 2, 1, 32)          \
+    X(13, KIND_FUSED2, 32, 3, 1, 1, 32)          \
+    X(14, KIND_FUSED2, 32, 3, 2, 1, 32)          \
+    X(15, KIND_FUSED2, 16, 1, 1, 1, 32)          \
+    X(16, KIND_FUSED2, 16, 1, 1, 2, 32)          \
+    X(17, KIND_FUSED2, 16, 1, 1, 3, 32)          \
+    X(18, KIND_FUSED2, 16, 1, 3, 2, 32)          \
+    X(19, KIND_FUSED2, 16, 3, 1, 1, 16)          \
+    X(20, KIND_FUSED2, 16, 3, 1, 3, 16)          \
+    X(21, KIND_FUSED2, 16, 1, 1, 1, 16)          \
+    X(22, KIND_FUSED2, 32, 1, 1, 1, 16)          \
+    X(23, KIND_FUSED2, 32, 3, 1, 1, 16)          \
+    X(24, KIND_FUSED2, 16, 3, 1, 1, 32)          \
+    X(25, KIND_POOL, 32, 1, 1, 1, 0)             \
+    X(26, KIND_POOL, 32, 1, 2, 1, 0)             \
+    X(27, KIND_POOL, 32, 3, 1, 1, 0)             \
+    X(28, KIND_POOL, 32, 3, 2, 1, 0)             \
+    X(29, KIND_POOL, 16, 1, 1, 1, 0)             \
+    X(30, KIND_POOL, 16, 3, 1, 1, 0)
+
+const std::vector<Variant> &variants();
+
+// Stage-2 tiles per wave are fixed by the matrix-core tile.
+constexpr int nrt2_of(int mf2) { return mf2 == 32 ? 2 : 1; }
+constexpr int npt2_of(int mf2) { return mf2 == 32 ? 1 : 2; }
+
+constexpr int STAGE_ITEMS = 4;      // float4 items each thread stages per pipeline step
+constexpr int MAX_THREADS = 512;
+
+// ---- launchers (kernels.hip) -------------------------------------------------
+hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t lds_bytes, hipStream_t s);
+hipError_t configure_kernels(int max_lds_bytes);      // raises the dynamic-LDS cap of every variant
+
+hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf,
+                              int nkg, int nrt, hipStream_t s);
+hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, int Ho, int Wo,
+                          int k, int stride, int pad, int Cy, int coff, hipStream_t s);
+hipError_t launch_add(const float *a, const float *b, float *y, long long count, int relu, hipStream_t s);
+hipError_t launch_gap(const float *x, float *y, int NC, int HW, hipStream_t s);
+
+}  // namespace xl

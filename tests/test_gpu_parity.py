@@ -1,0 +1,116 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.  Bar: |g - o| <= 1e-4 + 1e-4 |o| in fp32
+for every element, fused and unfused."""
+import numpy as np
+import pytest
+
+import xl_workloads as W
+from oracle import xlo
+
+pytestmark = pytest.mark.gpu
+
+ATOL = 1e-4
+RTOL = 1e-4
+
+
+def check(got: np.ndarray, ref: np.ndarray, what: str):
+    assert got.shape == ref.shape, what
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    bound = ATOL + RTOL * np.abs(ref.astype(np.float64))
+    bad = err > bound
+    if bad.any():
+        idx = np.unravel_index(np.argmax(err - bound), err.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements off; worst at {idx}: "
+                             f"gpu {got[idx]!r} oracle {ref[idx]!r}")
+    return float(err.max())
+
+
+def run_both(wl, **options):
+    from paper_2007_06000_amd.session import Session
+    x, params = W.make_tensors(wl)
+    ref = xlo.forward(wl, x, params)
+    s = Session(wl, x, params, **options)
+    out = {}
+    for fused in (True, False):
+        print(f"[case] {wl.name} shapes={wl.shapes[0]} fused={fused} opts={options}", flush=True)
+        got = s.output(fused)
+        out[fused] = got
+        check(got, ref, f"{wl.name} fused={fused}")
+    return out, ref, s
+
+
+SMALL = [
+    (1, {}),
+    (1, {"hw": 13}),
+    (2, {"n": 2, "hw": 20}),
+    (2, {"n": 1, "hw": 15, "c": 24}),
+    (3, {"n": 2, "hw": 19}),
+    (3, {"n": 1, "hw": 11, "cin": 40, "s": 16, "e": 64}),
+    (3, {"n": 1, "hw": 13, "cin": 72, "s": 48, "e": 96}),
+    (4, {"n": 2, "hw": 17, "c": 32}),
+    (4, {"n": 1, "hw": 9, "c": 64}),
+    (5, {"n": 2, "hw": 63, "classes": 40}),
+]
+
+
+@pytest.mark.parametrize("cfg,kw", SMALL)
+def test_small_and_ragged(cfg, kw):
+    run_both(W.config(cfg, **kw))
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_block_configs_full_size(cfg):
+    run_both(W.config(cfg))
+
+
+def test_config5_full_size():
+    run_both(W.config(5))
+
+
+@pytest.mark.parametrize("cfg,kw,tile", [
+    (1, {}, (4, 4)), (1, {}, (16, 16)), (1, {}, (5, 7)),
+    (3, {"n": 2, "hw": 19}, (19, 19)), (3, {"n": 2, "hw": 19}, (5, 8)), (3, {"n": 2, "hw": 19}, (3, 19)),
+    (4, {"n": 2, "hw": 17, "c": 32}, (6, 6)), (4, {"n": 2, "hw": 17, "c": 32}, (14, 14)),
+    (2, {"n": 2, "hw": 20}, (2, 10)), (2, {"n": 2, "hw": 20}, (5, 5)),
+])
+def test_tile_choice_does_not_change_the_result(cfg, kw, tile):
+    """Fusion order / tile size must not change the math (beyond fp32 reassociation)."""
+    run_both(W.config(cfg, **kw), force_tile_h=tile[0], force_tile_w=tile[1])
+
+
+@pytest.mark.parametrize("split", [1, 2, 4])
+def test_cout_split(split):
+    run_both(W.config(3, n=1, hw=13, cin=64, s=32, e=128), force_cout_split=split)
+
+
+def test_prezeroed_intermediate_border():
+    """Bias +1 everywhere: halo positions outside the image must reach layer 2 as 0, not relu(bias)."""
+    wl = W.config(1)
+    x, params = W.make_tensors(wl)
+    for p in params.values():
+        p["shift"] = np.ones_like(p["shift"])
+    ref = xlo.forward(wl, x, params)
+    from paper_2007_06000_amd.session import Session
+    for tile in ((16, 16), (4, 8), (7, 5)):
+        s = Session(wl, x, params, force_tile_h=tile[0], force_tile_w=tile[1])
+        check(s.output(True), ref, f"border tile={tile}")
+
+
+def test_batch_independence_bitwise():
+    wl3 = W.config(3, n=3, hw=19)
+    x, params = W.make_tensors(wl3)
+    from paper_2007_06000_amd.session import Session
+    full = Session(wl3, x, params, force_tile_h=7, force_tile_w=7).output(True)
+    wl1 = W.config(3, n=1, hw=19)
+    for n in range(3):
+        one = Session(wl1, x[n:n + 1], params, force_tile_h=7, force_tile_w=7).output(True)
+        np.testing.assert_array_equal(one[0], full[n])
+
+
+def test_single_convs():
+    for wl in (W.single_conv(2, 3, 31, 31, 64, 3, stride=2, pad=0),
+               W.single_conv(1, 512, 13, 13, 1000, 1),
+               W.single_conv(2, 20, 9, 11, 24, 3, stride=1, pad=1, bias=False, bn=True, relu=False),
+               W.single_conv(1, 8, 7, 7, 8, 1, relu=False)):
+        run_both(wl)
