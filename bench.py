@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-block hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of the workload:
+every fusion block of the network executed once by `xl_run(fused=1)`, inputs
+already resident in HBM.  The same step with `fused=0` (one kernel per layer,
+intermediates through HBM) is timed beside it for the speedup.  Prints ONE JSON
+line.  Inputs are seeded synthetic tensors (xl_workloads.py).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 matrix cores
+CACHE_BYTES = 512 << 20        # rotate buffers over more than L2 + Infinity Cache (256 MB)
+
+
+def time_steps(fn, steps, warmup, torch):
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        fn(warmup + i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3
+    return ev0.elapsed_time(ev1) / steps, wall / steps
+
+
+def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True):
+    wl = W.config(cfg)
+    x, params = W.make_tensors(wl)
+    s = Session(wl, x, params)
+    in_bytes = x.nbytes
+    out_bytes = int(np.prod(wl.shapes[wl.output_id])) * 4
+    sets = 1
+    if cold:
+        sets = max(1, min(64, -(-CACHE_BYTES // (in_bytes + out_bytes))))
+    xs = [s.x] + [s.x.clone() for _ in range(sets - 1)]
+    ys = [s.y] + [torch.empty_like(s.y) for _ in range(sets - 1)]
+
+    def fused(i):
+        s.run(True, xs[i % sets], ys[i % sets])
+
+    def unfused(i):
+        s.run(False, xs[i % sets], ys[i % sets])
+
+    ms_f, wall_f = time_steps(fused, steps, warmup, torch)
+    ms_u, _ = time_steps(unfused, steps, warmup, torch)
+    groups = [s.plan.query(g) for g in range(s.plan.num_groups)]
+    bytes_f = sum(g["bytes_fused"] for g in groups)
+    bytes_u = sum(g["bytes_unfused"] for g in groups)
+    flops = sum(g["flops"] for g in groups)
+    res = {
+        "workload": wl.name, "batch": wl.batch,
+        "ms_fused": ms_f, "ms_unfused": ms_u, "wall_ms_fused": wall_f,
+        "images_per_s": wl.batch / ms_f * 1e3,
+        "speedup_vs_unfused": ms_u / ms_f,
+        "launches_fused": s.plan.num_launches(True), "launches_unfused": s.plan.num_launches(False),
+        "alg_bytes_fused": bytes_f, "alg_bytes_unfused": bytes_u, "flops": flops,
+        "hbm_gbs_alg": bytes_f / ms_f / 1e6,
+        "hbm_frac": bytes_f / ms_f / 1e6 / HBM_PEAK_GBS,
+        "tflops": flops / ms_f / 1e9,
+        "mfma_frac": flops / ms_f / 1e9 / MFMA_FP32_PEAK_TFLOPS,
+        "buffer_sets": sets,
+    }
+    return res, s, wl, x, params
+
+
+def cpu_baseline(cfg, W, np, budget_s=15.0):
+    """The oracle as it stands, on a bounded sample of the same workload."""
+    from oracle import xlo
+    wl_full = W.config(cfg)
+    n = wl_full.batch
+    sample_n = max(1, min(n, 8))
+    wl = W.config(cfg, n=sample_n)
+    x, params = W.make_tensors(wl)
+    xlo.forward(wl, x[:1].repeat(sample_n, axis=0) if False else x, params)        # warm caches / build lib
+    reps, t_total = 0, 0.0
+    while t_total < budget_s and reps < 50:
+        t0 = time.perf_counter()
+        xlo.forward(wl, x, params)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    return {"value": sample_n * reps / t_total, "unit": "images/s", "cores": xlo.num_threads(), "kind": "oracle",
+            "sample": f"{reps} passes of {wl.name} at batch {sample_n} (full batch {n}), {t_total:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=5, help="BASELINE config number 1..5 timed as the headline")
+    ap.add_argument("--all", action="store_true", help="also time the other configs (reported under 'blocks')")
+    ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident) instead of rotating")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (images are independent; batch sharding needs no "
+              "collective); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import xl_workloads as W
+    from paper_2007_06000_amd.session import Session
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libxl has no CPU path", file=sys.stderr)
+        sys.exit(2)
+
+    res, s, wl, x, params = bench_workload(args.workload, args.steps, args.warmup, torch, np, W, Session,
+                                           cold=not args.warm)
+
+    # roofline of the dominant kernel of the headline workload
+    roof = dominant_kernel_roofline(args.workload, res, args, torch, np, W, Session)
+
+    out = {
+        "metric": "images/sec per fused block + HBM GB/s vs roofline; speedup over unfused",
+        "value": res["images_per_s"], "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_fused"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "launches_per_step": res["launches_fused"],
+                   "buffers": "rotating (cold)" if not args.warm else "single set (warm)"},
+        "speedup_vs_unfused": res["speedup_vs_unfused"],
+        "ms_per_step_unfused": res["ms_unfused"],
+        "hbm_gbs_algorithmic": res["hbm_gbs_alg"],
+        "fp32_tflops": res["tflops"], "fp32_mfma_frac": res["mfma_frac"],
+        "paper_context": {"fused_structures_speedup": 2.02, "squeezenet_speedup": 1.57,
+                          "hardware": "TITAN Xp / Tesla P4, vs cuDNN v7"},
+        "roofline": roof,
+    }
+    if args.all:
+        blocks = []
+        for c in (1, 2, 3, 4, 5):
+            if c == args.workload:
+                blocks.append({k: res[k] for k in res})
+                continue
+            r, *_ = bench_workload(c, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm)
+            blocks.append(r)
+        out["blocks"] = blocks
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload, W, np)
+    print(json.dumps(out))
+
+
+def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
+    """Time the block that dominates the headline workload on its own (one
+    kernel launch per step) and price it against the roofline that bounds it."""
+    wl_full = W.config(cfg)
+    x, params = W.make_tensors(wl_full)
+    s = Session(wl_full, x, params)
+    groups = [s.plan.query(g) for g in range(s.plan.num_groups)]
+    if len(groups) == 1:
+        g = groups[0]
+        ms = res["ms_fused"]
+        name = wl_full.name
+    else:
+        # the block with the largest roofline time, rebuilt as a workload of its own
+        def t_roof(g):
+            return max(g["flops"] / (MFMA_FP32_PEAK_TFLOPS * 1e12), g["bytes_fused"] / (HBM_PEAK_GBS * 1e9))
+        gi = max(range(len(groups)), key=lambda i: t_roof(groups[i]))
+        g = groups[gi]
+        sub = W.subgraph(wl_full, gi)
+        xs, ps = W.make_tensors(sub)
+        ss = Session(sub, xs, ps)
+        in_b, out_b = xs.nbytes, int(np.prod(sub.shapes[sub.output_id])) * 4
+        sets = max(1, min(64, -(-CACHE_BYTES // (in_b + out_b)))) if not args.warm else 1
+        bx = [ss.x] + [ss.x.clone() for _ in range(sets - 1)]
+        by = [ss.y] + [torch.empty_like(ss.y) for _ in range(sets - 1)]
+        ms, _ = time_steps(lambda i: ss.run(True, bx[i % sets], by[i % sets]), args.steps, args.warmup, torch)
+        g = ss.plan.query(0)
+        name = sub.name
+    t_m = g["flops"] / (MFMA_FP32_PEAK_TFLOPS * 1e12)
+    t_h = g["bytes_fused"] / (HBM_PEAK_GBS * 1e9)
+    if t_m >= t_h:
+        ach = g["flops"] / ms / 1e9
+        return {"bound": "mfma", "achieved": ach, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_FP32_PEAK_TFLOPS, "traffic": None, "kernel": name, "kernel_ms": ms,
+                "flops_per_launch": g["flops"], "bytes_per_launch": g["bytes_fused"]}
+    ach = g["bytes_fused"] / ms / 1e6
+    return {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "traffic": None, "kernel": name, "kernel_ms": ms,
+            "flops_per_launch": g["flops"], "bytes_per_launch": g["bytes_fused"]}
+
+
+if __name__ == "__main__":
+    main()

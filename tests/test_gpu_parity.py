@@ -70,7 +70,7 @@ def test_config5_full_size():
 
 @pytest.mark.parametrize("cfg,kw,tile", [
     (1, {}, (4, 4)), (1, {}, (16, 16)), (1, {}, (5, 7)),
-    (3, {"n": 2, "hw": 19}, (19, 19)), (3, {"n": 2, "hw": 19}, (5, 8)), (3, {"n": 2, "hw": 19}, (3, 19)),
+    (3, {"n": 2, "hw": 19}, (13, 19)), (3, {"n": 2, "hw": 19}, (5, 8)), (3, {"n": 2, "hw": 19}, (3, 19)),
     (4, {"n": 2, "hw": 17, "c": 32}, (6, 6)), (4, {"n": 2, "hw": 17, "c": 32}, (14, 14)),
     (2, {"n": 2, "hw": 20}, (2, 10)), (2, {"n": 2, "hw": 20}, (5, 5)),
 ])

@@ -311,3 +311,36 @@ def count_flops(wl: Workload) -> int:
             n, c, h, w = wl.shapes[L.out]
             total += 2 * n * c * h * w * (L.cin // L.groups) * L.k * L.k
     return total
+
+
+def subgraph(wl: Workload, group_index: int) -> Workload:
+    """The layers of one fusion block as a workload of their own (same shapes,
+    tensor ids renumbered).  Its input stands for the activations that reach the
+    block inside the network: post-ReLU, so non-negative N(0,1) draws, unless the
+    block starts at the network input."""
+    g = wl.groups[group_index]
+    ids = list(g.layers)
+    produced = {wl.layers[i].out for i in ids}
+    ext_in = []
+    for i in ids:
+        for t in wl.layers[i].inputs:
+            if t not in produced and t not in ext_in:
+                ext_in.append(t)
+    assert len(ext_in) == 1, "a block has one external input"
+    consumed = {t for i in ids for t in wl.layers[i].inputs}
+    outs = [wl.layers[i].out for i in ids if wl.layers[i].out not in consumed]
+    assert len(outs) == 1, "a block has one external output"
+    remap = {ext_in[0]: 0}
+    shapes = [wl.shapes[ext_in[0]]]
+    layers = []
+    for i in ids:
+        L = wl.layers[i]
+        remap[L.out] = len(shapes)
+        shapes.append(wl.shapes[L.out])
+        layers.append(Layer(L.op, tuple(remap[t] for t in L.inputs), remap[L.out], cin=L.cin, cout=L.cout, k=L.k,
+                            stride=L.stride, pad=L.pad, groups=L.groups, bias=L.bias, bn=L.bn, relu=L.relu,
+                            name=L.name))
+    dist = wl.input_dist if ext_in[0] == wl.input_id else "relu_normal"
+    name = f"{wl.name}.block{group_index}.{wl.layers[ids[0]].name}"
+    return Workload(name, shapes, layers, [Group(g.mode, tuple(range(len(ids))))], 0, remap[outs[0]], dist,
+                    wl.seed + 100 + group_index)
