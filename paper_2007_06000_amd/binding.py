@@ -11,7 +11,7 @@ import os
 from typing import Dict, List, Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libxl.so")
+LIB_PATH = os.environ.get("XL_LIBRARY_PATH") or os.path.join(_HERE, "libxl.so")
 
 XL_OK = 0
 XL_E_NULL, XL_E_SHAPE, XL_E_UNSUPPORTED, XL_E_LDS_BUDGET = -1, -2, -3, -4

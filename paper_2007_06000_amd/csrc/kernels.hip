@@ -26,6 +26,20 @@
 
 namespace xl {
 
+// Development aid: per-workgroup phase timestamps (only in builds with -DXL_PHASE_TIMING).
+#ifdef XL_PHASE_TIMING
+__device__ unsigned long long g_phase[16 * 8192];
+#define XL_PHASE(L, i)                                                        \
+    do {                                                                      \
+        if (threadIdx.x == 0 && (L) < 8192) {                                 \
+            g_phase[(L) * 16 + (i)] = clock64();                              \
+            g_phase[(L) * 16 + 8 + (i)] = wall_clock64();                     \
+        }                                                                     \
+    } while (0)
+#else
+#define XL_PHASE(L, i) do { } while (0)
+#endif
+
 // ----------------------------------------------------------------------------
 // matrix-core wrappers
 // ----------------------------------------------------------------------------
@@ -86,25 +100,40 @@ __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT]
 {
     typedef MM<MF> M;
     constexpr int T = KS * KS;
+    constexpr int D = 2;        // software pipeline: operands are fetched D (K step, tap) pairs ahead
     const int kstep = T * nrt * 64;
-#pragma unroll(KS == 1 ? 2 : 1)
+    f32x4 a[D + 1][NRT], b[D + 1][NPT];
+    auto fetch = [&](f32x4(&ra)[NRT], f32x4(&rb)[NPT], int kg, int t) {
+        const int u = t / KS, v = t % KS;
+        const f32x4 *w = wpl + kg * kstep + t * nrt * 64;
+#pragma unroll
+        for (int r = 0; r < NRT; ++r) ra[r] = w[rtc[r] * 64];
+        const float *s = src + kg * (M::GPS * gstride) + (u * src_w + v) * 4;
+#pragma unroll
+        for (int p = 0; p < NPT; ++p) rb[p] = *(const f32x4 *)(s + off[p]);
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d / T < nkg) fetch(a[d], b[d], d / T, d % T);
     for (int kg = 0; kg < nkg; ++kg) {
-        const float *s = src + kg * (M::GPS * gstride);
-        const f32x4 *w = wpl + kg * kstep;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const int u = t / KS, v = t % KS;
-            f32x4 a[NRT], b[NPT];
-#pragma unroll
-            for (int r = 0; r < NRT; ++r) a[r] = w[(t * nrt + rtc[r]) * 64];
-#pragma unroll
-            for (int p = 0; p < NPT; ++p) b[p] = *(const f32x4 *)(s + off[p] + (u * src_w + v) * 4);
+            if (kg + (t + D) / T < nkg) fetch(a[D], b[D], kg + (t + D) / T, (t + D) % T);
+            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of this step's matrix ops
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int r = 0; r < NRT; ++r)
 #pragma unroll
-                    for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(a[r][j], b[p][j], acc[r][p]);
+                    for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(a[0][r][j], b[0][p][j], acc[r][p]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+#pragma unroll
+                for (int r = 0; r < NRT; ++r) a[d][r] = a[d + 1][r];
+#pragma unroll
+                for (int p = 0; p < NPT; ++p) b[d][p] = b[d + 1][p];
+            }
         }
     }
 }
@@ -343,7 +372,9 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
     for (int r = 0; r < NRT1; ++r)
 #pragma unroll
         for (int p = 0; p < NPT1; ++p) zero_acc(acc[r][p]);
+    XL_PHASE(L, 0);
     stage1<MF1, K1, NRT1, NPT1>(acc, P, ximg, iy0, ix0, rt0, rt_end1, pt0, npx1, lin);
+    XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {
         store_global<MF1, NRT1, NPT1>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mw, rt0, rt_end1, pt0, npx1, P.sc,
@@ -354,6 +385,7 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
         store_mid<MF1, NRT1, NPT1>(acc, P, mid, my0, mx0, rt0, rt_end1, pt0, npx1,
                                    KIND == KIND_POOL ? -FLT_MAX : 0.f);
         __syncthreads();
+        XL_PHASE(L, 2);
 
         if constexpr (KIND == KIND_POOL) {
             // ---- S4/S5: max pooling from the LDS tile; one float4 (4 channels of one pixel) per item
@@ -402,6 +434,8 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
                 item -= nitems;
             }
         }
+        __syncthreads();
+        XL_PHASE(L, 3);
     }
 }
 
@@ -586,3 +620,10 @@ hipError_t launch_gap(const float *x, float *y, int NC, int HW, hipStream_t s)
 }
 
 }  // namespace xl
+
+#ifdef XL_PHASE_TIMING
+extern "C" int xl_debug_read_phases(unsigned long long *host, int count)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(xl::g_phase), sizeof(unsigned long long) * count);
+}
+#endif
