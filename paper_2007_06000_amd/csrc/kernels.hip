@@ -87,38 +87,35 @@ __device__ __forceinline__ int logical_block()
 }
 
 // ----------------------------------------------------------------------------
-// K loop: acc[r][p] += filter(row tile r) x pixels(pixel tile p) over `nkg` K steps
+// K loop over one staged chunk: acc[r][p] += filter(row tile r) x pixels(pixel tile p).
+// Both operands come from LDS: `wsrc` holds the filter chunk as
+// [K step][tap][row tile of this workgroup][lane] float4, `bsrc` the pixels as
+// [channel group][row][col][4].  Operands of the next (K step, tap) are fetched
+// while the matrix cores work on the current one.
 // ----------------------------------------------------------------------------
 template <int MF, int KS, int NRT, int NPT>
 __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT],
-                                           const float *src,             // LDS, group 0 of this K range
-                                           const int (&off)[NPT],        // per-lane float offset of tap (0,0)
-                                           int src_w, int gstride,
-                                           const f32x4 *__restrict__ wpl,   // packed filter + lane, K step 0
-                                           const int (&rtc)[NRT],        // row tile of each r (clamped)
-                                           int nrt, int nkg)
+                                           const float *bsrc, const int (&off)[NPT], int src_w, int gstride,
+                                           const float *wsrc, const int (&rloc)[NRT], int wg_rt, int nkg)
 {
     typedef MM<MF> M;
     constexpr int T = KS * KS;
-    constexpr int D = 2;        // software pipeline: operands are fetched D (K step, tap) pairs ahead
-    const int kstep = T * nrt * 64;
-    f32x4 a[D + 1][NRT], b[D + 1][NPT];
+    const int lane = threadIdx.x & 63;
+    f32x4 a[2][NRT], b[2][NPT];
     auto fetch = [&](f32x4(&ra)[NRT], f32x4(&rb)[NPT], int kg, int t) {
         const int u = t / KS, v = t % KS;
-        const f32x4 *w = wpl + kg * kstep + t * nrt * 64;
+        const float *w = wsrc + ((kg * T + t) * wg_rt * 64 + lane) * 4;
 #pragma unroll
-        for (int r = 0; r < NRT; ++r) ra[r] = w[rtc[r] * 64];
-        const float *s = src + kg * (M::GPS * gstride) + (u * src_w + v) * 4;
+        for (int r = 0; r < NRT; ++r) ra[r] = *(const f32x4 *)(w + rloc[r] * 256);
+        const float *s = bsrc + kg * (M::GPS * gstride) + (u * src_w + v) * 4;
 #pragma unroll
         for (int p = 0; p < NPT; ++p) rb[p] = *(const f32x4 *)(s + off[p]);
     };
-#pragma unroll
-    for (int d = 0; d < D; ++d)
-        if (d / T < nkg) fetch(a[d], b[d], d / T, d % T);
+    fetch(a[0], b[0], 0, 0);
     for (int kg = 0; kg < nkg; ++kg) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            if (kg + (t + D) / T < nkg) fetch(a[D], b[D], kg + (t + D) / T, (t + D) % T);
+            if (t + 1 < T || kg + 1 < nkg) fetch(a[1], b[1], kg + (t + 1) / T, (t + 1) % T);
             __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of this step's matrix ops
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -128,104 +125,159 @@ __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT]
                     for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(a[0][r][j], b[0][p][j], acc[r][p]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
+            for (int r = 0; r < NRT; ++r) a[0][r] = a[1][r];
 #pragma unroll
-                for (int r = 0; r < NRT; ++r) a[d][r] = a[d + 1][r];
-#pragma unroll
-                for (int p = 0; p < NPT; ++p) b[d][p] = b[d + 1][p];
-            }
+            for (int p = 0; p < NPT; ++p) b[0][p] = b[1][p];
         }
     }
 }
 
 // ----------------------------------------------------------------------------
-// Stage 1: stream the input tile through LDS and accumulate layer 1
+// One pass of a convolution over the tiles this workgroup holds in registers.
+// The filter (and, for STAGE_X, the halo-extended input tile) is streamed
+// through two LDS buffers in chunks of `chunk_kg` K steps: while the matrix
+// cores work on chunk i from one buffer, the global loads of chunk i+1 are in
+// flight into registers and are written to the other buffer afterwards; one
+// workgroup barrier per chunk.
 // ----------------------------------------------------------------------------
-template <int MF, int KS, int NRT, int NPT>
-__device__ __forceinline__ void stage1(typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
-                                       const float *__restrict__ ximg, int iy0, int ix0,
-                                       int rt0, int rt_end, int pt0, int npx, float *lin)
+struct PassGeom {
+    int rt_base;        // first row tile staged by this workgroup
+    int wg_rt;          // row tiles staged (= row waves x NRT)
+    int wr;             // this wave's position along the row-tile direction
+    int chunk_kg;       // K steps per chunk
+    int src_w, gstride; // pixel source: tile width, floats per channel group
+    int w_off;          // float offset of the filter chunk inside a buffer
+    int buf_stride;     // floats between the two buffers
+    bool active;        // this wave owns at least one real tile
+};
+
+template <int MF, int KS, int NRT, int NPT, bool STAGE_X>
+__device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P, const ConvW &c,
+                                          const PassGeom &g, const float *bsrc, const int (&off)[NPT], float *buf,
+                                          const float *__restrict__ ximg, int iy0, int ix0)
 {
     typedef MM<MF> M;
+    constexpr int T = KS * KS;
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const int lane = tid & 63;
-    const int sub = lane / MF, col = lane % MF;
-    const int s1 = P.c1.stride;
-    const int HW = P.H * P.W;
+    int rloc[NRT];
+#pragma unroll
+    for (int r = 0; r < NRT; ++r) rloc[r] = g.wr * NRT + r;
 
-    int off[NPT];
+    // ---- filter stager: a straight copy of [K step][tap][wg_rt][64] float4 out of the packed filter
+    const int wrow = g.wg_rt * 64;
+    const int w_items = g.chunk_kg * T * wrow;
+    const int nkt = c.nkg * T;
+    int w_src[STAGE_W], w_kt[STAGE_W];
 #pragma unroll
-    for (int p = 0; p < NPT; ++p) {
-        int pidx = (pt0 + p) * MF + col;
-        pidx = pidx < npx ? pidx : 0;
-        const int my = pidx / P.mw, mx = pidx - my * P.mw;
-        off[p] = ((my * s1) * P.iw + mx * s1) * 4 + sub * P.in_gstride;
-    }
-    int rtc[NRT];
-#pragma unroll
-    for (int r = 0; r < NRT; ++r) rtc[r] = min(rt0 + r, P.c1.nrt - 1);
-    const bool active = rt0 < rt_end && pt0 * MF < npx;
-
-    // what this thread stages per chunk: STAGE_ITEMS float4 items (4 channels of one pixel)
-    const int plane = P.ih * P.iw;
-    const int nitems = P.chunk_kg * M::GPS * plane;
-    int pixoff[STAGE_ITEMS], chan[STAGE_ITEMS];
-#pragma unroll
-    for (int i = 0; i < STAGE_ITEMS; ++i) {
+    for (int i = 0; i < STAGE_W; ++i) {
         const int item = i * nthreads + tid;
-        const int g = item / plane, rem = item - g * plane;
-        const int r = rem / P.iw, c = rem - r * P.iw;
-        const int gy = iy0 + r, gx = ix0 + c;
-        const bool in = item < nitems && gy >= 0 && gy < P.H && gx >= 0 && gx < P.W;
-        pixoff[i] = in ? gy * P.W + gx : -1;
-        chan[i] = g * 4;
+        const int kt = item / wrow, rem = item - kt * wrow;
+        const bool ok = item < w_items && g.rt_base + (rem >> 6) < c.nrt;
+        w_kt[i] = ok ? kt : (1 << 28);
+        w_src[i] = kt * c.nrt * 64 + g.rt_base * 64 + rem;
     }
-    f32x4 st[STAGE_ITEMS];
-    auto load_chunk = [&](int c0) {
+    f32x4 wst[STAGE_W];
+    auto load_w = [&](int kg0) {
+        const f32x4 *base = c.wp + (size_t)kg0 * T * c.nrt * 64;
 #pragma unroll
-        for (int i = 0; i < STAGE_ITEMS; ++i) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int cc = c0 + chan[i] + j;
-                st[i][j] = (pixoff[i] >= 0 && cc < P.Cin) ? ximg[(size_t)cc * HW + pixoff[i]] : 0.f;
-            }
+        for (int i = 0; i < STAGE_W; ++i) {
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            wst[i] = (kg0 * T + w_kt[i] < nkt) ? base[w_src[i]] : z;
         }
     };
-    auto store_chunk = [&]() {
+    auto store_w = [&](float *dst) {
+#pragma unroll
+        for (int i = 0; i < STAGE_W; ++i) {
+            const int item = i * nthreads + tid;
+            if (item < w_items) *(f32x4 *)(dst + item * 4) = wst[i];
+        }
+    };
+
+    // ---- input stager: float4 items = 4 channels of one pixel, NCHW -> [group][row][col][4]
+    const int HW = P.H * P.W;
+    const int plane = P.ih * P.iw;
+    const int x_items = STAGE_X ? g.chunk_kg * M::GPS * plane : 0;
+    int pixoff[STAGE_X ? STAGE_ITEMS : 1], chan[STAGE_X ? STAGE_ITEMS : 1];
+    f32x4 xst[STAGE_X ? STAGE_ITEMS : 1];
+    if constexpr (STAGE_X) {
 #pragma unroll
         for (int i = 0; i < STAGE_ITEMS; ++i) {
             const int item = i * nthreads + tid;
-            if (item < nitems) *(f32x4 *)(lin + item * 4) = st[i];
+            const int gr = item / plane, rem = item - gr * plane;
+            const int r = rem / P.iw, cc = rem - r * P.iw;
+            const int gy = iy0 + r, gx = ix0 + cc;
+            const bool in = item < x_items && gy >= 0 && gy < P.H && gx >= 0 && gx < P.W;
+            pixoff[i] = in ? gy * P.W + gx : -1;
+            chan[i] = gr * 4;
+        }
+    }
+    auto load_x = [&](int c0) {
+        if constexpr (STAGE_X) {
+#pragma unroll
+            for (int i = 0; i < STAGE_ITEMS; ++i) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int cc = c0 + chan[i] + j;
+                    xst[i][j] = (pixoff[i] >= 0 && cc < P.Cin) ? ximg[(size_t)cc * HW + pixoff[i]] : 0.f;
+                }
+            }
+        }
+    };
+    auto store_x = [&](float *dst) {
+        if constexpr (STAGE_X) {
+#pragma unroll
+            for (int i = 0; i < STAGE_ITEMS; ++i) {
+                const int item = i * nthreads + tid;
+                if (item < x_items) *(f32x4 *)(dst + item * 4) = xst[i];
+            }
         }
     };
 
-    const f32x4 *wpl = P.c1.wp + lane;
-    const int chunk_c = P.chunk_kg * M::KC;
-    const int kstep = KS * KS * P.c1.nrt * 64;
-    load_chunk(0);
-    store_chunk();
+    const int nchunks = (c.nkg + g.chunk_kg - 1) / g.chunk_kg;
+    load_x(0);
+    load_w(0);
+    store_x(buf);
+    store_w(buf + g.w_off);
     __syncthreads();
-    for (int ch = 0; ch < P.nchunks; ++ch) {
-        const bool more = ch + 1 < P.nchunks;
-        if (more) load_chunk((ch + 1) * chunk_c);
-        const int kg0 = ch * P.chunk_kg;
-        const int nkg = min(P.chunk_kg, P.c1.nkg - kg0);
-        if (active) conv_accum<MF, KS, NRT, NPT>(acc, lin, off, P.iw, P.in_gstride, wpl + kg0 * kstep, rtc, P.c1.nrt, nkg);
-        __syncthreads();
+    for (int ch = 0; ch < nchunks; ++ch) {
+        float *cur = buf + (ch & 1) * g.buf_stride;
+        float *nxt = buf + ((ch + 1) & 1) * g.buf_stride;
+        const bool more = ch + 1 < nchunks;
+        const int kg0 = ch * g.chunk_kg;
         if (more) {
-            store_chunk();
-            __syncthreads();
+            load_x((kg0 + g.chunk_kg) * M::KC);
+            load_w(kg0 + g.chunk_kg);
         }
+        const int nkg = min(g.chunk_kg, c.nkg - kg0);
+        if (g.active) {
+            const float *bs = STAGE_X ? cur : bsrc + kg0 * (M::GPS * g.gstride);
+            conv_accum<MF, KS, NRT, NPT>(acc, bs, off, g.src_w, g.gstride, cur + g.w_off, rloc, g.wg_rt, nkg);
+        }
+        if (more) {
+            store_x(nxt);
+            store_w(nxt + g.w_off);
+        }
+        __syncthreads();
     }
 }
 
-__device__ __forceinline__ float ld_or(const float *p, int i, float dflt) { return p ? p[i] : dflt; }
+// per-channel scale / shift of 4 consecutive output channels (clamped: callers mask co >= cout)
+__device__ __forceinline__ void load_affine(const ConvW &c, int cb, float (&sc)[4], float (&sh)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int co = min(cb + i, c.cout - 1);
+        sc[i] = c.scale ? c.scale[co] : 1.f;
+        sh[i] = c.shift ? c.shift[co] : 0.f;
+    }
+}
 
 // Epilogue of a tile to global memory (S5), also used by the single-layer kernel.
+// Pixel p of the tile sits at (p / vw, p % vw); columns >= tw of the virtual row are padding.
 template <int MF, int NRT, int NPT>
 __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
-                                             const ConvW &c, int coff, int n, int oy0, int ox0, int tw,
-                                             int rt0, int rt_end, int pt0, int npx, const float *sc, int relu_out)
+                                             const ConvW &c, int coff, int n, int oy0, int ox0, int th, int tw, int vw,
+                                             int rt0, int rt_end, int pt0, const float *sc, int relu_out)
 {
     typedef MM<MF> M;
     const int lane = threadIdx.x & 63;
@@ -234,28 +286,49 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
-        const int oy = pidx / tw, ox = pidx - oy * tw;
+        const int oy = pidx / vw, ox = pidx - oy * vw;
         const int gy = oy0 + oy, gx = ox0 + ox;
-        const bool pv = pidx < npx && gy < P.Ho && gx < P.Wo;
-        const size_t pix = (size_t)gy * P.Wo + gx;
+        const bool pv = oy < th && ox < tw && gy < P.Ho && gx < P.Wo;
+        const size_t pix = pv ? (size_t)gy * P.Wo + gx : 0;
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
             if (rt0 + r >= rt_end) continue;
+            float res[M::NQ][4];
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
+                float a[4], b[4];
+                load_affine(c, cb, a, b);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int co = cb + i;
-                    if (pv && co < c.cout) {
-                        float v = acc[r][p][q * 4 + i] * ld_or(c.scale, co, 1.f) + ld_or(c.shift, co, 0.f);
-                        if (c.relu) v = fmaxf(v, 0.f);
-                        if (sc) v += sc[((size_t)n * P.Csc + co) * plane + pix];
-                        if (relu_out) v = fmaxf(v, 0.f);
-                        P.y[((size_t)n * P.Cy + coff + co) * plane + pix] = v;
-                    }
+                    float v = acc[r][p][q * 4 + i] * a[i] + b[i];
+                    if (c.relu) v = fmaxf(v, 0.f);
+                    res[q][i] = v;
                 }
             }
+            if (sc) {       // shortcut add: all loads of this tile issued together, invalid lanes read element 0
+                float sv[M::NQ][4];
+#pragma unroll
+                for (int q = 0; q < M::NQ; ++q)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int co = min((rt0 + r) * MF + M::quad_row(q, sub) + i, c.cout - 1);
+                        sv[q][i] = sc[((size_t)n * P.Csc + co) * plane + pix];
+                    }
+#pragma unroll
+                for (int q = 0; q < M::NQ; ++q)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) res[q][i] += sv[q][i];
+            }
+#pragma unroll
+            for (int q = 0; q < M::NQ; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int co = (rt0 + r) * MF + M::quad_row(q, sub) + i;
+                    float v = res[q][i];
+                    if (relu_out) v = fmaxf(v, 0.f);
+                    if (pv && co < c.cout) P.y[((size_t)n * P.Cy + coff + co) * plane + pix] = v;
+                }
         }
     }
 }
@@ -274,7 +347,6 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
-        if (pidx >= npx) continue;
         const int my = pidx / P.mw, mx = pidx - my * P.mw;
         const int gy = my0 + my, gx = mx0 + mx;
         const bool inside = gy >= 0 && gy < P.H1 && gx >= 0 && gx < P.W1;
@@ -284,51 +356,21 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
+                float a[4], b[4];
+                load_affine(c, cb, a, b);
                 f32x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int co = cb + i;
-                    float z = 0.f;
-                    if (co < c.cout) {
-                        z = acc[r][p][q * 4 + i] * ld_or(c.scale, co, 1.f) + ld_or(c.shift, co, 0.f);
-                        if (c.relu) z = fmaxf(z, 0.f);
-                        if (!inside) z = fill;
-                    }
+                    float z = acc[r][p][q * 4 + i] * a[i] + b[i];
+                    if (c.relu) z = fmaxf(z, 0.f);
+                    if (!inside) z = fill;
+                    if (cb + i >= c.cout) z = 0.f;
                     v[i] = z;
                 }
-                *(f32x4 *)(mid + (cb >> 2) * P.mid_gstride + pidx * 4) = v;
+                if (pidx < npx) *(f32x4 *)(mid + (cb >> 2) * P.mid_gstride + pidx * 4) = v;
             }
         }
     }
-}
-
-// Stage 2: one (row-tile group, pixel-tile group) item of a convolution read from the LDS tile.
-template <int MF, int KS, int NRT, int NPT>
-__device__ __forceinline__ void stage2_item(const BlockParams &P, const ConvW &c, int coff, const float *mid, int n,
-                                            int oy0, int ox0, int rt0, int rt_end, int pt0, int npx)
-{
-    typedef MM<MF> M;
-    const int lane = threadIdx.x & 63;
-    const int sub = lane / MF, col = lane % MF;
-    const int d = P.P2 - c.pad;
-    int off[NPT];
-#pragma unroll
-    for (int p = 0; p < NPT; ++p) {
-        int pidx = (pt0 + p) * MF + col;
-        pidx = pidx < npx ? pidx : 0;
-        const int oy = pidx / P.tw, ox = pidx - oy * P.tw;
-        off[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * P.mid_gstride;
-    }
-    int rtc[NRT];
-#pragma unroll
-    for (int r = 0; r < NRT; ++r) rtc[r] = min(rt0 + r, c.nrt - 1);
-    typename M::Acc acc[NRT][NPT];
-#pragma unroll
-    for (int r = 0; r < NRT; ++r)
-#pragma unroll
-        for (int p = 0; p < NPT; ++p) zero_acc(acc[r][p]);
-    conv_accum<MF, KS, NRT, NPT>(acc, mid, off, P.mw, P.mid_gstride, c.wp + lane, rtc, c.nrt, c.nkg);
-    store_global<MF, NRT, NPT>(acc, P, c, coff, n, oy0, ox0, P.tw, rt0, rt_end, pt0, npx, P.sc, P.relu_out);
 }
 
 // ----------------------------------------------------------------------------
@@ -347,6 +389,7 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
     const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
     const int oy0 = ty * P.th, ox0 = tx * P.tw;
 
+    const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     typedef MM<MF1> M1;
 
@@ -357,27 +400,44 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
     const int ix0 = mx0 * P.c1.stride - P.c1.pad;
 
     float *mid = lds;
-    float *lin = lds + P.lds_in_off;
+    float *buf = lds + P.lds_buf_off;
     const float *ximg = P.x + (size_t)n * P.Cin * P.H * P.W;
 
     // ---- S1: layer 1 over the (halo-extended) tile
     const int npx1 = P.mh * P.mw;
-    const int wr = wave % P.waves_r1, wp = wave / P.waves_r1;
-    const int wg_rt = P.waves_r1 * NRT1;                         // row tiles one workgroup covers in stage 1
-    const int rt_base = (KIND == KIND_SINGLE) ? cs * wg_rt : 0;
-    const int rt_end1 = min(P.c1.nrt, rt_base + wg_rt);
-    const int rt0 = rt_base + wr * NRT1, pt0 = wp * NPT1;
+    PassGeom g1;
+    g1.wg_rt = P.waves_r1 * NRT1;
+    g1.rt_base = (KIND == KIND_SINGLE) ? cs * g1.wg_rt : 0;
+    g1.wr = wave % P.waves_r1;
+    g1.chunk_kg = P.chunk_kg;
+    g1.src_w = P.iw;
+    g1.gstride = P.in_gstride;
+    g1.w_off = P.w_off1;
+    g1.buf_stride = P.buf_stride;
+    const int rt_end1 = min(P.c1.nrt, g1.rt_base + g1.wg_rt);
+    const int rt0 = g1.rt_base + g1.wr * NRT1, pt0 = (wave / P.waves_r1) * NPT1;
+    g1.active = rt0 < rt_end1 && pt0 * MF1 < npx1;
     typename M1::Acc acc[NRT1][NPT1];
+    int off1[NPT1];
+    {
+        const int sub = lane / MF1, col = lane % MF1;
 #pragma unroll
-    for (int r = 0; r < NRT1; ++r)
+        for (int p = 0; p < NPT1; ++p) {
+            zero_acc(acc[0][p]);
 #pragma unroll
-        for (int p = 0; p < NPT1; ++p) zero_acc(acc[r][p]);
+            for (int r = 1; r < NRT1; ++r) acc[r][p] = acc[0][p];
+            int pidx = (pt0 + p) * MF1 + col;
+            pidx = pidx < npx1 ? pidx : 0;
+            const int my = pidx / P.mw, mx = pidx - my * P.mw;
+            off1[p] = ((my * P.c1.stride) * P.iw + mx * P.c1.stride) * 4 + sub * P.in_gstride;
+        }
+    }
     XL_PHASE(L, 0);
-    stage1<MF1, K1, NRT1, NPT1>(acc, P, ximg, iy0, ix0, rt0, rt_end1, pt0, npx1, lin);
+    conv_pass<MF1, K1, NRT1, NPT1, true>(acc, P, P.c1, g1, nullptr, off1, buf, ximg, iy0, ix0);
     XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {
-        store_global<MF1, NRT1, NPT1>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mw, rt0, rt_end1, pt0, npx1, P.sc,
+        store_global<MF1, NRT1, NPT1>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mh, P.mw, P.mw, rt0, rt_end1, pt0, P.sc,
                                       P.relu_out);
         return;
     } else {
@@ -393,11 +453,11 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
             const int npo = P.th * P.tw;
             const size_t plane = (size_t)P.Ho * P.Wo;
             for (int it = threadIdx.x; it < ngroups * npo; it += blockDim.x) {
-                const int g = it / npo, pidx = it - g * npo;
+                const int gq = it / npo, pidx = it - gq * npo;
                 const int oy = pidx / P.tw, ox = pidx - oy * P.tw;
                 const int gy = oy0 + oy, gx = ox0 + ox;
                 if (gy >= P.Ho || gx >= P.Wo) continue;
-                const float *s = mid + g * P.mid_gstride + ((oy * P.s2) * P.mw + ox * P.s2) * 4;
+                const float *s = mid + gq * P.mid_gstride + ((oy * P.s2) * P.mw + ox * P.s2) * 4;
                 f32x4 m = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
                 for (int u = 0; u < P.pool_k; ++u)
                     for (int v = 0; v < P.pool_k; ++v) {
@@ -407,34 +467,59 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
                     }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int co = g * 4 + j;
+                    const int co = gq * 4 + j;
                     if (co < P.c1.cout) P.y[((size_t)n * P.Cy + P.coff1 + co) * plane + (size_t)gy * P.Wo + gx] = m[j];
                 }
             }
         } else {
-            // ---- S4/S5: sibling convolutions from the LDS tile, heavier one first
+            // ---- S4/S5: sibling convolutions from the LDS tile, heavier one first.  Every pass covers
+            // (row waves x NRT2) row tiles by (pixel waves x NPT2) pixel tiles; all waves stream the
+            // same filter chunks.
             constexpr int NRT2 = nrt2_of(MF2), NPT2 = npt2_of(MF2);
-            const int npx2 = P.th * P.tw;
-            const int nptg = ((npx2 + MF2 - 1) / MF2 + NPT2 - 1) / NPT2;
-            int item = wave;
+            typedef MM<MF2> M2;
+            const int sub = lane / MF2, col = lane % MF2;
+            const int npt2 = (P.th * P.vw2 + MF2 - 1) / MF2;
+            const int wr2 = wave % P.waves_r2, wp2 = wave / P.waves_r2;
+            const int wg_pt2 = (nwaves / P.waves_r2) * NPT2;
             for (int ci = 0; ci < P.n2; ++ci) {
                 const ConvW &c = P.c2[ci];
                 const int per = (c.nrt + P.csplit - 1) / P.csplit;           // row tiles of this workgroup
                 const int rtb = cs * per, rte = min(c.nrt, rtb + per);
-                const int nrtg = rte > rtb ? (rte - rtb + NRT2 - 1) / NRT2 : 0;
-                const int nitems = nrtg * nptg;
-                for (; item < nitems; item += nwaves) {
-                    const int rtg = item / nptg, ptg = item - rtg * nptg;
-                    const int r0 = rtb + rtg * NRT2, p0 = ptg * NPT2;
-                    if (c.k == 3)
-                        stage2_item<MF2, 3, NRT2, NPT2>(P, c, P.coff2[ci], mid, n, oy0, ox0, r0, rte, p0, npx2);
-                    else
-                        stage2_item<MF2, 1, NRT2, NPT2>(P, c, P.coff2[ci], mid, n, oy0, ox0, r0, rte, p0, npx2);
+                PassGeom g2;
+                g2.wg_rt = P.waves_r2 * NRT2;
+                g2.wr = wr2;
+                g2.chunk_kg = P.chunk_kg2[ci];
+                g2.src_w = P.mw;
+                g2.gstride = P.mid_gstride;
+                g2.w_off = 0;
+                g2.buf_stride = P.buf_stride;
+                const int d = P.P2 - c.pad;
+                for (int rp = rtb; rp < rte; rp += g2.wg_rt) {
+                    for (int pp = 0; pp < npt2; pp += wg_pt2) {
+                        g2.rt_base = rp;
+                        const int r0 = rp + wr2 * NRT2, p0 = pp + wp2 * NPT2;
+                        g2.active = r0 < rte && p0 < npt2;
+                        typename M2::Acc acc2[NRT2][NPT2];
+                        int off2[NPT2];
+#pragma unroll
+                        for (int p = 0; p < NPT2; ++p) {
+                            zero_acc(acc2[0][p]);
+#pragma unroll
+                            for (int r = 1; r < NRT2; ++r) acc2[r][p] = acc2[0][p];
+                            const int pidx = (p0 + p) * MF2 + col;
+                            const int oy = min(pidx / P.vw2, P.th - 1), ox = min(pidx % P.vw2, P.tw - 1);
+                            off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * P.mid_gstride;
+                        }
+                        if (c.k == 3)
+                            conv_pass<MF2, 3, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
+                        else
+                            conv_pass<MF2, 1, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
+                        store_global<MF2, NRT2, NPT2>(acc2, P, c, P.coff2[ci], n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
+                                                      p0, P.sc, P.relu_out);
+                    }
                 }
-                item -= nitems;
             }
         }
-        __syncthreads();
         XL_PHASE(L, 3);
     }
 }

@@ -71,10 +71,11 @@ struct Choice {
     bool ok = false;
     double cost = 0;
     Variant v{};
-    int threads = 0, waves_r1 = 0, csplit = 1;
-    int th = 0, tw = 0, mh = 0, mw = 0, ih = 0, iw = 0;
+    int threads = 0, waves_r1 = 0, waves_r2 = 1, csplit = 1;
+    int th = 0, tw = 0, mh = 0, mw = 0, ih = 0, iw = 0, vw2 = 0;
     int tiles_y = 0, tiles_x = 0;
-    int chunk_kg = 0, nchunks = 0;
+    int chunk_kg = 0, chunk_kg2[2] = {1, 1};
+    int mid_floats = 0, buf_floats = 0, w_off1 = 0;
     int lds_bytes = 0, occ = 1;
     long long flops_exec = 0;
     bool lds_rejected = false;
@@ -88,6 +89,20 @@ static std::vector<int> tile_candidates(int extent)
 }
 
 static double mfma_clk(int mf) { return mf == 32 ? 64.0 : 32.0; }
+
+// Largest number of K steps per chunk the stagers can hold, shortened so that one chunk keeps
+// the matrix cores busy for a few thousand cycles (amortises the per-chunk barrier) and no more.
+static int pick_chunk(int nkg, int x_items_per_kg, int w_items_per_kg, int threads, double clk_per_kg)
+{
+    int cap = nkg;
+    if (x_items_per_kg > 0) cap = std::min(cap, STAGE_ITEMS * threads / x_items_per_kg);
+    cap = std::min(cap, STAGE_W * threads / std::max(w_items_per_kg, 1));
+    if (cap < 1) return 0;
+    int want = (int)std::ceil(6000.0 / std::max(clk_per_kg, 1.0));
+    int chunk = std::max(1, std::min(cap, want));
+    const int nchunks = ceil_div(nkg, chunk);
+    return std::min(cap, ceil_div(nkg, nchunks));       // balance the chunks
+}
 
 // Model of one candidate.  Times in seconds on a nominal MI355X (2.4 GHz, 8 TB/s).
 static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
@@ -108,34 +123,39 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
         if (rt0 < rt_end && pt0 * mf1 < npx1) simd[w % 4] += wave1;
     }
     double t1 = *std::max_element(simd, simd + 4);
+    int barriers = ceil_div(nkg1, c.chunk_kg);
     double t2 = 0;
     long long flops2 = 0;
     if (b.kind == KIND_FUSED2) {
         const int mf2 = v.mf2, NRT2 = nrt2_of(mf2), NPT2 = npt2_of(mf2);
-        const int npx2 = c.th * c.tw;
-        const int nptg = ceil_div(ceil_div(npx2, mf2), NPT2);
-        std::vector<double> wl(nw, 0.0);
-        int item = 0;       // running item counter, same order as the kernel's round-robin
+        const int npt2 = ceil_div(c.th * c.vw2, mf2);
+        const int wg_rt2 = c.waves_r2 * NRT2, wg_pt2 = (nw / c.waves_r2) * NPT2;
         for (int ci = 0; ci < b.n2; ++ci) {
             const ConvSpec &s = b.c2[ci];
             const int nrt = ceil_div(s.cout, mf2), nkg = ceil_div(s.cin, kc_of(mf2));
-            const int per = ceil_div(nrt, c.csplit);
-            const int nrtg = ceil_div(std::min(per, nrt), NRT2);
-            const double ic = (double)NRT2 * NPT2 * nkg * s.k * s.k * 4 * mfma_clk(mf2);
-            for (int i = 0; i < nrtg * nptg; ++i, ++item) wl[item % nw] += ic;
-            flops2 += 2LL * nrtg * NRT2 * mf2 * nptg * NPT2 * mf2 * nkg * kc_of(mf2) * s.k * s.k;
+            const int per = std::min(nrt, ceil_div(nrt, c.csplit));
+            const double wave2 = (double)NRT2 * NPT2 * nkg * s.k * s.k * 4 * mfma_clk(mf2);
+            for (int rp = 0; rp < per; rp += wg_rt2)
+                for (int pp = 0; pp < npt2; pp += wg_pt2) {
+                    double s2[4] = {0, 0, 0, 0};
+                    for (int w = 0; w < nw; ++w) {
+                        const int r0 = rp + (w % c.waves_r2) * NRT2, p0 = pp + (w / c.waves_r2) * NPT2;
+                        if (r0 < per && p0 < npt2) s2[w % 4] += wave2;
+                    }
+                    t2 += *std::max_element(s2, s2 + 4) + 2500.0;       // + epilogue / prologue of the pass
+                    barriers += ceil_div(nkg, c.chunk_kg2[ci]);
+                    flops2 += 2LL * std::min(wg_rt2, per - rp) * mf2 * std::min(wg_pt2, npt2 - pp) * mf2 * nkg *
+                              kc_of(mf2) * s.k * s.k;
+                }
         }
-        double s2[4] = {0, 0, 0, 0};
-        for (int w = 0; w < nw; ++w) s2[w % 4] += wl[w];
-        t2 = *std::max_element(s2, s2 + 4);
     } else if (b.kind == KIND_POOL) {
         t2 = (double)ceil_div(b.c1.cout, 4) * c.th * c.tw * b.pool_k * b.pool_k * 8.0 / c.threads * 4;
     }
-    const double ovh = 5000.0 + 800.0 * c.nchunks;
+    const double ovh = 6000.0 + 350.0 * barriers;
     const double wg_clk = t1 + t2 + ovh;
     const long long nwg = (long long)c.tiles_x * c.tiles_y * c.csplit * b.N;
     const double rounds = std::ceil((double)nwg / pl.num_cus);
-    const double t_mfma = rounds * wg_clk * (c.occ >= 2 ? 1.0 : 1.2) / 2.4e9;
+    const double t_mfma = rounds * wg_clk * (c.occ >= 2 ? 1.0 : 1.08) / 2.4e9;
 
     // memory side: algorithmic bytes at HBM speed plus per-workgroup cache-line traffic at L2 speed
     auto lines = [](int w) { return (double)((w * 4 + 64 + 127) / 128) * 128.0; };
@@ -172,6 +192,7 @@ static Choice search(const BlockSpec &b, const xl_plan &pl)
         if (v.kind != b.kind || v.k1 != b.c1.k) continue;
         const int mf1 = v.mf1;
         const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
+        const int taps1 = b.c1.k * b.c1.k;
         for (int threads : {256, 512}) {
             const int nw = threads / 64;
             for (int wr = 1; wr <= nw; wr *= 2) {
@@ -186,6 +207,7 @@ static Choice search(const BlockSpec &b, const xl_plan &pl)
                     c.waves_r1 = wr;
                     c.th = th;
                     c.tw = tw;
+                    c.vw2 = tw;
                     if (b.kind == KIND_SINGLE) {
                         c.mh = th;
                         c.mw = tw;
@@ -205,40 +227,70 @@ static Choice search(const BlockSpec &b, const xl_plan &pl)
                     c.iw = required_extent(c.mw, b.c1.k, b.c1.stride);
                     c.tiles_y = ceil_div(b.Ho, th);
                     c.tiles_x = ceil_div(b.Wo, tw);
-                    // input chunk: as many K steps as one pass of the stager can hold
-                    const int per_kg = gps_of(mf1) * c.ih * c.iw;
-                    int chunk = std::min(nkg1, (STAGE_ITEMS * threads) / per_kg);
-                    if (chunk < 1) continue;
-                    c.nchunks = ceil_div(nkg1, chunk);
-                    chunk = ceil_div(nkg1, c.nchunks);                          // balance the chunks
-                    c.chunk_kg = chunk;
-                    const int in_bytes = chunk * per_kg * 16;
-                    int mid_bytes = 0;
-                    if (b.kind != KIND_SINGLE) mid_bytes = nrt1 * mf1 / 4 * c.mh * c.mw * 16;
-                    c.lds_bytes = mid_bytes + in_bytes;
-                    if (c.lds_bytes > pl.lds_budget) {
-                        any_lds_reject = true;
-                        continue;
-                    }
-                    c.occ = std::max(1, std::min({pl.lds_per_cu / std::max(c.lds_bytes, 1), 2048 / threads, 16 / nw}));
-                    std::vector<int> splits;
-                    if (b.kind == KIND_SINGLE) {
-                        splits.push_back(ceil_div(nrt1, wg_rt));
-                    } else if (b.kind == KIND_POOL) {
-                        splits.push_back(1);
-                    } else if (pl.opts.force_cout_split > 0) {
-                        splits.push_back(pl.opts.force_cout_split);
+                    // stage-1 chunk: input tile chunk + filter chunk per buffer
+                    const int x_per_kg = gps_of(mf1) * c.ih * c.iw;
+                    const int w_per_kg = taps1 * wg_rt * 64;
+                    const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * 4 * mfma_clk(mf1);
+                    c.chunk_kg = pick_chunk(nkg1, x_per_kg, w_per_kg, threads, clk1);
+                    if (c.chunk_kg < 1) continue;
+                    c.w_off1 = c.chunk_kg * x_per_kg * 4;
+                    const int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
+                    c.mid_floats = b.kind == KIND_SINGLE ? 0 : nrt1 * mf1 / 4 * c.mh * c.mw * 4;
+
+                    std::vector<int> splits, wr2s, vws;
+                    if (b.kind == KIND_FUSED2) {
+                        if (pl.opts.force_cout_split > 0) {
+                            splits.push_back(pl.opts.force_cout_split);
+                        } else {
+                            int min_nrt = 1 << 30;
+                            for (int i = 0; i < b.n2; ++i) min_nrt = std::min(min_nrt, ceil_div(b.c2[i].cout, v.mf2));
+                            for (int s = 1; s <= 8 && s <= min_nrt; s *= 2) splits.push_back(s);
+                        }
+                        for (int w2 = 1; w2 <= nw; w2 *= 2) wr2s.push_back(w2);
+                        vws.push_back(tw);
+                        if (tw % 16 && (tw + 15) / 16 * 16 - tw <= 4) vws.push_back((tw + 15) / 16 * 16);
                     } else {
-                        int min_nrt = 1 << 30;
-                        for (int i = 0; i < b.n2; ++i) min_nrt = std::min(min_nrt, ceil_div(b.c2[i].cout, v.mf2));
-                        for (int s = 1; s <= 8 && s <= min_nrt; s *= 2) splits.push_back(s);
+                        splits.push_back(b.kind == KIND_SINGLE ? ceil_div(nrt1, wg_rt) : 1);
+                        wr2s.push_back(1);
+                        vws.push_back(tw);
                     }
-                    for (int cs : splits) {
-                        c.csplit = cs;
-                        evaluate(b, pl, c);
-                        c.ok = true;
-                        if (!best.ok || c.cost < best.cost) best = c;
-                    }
+                    for (int cs : splits)
+                        for (int w2 : wr2s)
+                            for (int vw : vws) {
+                                c.csplit = cs;
+                                c.waves_r2 = w2;
+                                c.vw2 = vw;
+                                int buf = buf1;
+                                bool fits = true;
+                                if (b.kind == KIND_FUSED2) {
+                                    const int NRT2 = nrt2_of(v.mf2), NPT2 = npt2_of(v.mf2);
+                                    int max_per = 0;
+                                    for (int i = 0; i < b.n2; ++i)
+                                        max_per = std::max(max_per, ceil_div(ceil_div(b.c2[i].cout, v.mf2), cs));
+                                    if (w2 > 1 && (w2 / 2) * NRT2 >= max_per) continue;     // idle row waves
+                                    for (int i = 0; i < b.n2; ++i) {
+                                        const int nkg2 = ceil_div(b.c2[i].cin, kc_of(v.mf2));
+                                        const int w2_per_kg = b.c2[i].k * b.c2[i].k * w2 * NRT2 * 64;
+                                        const double clk2 = (double)(nw / 4.0) * NRT2 * NPT2 * b.c2[i].k * b.c2[i].k * 4 *
+                                                            mfma_clk(v.mf2);
+                                        c.chunk_kg2[i] = pick_chunk(nkg2, 0, w2_per_kg, threads, clk2);
+                                        if (c.chunk_kg2[i] < 1) fits = false;
+                                        buf = std::max(buf, c.chunk_kg2[i] * w2_per_kg * 4);
+                                    }
+                                }
+                                if (!fits) continue;
+                                c.buf_floats = buf;
+                                c.lds_bytes = (c.mid_floats + 2 * buf) * 4;
+                                if (c.lds_bytes > pl.lds_budget) {
+                                    any_lds_reject = true;
+                                    continue;
+                                }
+                                c.occ = std::max(1, std::min({pl.lds_per_cu / std::max(c.lds_bytes, 1), 2048 / threads,
+                                                              8 / nw}));
+                                evaluate(b, pl, c);
+                                c.ok = true;
+                                if (!best.ok || c.cost < best.cost) best = c;
+                            }
                 }
             }
         }
@@ -497,11 +549,16 @@ struct Builder {
         p.csplit = ch.csplit;
         p.nblocks = ch.tiles_x * ch.tiles_y * ch.csplit * b.N;
         p.chunk_kg = ch.chunk_kg;
-        p.nchunks = ch.nchunks;
+        p.chunk_kg2[0] = ch.chunk_kg2[0];
+        p.chunk_kg2[1] = ch.chunk_kg2[1];
         p.waves_r1 = ch.waves_r1;
+        p.waves_r2 = ch.waves_r2;
+        p.vw2 = ch.vw2;
         p.mid_gstride = ch.mh * ch.mw * 4;
         p.in_gstride = ch.ih * ch.iw * 4;
-        p.lds_in_off = b.kind == KIND_SINGLE ? 0 : p.c1.nrt * ch.v.mf1 / 4 * p.mid_gstride;
+        p.lds_buf_off = ch.mid_floats;
+        p.buf_stride = ch.buf_floats;
+        p.w_off1 = ch.w_off1;
         return XL_OK;
     }
 

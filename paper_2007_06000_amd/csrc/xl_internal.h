@@ -64,11 +64,16 @@ struct BlockParams {
     int ih, iw;             // input tile (incl. halo)
     int tiles_x, tiles_y, csplit;
     int nblocks;            // logical workgroups = N * csplit * tiles_y * tiles_x
-    int chunk_kg, nchunks;  // K steps staged per pipeline step; number of steps
+    int chunk_kg;           // stage 1: K steps staged per chunk
+    int chunk_kg2[2];       // stage 2: K steps of filter staged per chunk, per convolution
     int waves_r1;           // stage-1 waves along the row-tile (Cout) direction
+    int waves_r2;           // stage-2 waves along the row-tile direction
+    int vw2;                // stage 2 lays output pixels out in virtual rows of vw2 >= tw columns
     int mid_gstride;        // floats between consecutive 4-channel groups of the LDS tile
     int in_gstride;         // same for the staged input
-    int lds_in_off;         // float offset of the input staging area in LDS
+    int lds_buf_off;        // float offset of the two staging buffers in LDS (after the tile)
+    int buf_stride;         // floats per staging buffer
+    int w_off1;             // stage 1: float offset of the filter chunk inside a buffer (after the input chunk)
 };
 
 // A compiled kernel variant.
@@ -119,7 +124,8 @@ const std::vector<Variant> &variants();
 constexpr int nrt2_of(int mf2) { return mf2 == 32 ? 2 : 1; }
 constexpr int npt2_of(int mf2) { return mf2 == 32 ? 1 : 2; }
 
-constexpr int STAGE_ITEMS = 4;      // float4 items each thread stages per pipeline step
+constexpr int STAGE_ITEMS = 4;      // float4 input items each thread stages per chunk
+constexpr int STAGE_W = 6;          // float4 filter items each thread stages per chunk
 constexpr int MAX_THREADS = 512;
 
 // ---- launchers (kernels.hip) -------------------------------------------------
