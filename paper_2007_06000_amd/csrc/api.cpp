@@ -166,6 +166,9 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, vo
         hipError_t e = xl::launch_pack_filter(static_cast<const float *>(weights[L.w_slot]),
                                               reinterpret_cast<xl::f32x4 *>(ws + p.offset), L.cout, L.cin, L.k, p.mf,
                                               p.nkg, p.nrt, s);
+        if (e == hipSuccess)
+            e = xl::launch_pack_affine(plan->scale_ptr[p.layer], plan->shift_ptr[p.layer],
+                                       reinterpret_cast<xl::f32x4 *>(ws + p.aff_offset), L.cout, p.mf, p.nrt, s);
         if (e != hipSuccess) {
             plan->error = std::string("filter re-layout launch failed: ") + hipGetErrorString(e);
             return XL_E_LAUNCH;
@@ -214,8 +217,7 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors, 
             for (int i = 0; i < 3; ++i) {
                 if (st.conv_layer[i] < 0) continue;
                 cw[i]->wp = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].offset);
-                cw[i]->scale = plan->scale_ptr[st.conv_layer[i]];
-                cw[i]->shift = plan->shift_ptr[st.conv_layer[i]];
+                cw[i]->aff = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].aff_offset);
             }
             e = xl::launch_block(st.variant, p, st.threads, (size_t)st.lds_bytes, s);
         } else if (st.type == xl::STEP_MAXPOOL) {

@@ -218,7 +218,7 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int cc = c0 + chan[i] + j;
-                    xst[i][j] = (pixoff[i] >= 0 && cc < P.Cin) ? ximg[(size_t)cc * HW + pixoff[i]] : 0.f;
+                    xst[i][j] = (pixoff[i] >= 0 && cc < P.Cin) ? ximg[cc * HW + pixoff[i]] : 0.f;
                 }
             }
         }
@@ -234,6 +234,9 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     };
 
     const int nchunks = (c.nkg + g.chunk_kg - 1) / g.chunk_kg;
+#ifdef XL_PHASE_TIMING
+    long long t_ld = 0, t_mm = 0, t_st = 0, t_pro = clock64();
+#endif
     load_x(0);
     load_w(0);
     store_x(buf);
@@ -244,32 +247,52 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         float *nxt = buf + ((ch + 1) & 1) * g.buf_stride;
         const bool more = ch + 1 < nchunks;
         const int kg0 = ch * g.chunk_kg;
+#ifdef XL_PHASE_TIMING
+        if (ch == 0) t_pro = clock64() - t_pro;
+        long long t0 = clock64();
+#endif
         if (more) {
             load_x((kg0 + g.chunk_kg) * M::KC);
             load_w(kg0 + g.chunk_kg);
         }
+#ifdef XL_PHASE_TIMING
+        long long t1 = clock64();
+#endif
         const int nkg = min(g.chunk_kg, c.nkg - kg0);
         if (g.active) {
             const float *bs = STAGE_X ? cur : bsrc + kg0 * (M::GPS * g.gstride);
             conv_accum<MF, KS, NRT, NPT>(acc, bs, off, g.src_w, g.gstride, cur + g.w_off, rloc, g.wg_rt, nkg);
         }
+#ifdef XL_PHASE_TIMING
+        long long t2 = clock64();
+#endif
         if (more) {
             store_x(nxt);
             store_w(nxt + g.w_off);
         }
         __syncthreads();
+#ifdef XL_PHASE_TIMING
+        long long t3 = clock64();
+        t_ld += t1 - t0; t_mm += t2 - t1; t_st += t3 - t2;
+#endif
     }
+#ifdef XL_PHASE_TIMING
+    if (threadIdx.x == 0 && STAGE_X) {
+        const int Lb = logical_block();
+        if (Lb < 8192) { g_phase[Lb * 16 + 4] = t_pro; g_phase[Lb * 16 + 5] = t_ld; g_phase[Lb * 16 + 6] = t_mm; g_phase[Lb * 16 + 7] = t_st; }
+    }
+#endif
 }
 
-// per-channel scale / shift of 4 consecutive output channels (clamped: callers mask co >= cout)
-__device__ __forceinline__ void load_affine(const ConvW &c, int cb, float (&sc)[4], float (&sh)[4])
+// Per-channel scale / shift of the 4 consecutive output channels a lane holds in accumulator
+// quad q of row tile rt, from the table xl_prepare lays out in accumulator order:
+// [row tile][quad][scale, shift][lane] float4 (0 for channels past Cout).
+template <int MF>
+__device__ __forceinline__ void load_affine(const ConvW &c, int rt, int q, f32x4 &sc, f32x4 &sh)
 {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int co = min(cb + i, c.cout - 1);
-        sc[i] = c.scale ? c.scale[co] : 1.f;
-        sh[i] = c.shift ? c.shift[co] : 0.f;
-    }
+    const f32x4 *t = c.aff + ((rt * MM<MF>::NQ + q) * 2) * 64 + (threadIdx.x & 63);
+    sc = t[0];
+    sh = t[64];
 }
 
 // Epilogue of a tile to global memory (S5), also used by the single-layer kernel.
@@ -282,53 +305,46 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     typedef MM<MF> M;
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
-    const size_t plane = (size_t)P.Ho * P.Wo;
+    // per-image element counts fit 31 bits (checked by the planner): 32-bit offsets from uniform bases
+    const int plane = P.Ho * P.Wo;
+    float *__restrict__ yn = P.y + ((size_t)n * P.Cy + coff) * plane;
+    const float *__restrict__ scn = sc ? sc + (size_t)n * P.Csc * plane : nullptr;
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
         const int oy = pidx / vw, ox = pidx - oy * vw;
         const int gy = oy0 + oy, gx = ox0 + ox;
         const bool pv = oy < th && ox < tw && gy < P.Ho && gx < P.Wo;
-        const size_t pix = pv ? (size_t)gy * P.Wo + gx : 0;
+        const int pix = pv ? gy * P.Wo + gx : 0;
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
             if (rt0 + r >= rt_end) continue;
-            float res[M::NQ][4];
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
-                float a[4], b[4];
-                load_affine(c, cb, a, b);
+                f32x4 a, b;
+                float res[4];
+                load_affine<MF>(c, rt0 + r, q, a, b);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float v = acc[r][p][q * 4 + i] * a[i] + b[i];
                     if (c.relu) v = fmaxf(v, 0.f);
-                    res[q][i] = v;
+                    res[i] = v;
                 }
-            }
-            if (sc) {       // shortcut add: all loads of this tile issued together, invalid lanes read element 0
-                float sv[M::NQ][4];
+                if (scn) {      // shortcut add: the 4 loads go out together, invalid lanes read element 0
+                    float sv[4];
 #pragma unroll
-                for (int q = 0; q < M::NQ; ++q)
+                    for (int i = 0; i < 4; ++i) sv[i] = scn[min(cb + i, c.cout - 1) * plane + pix];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int co = min((rt0 + r) * MF + M::quad_row(q, sub) + i, c.cout - 1);
-                        sv[q][i] = sc[((size_t)n * P.Csc + co) * plane + pix];
-                    }
-#pragma unroll
-                for (int q = 0; q < M::NQ; ++q)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) res[q][i] += sv[q][i];
-            }
-#pragma unroll
-            for (int q = 0; q < M::NQ; ++q)
+                    for (int i = 0; i < 4; ++i) res[i] += sv[i];
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int co = (rt0 + r) * MF + M::quad_row(q, sub) + i;
-                    float v = res[q][i];
+                    float v = res[i];
                     if (relu_out) v = fmaxf(v, 0.f);
-                    if (pv && co < c.cout) P.y[((size_t)n * P.Cy + coff + co) * plane + pix] = v;
+                    if (pv && cb + i < c.cout) yn[(cb + i) * plane + pix] = v;
                 }
+            }
         }
     }
 }
@@ -356,8 +372,8 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
-                float a[4], b[4];
-                load_affine(c, cb, a, b);
+                f32x4 a, b;
+                load_affine<MF>(c, rt0 + r, q, a, b);
                 f32x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -482,13 +498,16 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
             const int wr2 = wave % P.waves_r2, wp2 = wave / P.waves_r2;
             const int wg_pt2 = (nwaves / P.waves_r2) * NPT2;
             for (int ci = 0; ci < P.n2; ++ci) {
-                const ConvW &c = P.c2[ci];
+                // copy the descriptor by value: indexing the kernel argument with a runtime index
+                // would move the whole argument block into scratch memory
+                const ConvW c = ci == 0 ? P.c2[0] : P.c2[1];
+                const int coff = ci == 0 ? P.coff2[0] : P.coff2[1];
                 const int per = (c.nrt + P.csplit - 1) / P.csplit;           // row tiles of this workgroup
                 const int rtb = cs * per, rte = min(c.nrt, rtb + per);
                 PassGeom g2;
                 g2.wg_rt = P.waves_r2 * NRT2;
                 g2.wr = wr2;
-                g2.chunk_kg = P.chunk_kg2[ci];
+                g2.chunk_kg = ci == 0 ? P.chunk_kg2[0] : P.chunk_kg2[1];
                 g2.src_w = P.mw;
                 g2.gstride = P.mid_gstride;
                 g2.w_off = 0;
@@ -514,7 +533,7 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
                             conv_pass<MF2, 3, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
                         else
                             conv_pass<MF2, 1, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
-                        store_global<MF2, NRT2, NPT2>(acc2, P, c, P.coff2[ci], n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
+                        store_global<MF2, NRT2, NPT2>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
                                                       p0, P.sc, P.relu_out);
                     }
                 }
@@ -608,6 +627,36 @@ hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int 
     const int threads = 256;
     const int grid = (int)((total + threads - 1) / threads);
     hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, wp, cout, cin, k, mf, nkg, nrt);
+    return hipGetLastError();
+}
+
+// scale / shift in accumulator order: [row tile][quad][scale, shift][lane] float4
+__global__ void pack_affine_kernel(const float *__restrict__ scale, const float *__restrict__ shift,
+                                   f32x4 *__restrict__ out, int cout, int mf, int nrt)
+{
+    const int nq = mf == 32 ? 4 : 1;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // over nrt * nq * 64
+    if (idx >= nrt * nq * 64) return;
+    const int lane = idx & 63, q = (idx >> 6) % nq, rt = (idx >> 6) / nq;
+    const int sub = lane / mf;
+    const int cb = rt * mf + (mf == 32 ? q * 8 + sub * 4 : sub * 4);
+    f32x4 a, b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int co = cb + i;
+        a[i] = co < cout ? (scale ? scale[co] : 1.f) : 0.f;
+        b[i] = co < cout ? (shift ? shift[co] : 0.f) : 0.f;
+    }
+    out[((rt * nq + q) * 2) * 64 + lane] = a;
+    out[((rt * nq + q) * 2 + 1) * 64 + lane] = b;
+}
+
+hipError_t launch_pack_affine(const float *scale, const float *shift, f32x4 *out, int cout, int mf, int nrt,
+                              hipStream_t s)
+{
+    const int total = nrt * (mf == 32 ? 4 : 1) * 64;
+    hipLaunchKernelGGL(pack_affine_kernel, dim3((total + 255) / 256), dim3(256), 0, s, scale, shift, out, cout, mf,
+                       nrt);
     return hipGetLastError();
 }
 

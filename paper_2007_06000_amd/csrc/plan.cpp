@@ -474,6 +474,8 @@ struct Builder {
         p.nrt = ceil_div(L.cout, mf);
         p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16;
         p.offset = 0;
+        p.aff_bytes = (size_t)p.nrt * (mf == 32 ? 4 : 1) * 2 * 64 * 16;
+        p.aff_offset = 0;
         pl.packed.push_back(p);
         return (int)pl.packed.size() - 1;
     }
@@ -513,7 +515,7 @@ struct Builder {
         p.Csc = sc_id >= 0 ? pl.shapes[sc_id].c : 0;
         auto fill = [&](ConvW &w, const ConvSpec &s, int mf) {
             w.wp = nullptr;
-            w.scale = w.shift = nullptr;
+            w.aff = nullptr;
             w.cin = s.cin;
             w.cout = s.cout;
             w.k = s.k;
@@ -826,6 +828,8 @@ struct Builder {
         for (PackedFilter &p : pl.packed) {
             p.offset = off;
             off = align_up(off + p.bytes, 256);
+            p.aff_offset = off;
+            off = align_up(off + p.aff_bytes, 256);
         }
         for (size_t t = 0; t < pl.shapes.size(); ++t) {
             Storage &st = pl.storage[t];

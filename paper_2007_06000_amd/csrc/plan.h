@@ -18,6 +18,8 @@ struct PackedFilter {
     int nkg, nrt;
     size_t offset;      // bytes into the workspace
     size_t bytes;
+    size_t aff_offset;  // scale / shift table in accumulator order
+    size_t aff_bytes;
 };
 
 // Where a tensor lives: itself, or a channel slice of a concatenated tensor.

@@ -23,8 +23,7 @@ constexpr int gps_of(int mf) { return mf == 32 ? 2 : 4; }       // 4-channel gro
 // One convolution as the kernels see it.
 struct ConvW {
     const f32x4 *wp;        // filter re-laid out as [K step][tap][row tile][lane] of float4
-    const float *scale;     // per output channel, or nullptr (= 1)
-    const float *shift;     // per output channel, or nullptr (= 0)
+    const f32x4 *aff;       // scale / shift in accumulator order: [row tile][quad][scale, shift][lane] float4
     int cin, cout;
     int k, stride, pad;
     int relu;
@@ -134,6 +133,8 @@ hipError_t configure_kernels(int max_lds_bytes);      // raises the dynamic-LDS 
 
 hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf,
                               int nkg, int nrt, hipStream_t s);
+hipError_t launch_pack_affine(const float *scale, const float *shift, f32x4 *out, int cout, int mf, int nrt,
+                              hipStream_t s);
 hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, int Ho, int Wo,
                           int k, int stride, int pad, int Cy, int coff, hipStream_t s);
 hipError_t launch_add(const float *a, const float *b, float *y, long long count, int relu, hipStream_t s);
