@@ -22,6 +22,8 @@
 // is exactly one float4 of the LDS tile layout.
 #include <float.h>
 
+#include <type_traits>
+
 #include "xl_internal.h"
 
 namespace xl {
@@ -297,10 +299,12 @@ __device__ __forceinline__ void load_affine(const ConvW &c, int rt, int q, f32x4
 
 // Epilogue of a tile to global memory (S5), also used by the single-layer kernel.
 // Pixel p of the tile sits at (p / vw, p % vw); columns >= tw of the virtual row are padding.
-template <int MF, int NRT, int NPT>
+// HAS_SC (merge mode): the shortcut values of one row tile are fetched together before they are
+// used; invalid lanes read element 0.
+template <int MF, int NRT, int NPT, bool HAS_SC>
 __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
                                              const ConvW &c, int coff, int n, int oy0, int ox0, int th, int tw, int vw,
-                                             int rt0, int rt_end, int pt0, const float *sc, int relu_out)
+                                             int rt0, int rt_end, int pt0, int relu_out)
 {
     typedef MM<MF> M;
     const int lane = threadIdx.x & 63;
@@ -308,7 +312,7 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     // per-image element counts fit 31 bits (checked by the planner): 32-bit offsets from uniform bases
     const int plane = P.Ho * P.Wo;
     float *__restrict__ yn = P.y + ((size_t)n * P.Cy + coff) * plane;
-    const float *__restrict__ scn = sc ? sc + (size_t)n * P.Csc * plane : nullptr;
+    const float *__restrict__ scn = HAS_SC ? P.sc + (size_t)n * P.Csc * plane : nullptr;
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -319,28 +323,24 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
             if (rt0 + r >= rt_end) continue;
+            float sv[M::NQ * 4];
+            if constexpr (HAS_SC) {
+#pragma unroll
+                for (int e = 0; e < M::NQ * 4; ++e) {
+                    const int co = min((rt0 + r) * MF + M::quad_row(e >> 2, sub) + (e & 3), c.cout - 1);
+                    sv[e] = scn[co * plane + pix];
+                }
+            }
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
                 f32x4 a, b;
-                float res[4];
                 load_affine<MF>(c, rt0 + r, q, a, b);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float v = acc[r][p][q * 4 + i] * a[i] + b[i];
                     if (c.relu) v = fmaxf(v, 0.f);
-                    res[i] = v;
-                }
-                if (scn) {      // shortcut add: the 4 loads go out together, invalid lanes read element 0
-                    float sv[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) sv[i] = scn[min(cb + i, c.cout - 1) * plane + pix];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) res[i] += sv[i];
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float v = res[i];
+                    if constexpr (HAS_SC) v += sv[q * 4 + i];
                     if (relu_out) v = fmaxf(v, 0.f);
                     if (pv && cb + i < c.cout) yn[(cb + i) * plane + pix] = v;
                 }
@@ -392,7 +392,7 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 // ----------------------------------------------------------------------------
 // The block kernel
 // ----------------------------------------------------------------------------
-template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2>
+template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int K2A, int K2B, bool SC>
 __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -453,8 +453,8 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
     XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {
-        store_global<MF1, NRT1, NPT1>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mh, P.mw, P.mw, rt0, rt_end1, pt0, P.sc,
-                                      P.relu_out);
+        store_global<MF1, NRT1, NPT1, false>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mh, P.mw, P.mw, rt0, rt_end1, pt0,
+                                             P.relu_out);
         return;
     } else {
         // ---- S2: epilogue of layer 1 into the LDS tile, S3: barrier
@@ -497,17 +497,14 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
             const int npt2 = (P.th * P.vw2 + MF2 - 1) / MF2;
             const int wr2 = wave % P.waves_r2, wp2 = wave / P.waves_r2;
             const int wg_pt2 = (nwaves / P.waves_r2) * NPT2;
-            for (int ci = 0; ci < P.n2; ++ci) {
-                // copy the descriptor by value: indexing the kernel argument with a runtime index
-                // would move the whole argument block into scratch memory
-                const ConvW c = ci == 0 ? P.c2[0] : P.c2[1];
-                const int coff = ci == 0 ? P.coff2[0] : P.coff2[1];
+            auto run_conv = [&](auto ks_tag, const ConvW &c, int coff, int chunk_kg2) {
+                constexpr int KS2 = decltype(ks_tag)::value;
                 const int per = (c.nrt + P.csplit - 1) / P.csplit;           // row tiles of this workgroup
                 const int rtb = cs * per, rte = min(c.nrt, rtb + per);
                 PassGeom g2;
                 g2.wg_rt = P.waves_r2 * NRT2;
                 g2.wr = wr2;
-                g2.chunk_kg = ci == 0 ? P.chunk_kg2[0] : P.chunk_kg2[1];
+                g2.chunk_kg = chunk_kg2;
                 g2.src_w = P.mw;
                 g2.gstride = P.mid_gstride;
                 g2.w_off = 0;
@@ -529,15 +526,15 @@ __global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
                             const int oy = min(pidx / P.vw2, P.th - 1), ox = min(pidx % P.vw2, P.tw - 1);
                             off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * P.mid_gstride;
                         }
-                        if (c.k == 3)
-                            conv_pass<MF2, 3, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
-                        else
-                            conv_pass<MF2, 1, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
-                        store_global<MF2, NRT2, NPT2>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
-                                                      p0, P.sc, P.relu_out);
+                        conv_pass<MF2, KS2, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
+                        if (g2.active)
+                            store_global<MF2, NRT2, NPT2, SC>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
+                                                              p0, P.relu_out);
                     }
                 }
-            }
+            };
+            run_conv(std::integral_constant<int, K2A>{}, P.c2[0], P.coff2[0], P.chunk_kg2[0]);
+            if constexpr (K2B != 0) run_conv(std::integral_constant<int, K2B>{}, P.c2[1], P.coff2[1], P.chunk_kg2[1]);
         }
         XL_PHASE(L, 3);
     }
@@ -551,9 +548,9 @@ typedef void (*BlockKernel)(const BlockParams);
 static BlockKernel kernel_of(int variant)
 {
     switch (variant) {
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2) \
-    case ID:                                  \
-        return block_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2)>;
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC) \
+    case ID:                                                \
+        return block_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0)>;
         XL_VARIANT_LIST(X)
 #undef X
     }
@@ -563,7 +560,7 @@ static BlockKernel kernel_of(int variant)
 const std::vector<Variant> &variants()
 {
     static const std::vector<Variant> v = {
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2) Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2},
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC) Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC},
         XL_VARIANT_LIST(X)
 #undef X
     };

@@ -190,6 +190,9 @@ static Choice search(const BlockSpec &b, const xl_plan &pl)
     bool any_lds_reject = false;
     for (const Variant &v : variants()) {
         if (v.kind != b.kind || v.k1 != b.c1.k) continue;
+        if (b.kind == KIND_FUSED2) {
+            if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
+        }
         const int mf1 = v.mf1;
         const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
         const int taps1 = b.c1.k * b.c1.k;
@@ -698,8 +701,8 @@ struct Builder {
             }
             b.kind = KIND_FUSED2;
             b.n2 = 2;
-            // heavier sibling first so the round-robin over waves starts with the long items
-            const bool a_first = (long long)A.k * A.k * A.cout >= (long long)B.k * B.k * B.cout;
+            // the sibling with the larger filter first (the kernel variants are compiled for that order)
+            const bool a_first = A.k > B.k || (A.k == B.k && A.cout >= B.cout);
             const int first = a_first ? ids[1] : ids[2], second = a_first ? ids[2] : ids[1];
             conv_spec(first, b.c2[0]);
             conv_spec(second, b.c2[1]);

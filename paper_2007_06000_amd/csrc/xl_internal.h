@@ -81,41 +81,57 @@ struct Variant {
     int kind;
     int mf1, k1, nrt1, npt1;    // stage 1: matrix-core tile, filter size, tiles per wave
     int mf2;                    // stage 2 matrix-core tile (0 when unused)
+    int k2a, k2b;               // stage 2 filter sizes, heavier sibling first (0 = absent)
+    int sc;                     // 1: adds a shortcut tensor in the epilogue (merge mode)
 };
 
-// id, kind, MF1, K1, NRT1, NPT1, MF2
-#define XL_VARIANT_LIST(X)                       \
-    X(0, KIND_SINGLE, 32, 1, 1, 1, 0)            \
-    X(1, KIND_SINGLE, 32, 1, 2, 1, 0)            \
-    X(2, KIND_SINGLE, 32, 1, 2, 2, 0)            \
-    X(3, KIND_SINGLE, 32, 3, 1, 1, 0)            \
-    X(4, KIND_SINGLE, 32, 3, 2, 1, 0)            \
-    X(5, KIND_SINGLE, 32, 3, 2, 2, 0)            \
-    X(6, KIND_SINGLE, 16, 1, 1, 1, 0)            \
-    X(7, KIND_SINGLE, 16, 1, 1, 2, 0)            \
-    X(8, KIND_SINGLE, 16, 1, 3, 2, 0)            \
-    X(9, KIND_SINGLE, 16, 3, 1, 1, 0)            \
-    X(10, KIND_SINGLE, 16, 3, 1, 2, 0)           \
-    X(11, KIND_FUSED2, 32, 1, 1, 1, 32)          \
-    X(12, KIND_FUSED2, 32, 1, 2, 1, 32)          \
-    X(13, KIND_FUSED2, 32, 3, 1, 1, 32)          \
-    X(14, KIND_FUSED2, 32, 3, 2, 1, 32)          \
-    X(15, KIND_FUSED2, 16, 1, 1, 1, 32)          \
-    X(16, KIND_FUSED2, 16, 1, 1, 2, 32)          \
-    X(17, KIND_FUSED2, 16, 1, 1, 3, 32)          \
-    X(18, KIND_FUSED2, 16, 1, 3, 2, 32)          \
-    X(19, KIND_FUSED2, 16, 3, 1, 1, 16)          \
-    X(20, KIND_FUSED2, 16, 3, 1, 3, 16)          \
-    X(21, KIND_FUSED2, 16, 1, 1, 1, 16)          \
-    X(22, KIND_FUSED2, 32, 1, 1, 1, 16)          \
-    X(23, KIND_FUSED2, 32, 3, 1, 1, 16)          \
-    X(24, KIND_FUSED2, 16, 3, 1, 1, 32)          \
-    X(25, KIND_POOL, 32, 1, 1, 1, 0)             \
-    X(26, KIND_POOL, 32, 1, 2, 1, 0)             \
-    X(27, KIND_POOL, 32, 3, 1, 1, 0)             \
-    X(28, KIND_POOL, 32, 3, 2, 1, 0)             \
-    X(29, KIND_POOL, 16, 1, 1, 1, 0)             \
-    X(30, KIND_POOL, 16, 3, 1, 1, 0)
+// id, kind, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC
+#define XL_VARIANT_LIST(X)                                \
+    X(0, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0)            \
+    X(1, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0)            \
+    X(2, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0)            \
+    X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0)            \
+    X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0)            \
+    X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0)            \
+    X(6, KIND_SINGLE, 16, 1, 1, 1, 0, 0, 0, 0)            \
+    X(7, KIND_SINGLE, 16, 1, 1, 2, 0, 0, 0, 0)            \
+    X(8, KIND_SINGLE, 16, 1, 3, 2, 0, 0, 0, 0)            \
+    X(9, KIND_SINGLE, 16, 3, 1, 1, 0, 0, 0, 0)            \
+    X(10, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0)           \
+    /* split (fire-like): 1x1 -> {3x3, 1x1} */            \
+    X(11, KIND_FUSED2, 32, 1, 1, 1, 32, 3, 1, 0)          \
+    X(12, KIND_FUSED2, 32, 1, 2, 1, 32, 3, 1, 0)          \
+    X(13, KIND_FUSED2, 16, 1, 1, 1, 32, 3, 1, 0)          \
+    X(14, KIND_FUSED2, 16, 1, 1, 2, 32, 3, 1, 0)          \
+    X(15, KIND_FUSED2, 16, 1, 1, 3, 32, 3, 1, 0)          \
+    X(16, KIND_FUSED2, 16, 1, 3, 2, 32, 3, 1, 0)          \
+    X(17, KIND_FUSED2, 16, 1, 1, 1, 16, 3, 1, 0)          \
+    X(18, KIND_FUSED2, 32, 1, 1, 1, 16, 3, 1, 0)          \
+    /* straight conv -> conv, and merge (with shortcut) */ \
+    X(19, KIND_FUSED2, 32, 3, 2, 1, 32, 3, 0, 0)          \
+    X(20, KIND_FUSED2, 32, 3, 2, 1, 32, 3, 0, 1)          \
+    X(21, KIND_FUSED2, 32, 3, 1, 1, 32, 3, 0, 0)          \
+    X(22, KIND_FUSED2, 32, 3, 1, 1, 32, 3, 0, 1)          \
+    X(23, KIND_FUSED2, 16, 3, 1, 1, 16, 3, 0, 0)          \
+    X(24, KIND_FUSED2, 16, 3, 1, 3, 16, 3, 0, 0)          \
+    X(25, KIND_FUSED2, 16, 3, 1, 1, 16, 3, 0, 1)          \
+    X(26, KIND_FUSED2, 32, 1, 1, 1, 32, 3, 0, 0)          \
+    X(27, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 0, 0)          \
+    X(28, KIND_FUSED2, 32, 3, 1, 1, 32, 1, 0, 0)          \
+    X(29, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 0, 0)          \
+    X(30, KIND_FUSED2, 16, 1, 1, 1, 16, 3, 0, 0)          \
+    X(31, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 0, 0)          \
+    X(32, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 0, 1)          \
+    X(33, KIND_FUSED2, 32, 1, 1, 1, 32, 3, 0, 1)          \
+    X(34, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 0, 1)          \
+    X(35, KIND_FUSED2, 16, 1, 1, 1, 16, 3, 0, 1)          \
+    /* conv -> maxpool */                                 \
+    X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0)             \
+    X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0)             \
+    X(38, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0)             \
+    X(39, KIND_POOL, 32, 3, 2, 1, 0, 0, 0, 0)             \
+    X(40, KIND_POOL, 16, 1, 1, 1, 0, 0, 0, 0)             \
+    X(41, KIND_POOL, 16, 3, 1, 1, 0, 0, 0, 0)
 
 const std::vector<Variant> &variants();
 
