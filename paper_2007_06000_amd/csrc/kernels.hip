@@ -283,6 +283,10 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         const int Lb = logical_block();
         if (Lb < 8192) { g_phase[Lb * 16 + 4] = t_pro; g_phase[Lb * 16 + 5] = t_ld; g_phase[Lb * 16 + 6] = t_mm; g_phase[Lb * 16 + 7] = t_st; }
     }
+    if (threadIdx.x == 0 && !STAGE_X && KS == 3) {
+        const int Lb = logical_block();
+        if (Lb < 8192) { g_phase[Lb * 16 + 12] = t_pro; g_phase[Lb * 16 + 13] = t_ld; g_phase[Lb * 16 + 14] = t_mm; g_phase[Lb * 16 + 15] = t_st; }
+    }
 #endif
 }
 
@@ -313,6 +317,14 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     const int plane = P.Ho * P.Wo;
     float *__restrict__ yn = P.y + ((size_t)n * P.Cy + coff) * plane;
     const float *__restrict__ scn = HAS_SC ? P.sc + (size_t)n * P.Csc * plane : nullptr;
+    // scale / shift of every channel this lane holds: all loads go out before the first use, but not
+    // before the K loop (the clobber keeps the compiler from hoisting 64 live registers over it)
+    asm volatile("" ::: "memory");
+    f32x4 fa[NRT][M::NQ], fb[NRT][M::NQ];
+#pragma unroll
+    for (int r = 0; r < NRT; ++r)
+#pragma unroll
+        for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[r][q], fb[r][q]);
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -334,15 +346,17 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
-                f32x4 a, b;
-                load_affine<MF>(c, rt0 + r, q, a, b);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float v = acc[r][p][q * 4 + i] * a[i] + b[i];
+                    float v = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
                     if (c.relu) v = fmaxf(v, 0.f);
                     if constexpr (HAS_SC) v += sv[q * 4 + i];
                     if (relu_out) v = fmaxf(v, 0.f);
+#ifdef XL_EXPERIMENT_NO_STORE
+                    if (pv && cb + i < c.cout && v == 12345.678f) yn[(cb + i) * plane + pix] = v;
+#else
                     if (pv && cb + i < c.cout) yn[(cb + i) * plane + pix] = v;
+#endif
                 }
             }
         }
@@ -360,6 +374,12 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
     const ConvW &c = P.c1;
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
+    asm volatile("" ::: "memory");      // keep the loads below from being hoisted over the K loop
+    f32x4 fa[NRT][M::NQ], fb[NRT][M::NQ];
+#pragma unroll
+    for (int r = 0; r < NRT; ++r)
+#pragma unroll
+        for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[r][q], fb[r][q]);
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -372,12 +392,10 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
-                f32x4 a, b;
-                load_affine<MF>(c, rt0 + r, q, a, b);
                 f32x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float z = acc[r][p][q * 4 + i] * a[i] + b[i];
+                    float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
                     if (c.relu) z = fmaxf(z, 0.f);
                     if (!inside) z = fill;
                     if (cb + i >= c.cout) z = 0.f;
