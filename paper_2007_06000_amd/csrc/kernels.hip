@@ -411,7 +411,7 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 // The block kernel
 // ----------------------------------------------------------------------------
 template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int K2A, int K2B, bool SC>
-__global__ void __launch_bounds__(MAX_THREADS) block_kernel(const BlockParams P)
+__global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const BlockParams P)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int L = logical_block();

@@ -621,6 +621,12 @@ struct Builder {
             b.W = x.w;
             b.H1 = b.Ho = y.h;
             b.W1 = b.Wo = y.w;
+            if (L.k == 1 && L.stride == 1 && L.pad == 0) {
+                // a pointwise convolution does not care about rows: tile the image as one row of
+                // H*W pixels, so that tiles are contiguous runs and no pixel tile is half empty
+                b.W = b.W1 = b.Wo = x.h * x.w;
+                b.H = b.H1 = b.Ho = 1;
+            }
             long long by, stv;
             layer_traffic(li, by, stv);
             b.alg_bytes = by;

@@ -90,6 +90,9 @@ struct Variant {
     X(0, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0)            \
     X(1, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0)            \
     X(2, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0)            \
+    X(42, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0)           \
+    X(43, KIND_SINGLE, 32, 1, 1, 3, 0, 0, 0, 0)           \
+    X(44, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0)           \
     X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0)            \
     X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0)            \
     X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0)            \
@@ -142,6 +145,9 @@ constexpr int npt2_of(int mf2) { return mf2 == 32 ? 1 : 2; }
 constexpr int STAGE_ITEMS = 4;      // float4 input items each thread stages per chunk
 constexpr int STAGE_W = 6;          // float4 filter items each thread stages per chunk
 constexpr int MAX_THREADS = 512;
+#ifndef XL_MIN_WAVES
+#define XL_MIN_WAVES 2
+#endif
 
 // ---- launchers (kernels.hip) -------------------------------------------------
 hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t lds_bytes, hipStream_t s);
