@@ -195,11 +195,15 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         }
     };
 
-    // ---- input stager: float4 items = 4 channels of one pixel, NCHW -> [group][row][col][4]
+    // ---- input stager: float4 items = 4 channels of one pixel, NCHW -> [group][row][col][4].
+    // Loads use a uniform base (first channel of the chunk) plus a 32-bit per-lane offset and are
+    // issued unconditionally with clamped offsets; pixels outside the image and channels past Cin
+    // are masked when the item is written to LDS (a select right after the load would stall on it).
     const int HW = P.H * P.W;
     const int plane = P.ih * P.iw;
     const int x_items = STAGE_X ? g.chunk_kg * M::GPS * plane : 0;
-    int pixoff[STAGE_X ? STAGE_ITEMS : 1], chan[STAGE_X ? STAGE_ITEMS : 1];
+    unsigned xoff[STAGE_X ? STAGE_ITEMS : 1];     // chan * HW + pixel offset inside the image
+    int chan[STAGE_X ? STAGE_ITEMS : 1];          // first channel of the item inside the chunk, -1 = zero item
     f32x4 xst[STAGE_X ? STAGE_ITEMS : 1];
     if constexpr (STAGE_X) {
 #pragma unroll
@@ -209,28 +213,38 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             const int r = rem / P.iw, cc = rem - r * P.iw;
             const int gy = iy0 + r, gx = ix0 + cc;
             const bool in = item < x_items && gy >= 0 && gy < P.H && gx >= 0 && gx < P.W;
-            pixoff[i] = in ? gy * P.W + gx : -1;
-            chan[i] = gr * 4;
+            chan[i] = in ? gr * 4 : -1;
+            xoff[i] = in ? (unsigned)(gr * 4 * HW + gy * P.W + gx) : 0u;
         }
     }
     auto load_x = [&](int c0) {
         if constexpr (STAGE_X) {
+            const float *__restrict__ cbase = ximg + (size_t)c0 * HW;
+            const int last = P.Cin - 1 - c0;            // last valid channel relative to the chunk
 #pragma unroll
             for (int i = 0; i < STAGE_ITEMS; ++i) {
+                if (i * nthreads < x_items) {           // uniform: skips item slots no thread uses
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int cc = c0 + chan[i] + j;
-                    xst[i][j] = (pixoff[i] >= 0 && cc < P.Cin) ? ximg[cc * HW + pixoff[i]] : 0.f;
+                    for (int j = 0; j < 4; ++j) {
+                        // channels past Cin re-read the last valid one (masked at the store)
+                        const int over = max(0, max(chan[i], 0) + j - last);
+                        xst[i][j] = cbase[xoff[i] + (unsigned)((j - over) * HW)];
+                    }
                 }
             }
         }
     };
-    auto store_x = [&](float *dst) {
+    auto store_x = [&](float *dst, int c0) {
         if constexpr (STAGE_X) {
 #pragma unroll
             for (int i = 0; i < STAGE_ITEMS; ++i) {
                 const int item = i * nthreads + tid;
-                if (item < x_items) *(f32x4 *)(dst + item * 4) = xst[i];
+                if (item < x_items) {
+                    f32x4 v;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = (chan[i] >= 0 && c0 + chan[i] + j < P.Cin) ? xst[i][j] : 0.f;
+                    *(f32x4 *)(dst + item * 4) = v;
+                }
             }
         }
     };
@@ -241,7 +255,7 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #endif
     load_x(0);
     load_w(0);
-    store_x(buf);
+    store_x(buf, 0);
     store_w(buf + g.w_off);
     __syncthreads();
     for (int ch = 0; ch < nchunks; ++ch) {
@@ -269,7 +283,7 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         long long t2 = clock64();
 #endif
         if (more) {
-            store_x(nxt);
+            store_x(nxt, (kg0 + g.chunk_kg) * M::KC);
             store_w(nxt + g.w_off);
         }
         __syncthreads();
@@ -352,11 +366,7 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
                     if (c.relu) v = fmaxf(v, 0.f);
                     if constexpr (HAS_SC) v += sv[q * 4 + i];
                     if (relu_out) v = fmaxf(v, 0.f);
-#ifdef XL_EXPERIMENT_NO_STORE
-                    if (pv && cb + i < c.cout && v == 12345.678f) yn[(cb + i) * plane + pix] = v;
-#else
                     if (pv && cb + i < c.cout) yn[(cb + i) * plane + pix] = v;
-#endif
                 }
             }
         }
