@@ -87,7 +87,7 @@ def cpu_baseline(cfg, W, np, budget_s=15.0):
     sample_n = max(1, min(n, 8))
     wl = W.config(cfg, n=sample_n)
     x, params = W.make_tensors(wl)
-    xlo.forward(wl, x[:1].repeat(sample_n, axis=0) if False else x, params)        # warm caches / build lib
+    xlo.forward(wl, x, params)        # warm-up pass (also builds the C library if needed)
     reps, t_total = 0, 0.0
     while t_total < budget_s and reps < 50:
         t0 = time.perf_counter()
@@ -104,7 +104,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=5, help="BASELINE config number 1..5 timed as the headline")
-    ap.add_argument("--all", action="store_true", help="also time the other configs (reported under 'blocks')")
+    ap.add_argument("--headline-only", action="store_true", help="skip the per-config table reported under 'blocks'")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one 256 MiB copy (calibration), then 3 fused and 3 unfused steps")
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident) instead of rotating")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -122,6 +124,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; libxl has no CPU path", file=sys.stderr)
         sys.exit(2)
+
+    if args.traffic_probe:
+        traffic_probe(args.workload, torch, np, W, Session)
+        return
 
     res, s, wl, x, params = bench_workload(args.workload, args.steps, args.warmup, torch, np, W, Session,
                                            cold=not args.warm)
@@ -145,7 +151,7 @@ def main():
                           "hardware": "TITAN Xp / Tesla P4, vs cuDNN v7"},
         "roofline": roof,
     }
-    if args.all:
+    if not args.headline_only:
         blocks = []
         for c in (1, 2, 3, 4, 5):
             if c == args.workload:
@@ -157,6 +163,42 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload, W, np)
     print(json.dumps(out))
+
+
+def traffic_probe(cfg, torch, np, W, Session):
+    """Work for the two counter passes (FETCH_SIZE, WRITE_SIZE): a copy of known size to scale the
+    counters by, then the fused and the unfused path on cold buffers."""
+    n = 64 << 20
+    a = torch.ones(n, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    wl = W.config(cfg)
+    x, params = W.make_tensors(wl)
+    s = Session(wl, x, params)
+    for fused in (True, False):
+        for _ in range(3):
+            xs, ys = s.x.clone(), torch.empty_like(s.y)
+            torch.cuda.synchronize()
+            s.run(fused, xs, ys)
+            torch.cuda.synchronize()
+    groups = [s.plan.query(g) for g in range(s.plan.num_groups)]
+    print(json.dumps({"probe": wl.name, "copy_bytes_read": n * 4, "copy_bytes_written": n * 4,
+                      "alg_bytes_fused": sum(g["bytes_fused"] for g in groups),
+                      "alg_bytes_unfused": sum(g["bytes_unfused"] for g in groups)}))
+
+
+def measured_traffic(kernel_name):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for ln in open(path):
+        f = ln.split()
+        if len(f) >= 3 and f[0] == kernel_name and not ln.startswith("#"):
+            return float(f[1]) + float(f[2])
+    return None
 
 
 def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
@@ -191,11 +233,11 @@ def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
     if t_m >= t_h:
         ach = g["flops"] / ms / 1e9
         return {"bound": "mfma", "achieved": ach, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_FP32_PEAK_TFLOPS, "traffic": None, "kernel": name, "kernel_ms": ms,
+                "frac": ach / MFMA_FP32_PEAK_TFLOPS, "traffic": measured_traffic(name), "kernel": name, "kernel_ms": ms,
                 "flops_per_launch": g["flops"], "bytes_per_launch": g["bytes_fused"]}
     ach = g["bytes_fused"] / ms / 1e6
     return {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-            "traffic": None, "kernel": name, "kernel_ms": ms,
+            "traffic": measured_traffic(name), "kernel": name, "kernel_ms": ms,
             "flops_per_launch": g["flops"], "bytes_per_launch": g["bytes_fused"]}
 
 
