@@ -108,6 +108,7 @@ typedef struct xl_options {
     int force_cout_split;   /* >0: fix how many workgroups share one tile's output channels   */
     int paper_tuner_only;   /* 1: restrict candidates to the paper's square common-factor
                                (tile, grid) pairs (section 3.2)                               */
+    int force_threads;      /* >0: fix the workgroup size (256 or 512) of every block         */
 } xl_options;
 
 /* What the planner decided for one block (all sizes in elements unless named bytes). */
@@ -179,6 +180,19 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights,
  */
 xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
                  void *workspace, void *stream, int fused);
+
+/*
+ * Measured tuning (paper section 3.2: a tuning tool searches tile sizes because the best one is a
+ * trade-off the data dependency alone does not settle).  For every convolution block, in both
+ * execution modes, times the planner's ranked candidates (tile, workgroup size, wave layout,
+ * output-channel split) on the device with the caller's buffers and keeps the fastest; afterwards
+ * xl_plan_query reports the adopted tiles.  Needs xl_prepare on this workspace first.  Contents of
+ * the tensors do not matter but every graph input/output pointer must be valid; outputs and the
+ * workspace intermediates are overwritten.  Unlike xl_run this call SYNCHRONISES the stream
+ * repeatedly; call it once, outside any timed region.  reps < 1 means 3 timed launches per candidate.
+ */
+xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors,
+                  void *workspace, void *stream, int reps);
 
 /* Number of kernel launches one xl_run issues in the given mode. */
 int xl_plan_num_launches(const xl_plan *plan, int fused);

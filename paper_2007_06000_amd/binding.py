@@ -26,7 +26,7 @@ MODES = {"single": XL_SINGLE, "straight": XL_STRAIGHT, "split": XL_SPLIT, "merge
 # every symbol include/xl.h declares
 EXPORTS = [
     "xl_plan_create", "xl_plan_destroy", "xl_plan_num_groups", "xl_plan_query", "xl_plan_workspace_bytes",
-    "xl_prepare", "xl_run", "xl_plan_num_launches", "xl_tuner_candidates", "xl_required_extent",
+    "xl_prepare", "xl_run", "xl_tune", "xl_plan_num_launches", "xl_tuner_candidates", "xl_required_extent",
     "xl_strerror", "xl_plan_last_error", "xl_version",
 ]
 
@@ -50,7 +50,8 @@ class xl_group(ctypes.Structure):
 class xl_options(ctypes.Structure):
     _fields_ = [("lds_budget_bytes", ctypes.c_int), ("num_cus", ctypes.c_int),
                 ("force_tile_h", ctypes.c_int), ("force_tile_w", ctypes.c_int),
-                ("force_cout_split", ctypes.c_int), ("paper_tuner_only", ctypes.c_int)]
+                ("force_cout_split", ctypes.c_int), ("paper_tuner_only", ctypes.c_int),
+                ("force_threads", ctypes.c_int)]
 
 
 class xl_group_info(ctypes.Structure):
@@ -103,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.xl_prepare.restype = i
         L.xl_run.argtypes = [vp, ctypes.POINTER(vp), i, vp, vp, i]
         L.xl_run.restype = i
+        L.xl_tune.argtypes = [vp, ctypes.POINTER(vp), i, vp, vp, i]
+        L.xl_tune.restype = i
         L.xl_plan_num_launches.argtypes = [vp, i]
         L.xl_plan_num_launches.restype = i
         L.xl_tuner_candidates.argtypes = [i, ctypes.POINTER(i), ctypes.POINTER(i), i]
@@ -221,3 +224,10 @@ class Plan:
             arr[t] = p
         self._check(lib().xl_run(self.handle, arr, self.ntensors, ctypes.c_void_p(workspace_ptr),
                                  ctypes.c_void_p(stream), int(fused)))
+
+    def tune(self, tensor_ptrs: Dict[int, int], workspace_ptr: int, stream: int = 0, reps: int = 3):
+        arr = (ctypes.c_void_p * self.ntensors)()
+        for t, p in tensor_ptrs.items():
+            arr[t] = p
+        self._check(lib().xl_tune(self.handle, arr, self.ntensors, ctypes.c_void_p(workspace_ptr),
+                                  ctypes.c_void_p(stream), int(reps)))

@@ -178,6 +178,70 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, vo
     return XL_OK;
 }
 
+// Enqueue one step.  Shared by xl_run and xl_tune.
+static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void *const *tensors, char *ws,
+                             hipStream_t s)
+{
+    xl_plan *mp = const_cast<xl_plan *>(plan);       // only the error string is written
+    auto base = [&](int t) -> char * {
+        const xl::Storage &sg = plan->storage[t];
+        if (sg.external) return static_cast<char *>(const_cast<void *>(tensors[sg.root]));
+        return ws + sg.offset;
+    };
+    char *x = base(st.x_id), *y = base(st.y_id);
+    if (!x || !y) {
+        mp->error = "a graph input or output pointer is NULL";
+        return XL_E_NULL;
+    }
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) % 16) {
+        mp->error = "tensor pointers must be 16-byte aligned";
+        return XL_E_ALIGN;
+    }
+    hipError_t e = hipSuccess;
+    if (st.type == xl::STEP_BLOCK) {
+        xl::BlockParams p = st.bp;
+        p.x = reinterpret_cast<const float *>(x);
+        p.y = reinterpret_cast<float *>(y);
+        p.sc = nullptr;
+        if (st.sc_id >= 0) {
+            p.sc = reinterpret_cast<const float *>(base(st.sc_id));
+            if (!p.sc) return XL_E_NULL;
+        }
+        xl::ConvW *cw[3] = {&p.c1, &p.c2[0], &p.c2[1]};
+        for (int i = 0; i < 3; ++i) {
+            if (st.conv_layer[i] < 0) continue;
+            cw[i]->wp = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].offset);
+            cw[i]->aff = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].aff_offset);
+        }
+        e = xl::launch_block(st.variant, p, st.threads, (size_t)st.lds_bytes, s);
+    } else if (st.type == xl::STEP_MAXPOOL) {
+        const xl::Storage &ys = plan->storage[st.y_id];
+        e = xl::launch_maxpool(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N, st.C, st.H,
+                               st.W, st.Ho, st.Wo, st.k, st.stride, st.pad, ys.ctot, ys.coff, s);
+    } else if (st.type == xl::STEP_ADD) {
+        char *b = base(st.b_id);
+        if (!b) return XL_E_NULL;
+        if (plan->storage[st.y_id].root != st.y_id) {
+            mp->error = "add writing into a concat slice is not supported";
+            return XL_E_UNSUPPORTED;
+        }
+        e = xl::launch_add(reinterpret_cast<const float *>(x), reinterpret_cast<const float *>(b),
+                           reinterpret_cast<float *>(y), st.count, st.relu, s);
+    } else if (st.type == xl::STEP_GAP) {
+        if (plan->storage[st.y_id].root != st.y_id) {
+            mp->error = "global pooling writing into a concat slice is not supported";
+            return XL_E_UNSUPPORTED;
+        }
+        e = xl::launch_gap(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N * st.C,
+                           st.H * st.W, s);
+    }
+    if (e != hipSuccess) {
+        mp->error = std::string("kernel launch failed: ") + hipGetErrorString(e);
+        return XL_E_LAUNCH;
+    }
+    return XL_OK;
+}
+
 xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors, void *workspace, void *stream,
                  int fused)
 {
@@ -186,67 +250,89 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors, 
     if (ntensors < (int)plan->shapes.size()) return XL_E_GRAPH;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    xl_plan *mp = const_cast<xl_plan *>(plan);       // only the error string is written
-    auto base = [&](int t) -> char * {
-        const xl::Storage &st = plan->storage[t];
-        if (st.external) return static_cast<char *>(const_cast<void *>(tensors[st.root]));
-        return ws + st.offset;
-    };
     const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
     for (const xl::Step &st : steps) {
-        char *x = base(st.x_id), *y = base(st.y_id);
-        if (!x || !y) {
-            mp->error = "a graph input or output pointer is NULL";
-            return XL_E_NULL;
-        }
-        if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) % 16) {
-            mp->error = "tensor pointers must be 16-byte aligned";
-            return XL_E_ALIGN;
-        }
-        hipError_t e = hipSuccess;
-        if (st.type == xl::STEP_BLOCK) {
-            xl::BlockParams p = st.bp;
-            p.x = reinterpret_cast<const float *>(x);
-            p.y = reinterpret_cast<float *>(y);
-            p.sc = nullptr;
-            if (st.sc_id >= 0) {
-                p.sc = reinterpret_cast<const float *>(base(st.sc_id));
-                if (!p.sc) return XL_E_NULL;
-            }
-            xl::ConvW *cw[3] = {&p.c1, &p.c2[0], &p.c2[1]};
-            for (int i = 0; i < 3; ++i) {
-                if (st.conv_layer[i] < 0) continue;
-                cw[i]->wp = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].offset);
-                cw[i]->aff = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].aff_offset);
-            }
-            e = xl::launch_block(st.variant, p, st.threads, (size_t)st.lds_bytes, s);
-        } else if (st.type == xl::STEP_MAXPOOL) {
-            const xl::Storage &ys = plan->storage[st.y_id];
-            e = xl::launch_maxpool(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N, st.C, st.H,
-                                   st.W, st.Ho, st.Wo, st.k, st.stride, st.pad, ys.ctot, ys.coff, s);
-        } else if (st.type == xl::STEP_ADD) {
-            char *b = base(st.b_id);
-            if (!b) return XL_E_NULL;
-            if (plan->storage[st.y_id].root != st.y_id) {
-                mp->error = "add writing into a concat slice is not supported";
-                return XL_E_UNSUPPORTED;
-            }
-            e = xl::launch_add(reinterpret_cast<const float *>(x), reinterpret_cast<const float *>(b),
-                               reinterpret_cast<float *>(y), st.count, st.relu, s);
-        } else if (st.type == xl::STEP_GAP) {
-            if (plan->storage[st.y_id].root != st.y_id) {
-                mp->error = "global pooling writing into a concat slice is not supported";
-                return XL_E_UNSUPPORTED;
-            }
-            e = xl::launch_gap(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N * st.C,
-                               st.H * st.W, s);
-        }
-        if (e != hipSuccess) {
-            mp->error = std::string("kernel launch failed: ") + hipGetErrorString(e);
-            return XL_E_LAUNCH;
-        }
+        xl_status rc = launch_step(plan, st, tensors, ws, s);
+        if (rc != XL_OK) return rc;
     }
     return XL_OK;
+}
+
+xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void *workspace, void *stream, int reps)
+{
+    if (!plan || !tensors || !workspace) return XL_E_NULL;
+    if (plan->prepared_ws != workspace) return XL_E_STATE;
+    if (ntensors < (int)plan->shapes.size()) return XL_E_GRAPH;
+    if (reps < 1) reps = 3;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        plan->error = "cannot create timing events";
+        return XL_E_DEVICE;
+    }
+    xl_status rc = XL_OK;
+    for (int pass = 0; pass < 2 && rc == XL_OK; ++pass) {
+        std::vector<xl::Step> &steps = pass == 0 ? plan->fused_steps : plan->unfused_steps;
+        for (xl::Step &st : steps) {
+            if (st.type != xl::STEP_BLOCK || st.alts.size() < 2) {
+                // still run the step once so that later blocks time on produced data
+                rc = launch_step(plan, st, tensors, ws, s);
+                if (rc != XL_OK) break;
+                continue;
+            }
+            int best = 0;
+            float best_ms = 0.f;
+            for (size_t a = 0; a < st.alts.size() && rc == XL_OK; ++a) {
+                rc = launch_step(plan, st.alts[a], tensors, ws, s);         // warm-up (code, filters in L2)
+                if (rc != XL_OK) break;
+                float t_min = 1e30f;
+                for (int r = 0; r < reps && rc == XL_OK; ++r) {
+                    (void)hipEventRecord(e0, s);
+                    rc = launch_step(plan, st.alts[a], tensors, ws, s);
+                    (void)hipEventRecord(e1, s);
+                    if (hipEventSynchronize(e1) != hipSuccess) {
+                        plan->error = "a candidate kernel failed while tuning";
+                        rc = XL_E_LAUNCH;
+                        break;
+                    }
+                    float ms = 0.f;
+                    (void)hipEventElapsedTime(&ms, e0, e1);
+                    t_min = ms < t_min ? ms : t_min;
+                }
+                if (rc == XL_OK && (a == 0 || t_min < best_ms)) {
+                    best = (int)a;
+                    best_ms = t_min;
+                }
+            }
+            if (rc != XL_OK) break;
+            // adopt the winner (keep the candidate list for a later re-tune)
+            std::vector<xl::Step> alts;
+            std::vector<xl_group_info> infos;
+            alts.swap(st.alts);
+            infos.swap(st.alt_info);
+            const int group = st.group;
+            st = alts[best];
+            st.group = group;
+            st.alts.swap(alts);
+            st.alt_info.swap(infos);
+            if (pass == 0 && group >= 0 && group < (int)plan->groups.size()) {
+                xl_group_info &gi = plan->groups[group].info;
+                const xl_group_info &src = st.alt_info[best];
+                gi.tile_h = src.tile_h; gi.tile_w = src.tile_w;
+                gi.mid_h = src.mid_h; gi.mid_w = src.mid_w;
+                gi.in_h = src.in_h; gi.in_w = src.in_w;
+                gi.tiles_y = src.tiles_y; gi.tiles_x = src.tiles_x;
+                gi.cout_split = src.cout_split; gi.workgroups = src.workgroups;
+                gi.threads = src.threads; gi.lds_bytes = src.lds_bytes;
+                gi.workgroups_per_cu = src.workgroups_per_cu; gi.chunk_channels = src.chunk_channels;
+                gi.flops_executed = src.flops_executed; gi.redundancy = src.redundancy;
+            }
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
 }
 
 }  // extern "C"

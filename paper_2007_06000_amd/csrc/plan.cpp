@@ -6,7 +6,9 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <set>
+#include <tuple>
 
 namespace xl {
 
@@ -171,9 +173,10 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     c.flops_exec = tiles * (b.kind == KIND_SINGLE ? 1 : c.csplit) * s1 + tiles * c.csplit * flops2;
 }
 
-static Choice search(const BlockSpec &b, const xl_plan &pl)
+static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &lds_rejected)
 {
     Choice best;
+    std::map<std::tuple<int, int, int, int>, Choice> per_key;     // best per (variant, threads, tile)
     const std::vector<int> ths = tile_candidates(b.Ho), tws = tile_candidates(b.Wo);
     std::vector<std::pair<int, int>> tiles;
     if (pl.opts.force_tile_h > 0 && pl.opts.force_tile_w > 0) {
@@ -197,6 +200,7 @@ static Choice search(const BlockSpec &b, const xl_plan &pl)
         const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
         const int taps1 = b.c1.k * b.c1.k;
         for (int threads : {256, 512}) {
+            if (pl.opts.force_threads > 0 && pl.opts.force_threads != threads) continue;
             const int nw = threads / 64;
             for (int wr = 1; wr <= nw; wr *= 2) {
                 const int wg_rt = wr * v.nrt1;
@@ -293,13 +297,21 @@ static Choice search(const BlockSpec &b, const xl_plan &pl)
                                 evaluate(b, pl, c);
                                 c.ok = true;
                                 if (!best.ok || c.cost < best.cost) best = c;
+                                auto key = std::make_tuple(v.id, threads, th, tw);
+                                auto it = per_key.find(key);
+                                if (it == per_key.end() || c.cost < it->second.cost) per_key[key] = c;
                             }
                 }
             }
         }
     }
-    if (!best.ok) best.lds_rejected = any_lds_reject;
-    return best;
+    lds_rejected = !best.ok && any_lds_reject;
+    // ranked list: the model's best first, then the best of other (variant, threads, tile) combinations
+    std::vector<Choice> ranked;
+    for (auto &kv : per_key) ranked.push_back(kv.second);
+    std::sort(ranked.begin(), ranked.end(), [](const Choice &a, const Choice &b) { return a.cost < b.cost; });
+    if (ranked.size() > (size_t)MAX_ALTERNATIVES) ranked.resize(MAX_ALTERNATIVES);
+    return ranked;
 }
 
 // ----------------------------------------------------------------------------
@@ -487,10 +499,28 @@ struct Builder {
     xl_status make_block_step(const BlockSpec &b, int x_id, int y_id, int sc_id, int coff1, Step &st, Choice &ch,
                               const std::string &what)
     {
-        ch = search(b, pl);
-        if (!ch.ok)
-            return fail(ch.lds_rejected ? XL_E_LDS_BUDGET : XL_E_UNSUPPORTED,
-                        what + (ch.lds_rejected ? ": no tile fits the LDS budget" : ": no kernel variant covers this block"));
+        bool lds_rejected = false;
+        std::vector<Choice> ranked = search(b, pl, lds_rejected);
+        if (ranked.empty())
+            return fail(lds_rejected ? XL_E_LDS_BUDGET : XL_E_UNSUPPORTED,
+                        what + (lds_rejected ? ": no tile fits the LDS budget" : ": no kernel variant covers this block"));
+        ch = ranked[0];
+        fill_step(b, ch, x_id, y_id, sc_id, coff1, st);
+        // the other candidates, for xl_tune to time on the device
+        for (size_t i = 0; i < ranked.size(); ++i) {
+            Step alt;
+            fill_step(b, ranked[i], x_id, y_id, sc_id, coff1, alt);
+            xl_group_info gi;
+            memset(&gi, 0, sizeof gi);
+            fill_info(gi, b, ranked[i]);
+            st.alts.push_back(alt);
+            st.alt_info.push_back(gi);
+        }
+        return XL_OK;
+    }
+
+    void fill_step(const BlockSpec &b, const Choice &ch, int x_id, int y_id, int sc_id, int coff1, Step &st)
+    {
         st = Step{};
         st.type = STEP_BLOCK;
         st.variant = ch.v.id;
@@ -564,7 +594,6 @@ struct Builder {
         p.lds_buf_off = ch.mid_floats;
         p.buf_stride = ch.buf_floats;
         p.w_off1 = ch.w_off1;
-        return XL_OK;
     }
 
     void fill_info(xl_group_info &gi, const BlockSpec &b, const Choice &ch) const
@@ -763,6 +792,7 @@ struct Builder {
         xl_status s = make_block_step(b, t_in, y_id, sc_id, 0, st, ch, at.substr(0, at.size() - 2));
         if (s != XL_OK) return s;
         fill_info(gi, b, ch);
+        st.group = (int)pl.groups.size();
         pl.fused_steps.push_back(st);
         return XL_OK;
     }
@@ -817,6 +847,7 @@ struct Builder {
                     Step st;
                     s = single_step(li, st, &gp.info);
                     if (s != XL_OK) return s;
+                    st.group = (int)pl.groups.size();
                     pl.fused_steps.push_back(st);
                 }
             } else {

@@ -46,6 +46,11 @@ struct Step {
     int N, C, H, W, Ho, Wo, k, stride, pad, relu;
     int b_id;
     long long count;
+    // tuning: the planner's ranked candidates for this block (alts[0] is the model's choice) with
+    // the tile facts each would report, and the fusion block whose info the selection updates
+    int group = -1;
+    std::vector<Step> alts;
+    std::vector<xl_group_info> alt_info;
 };
 
 struct GroupPlan {

@@ -14,7 +14,8 @@ from .binding import Plan
 
 
 class Session:
-    def __init__(self, workload, x: np.ndarray, params: Dict[int, dict], device: int = 0, **options):
+    def __init__(self, workload, x: np.ndarray, params: Dict[int, dict], device: int = 0, tune: bool = False,
+                 **options):
         if not torch.cuda.is_available():
             raise RuntimeError("xl needs a GPU: libxl has no CPU path")
         self.dev = torch.device("cuda", device)
@@ -35,6 +36,9 @@ class Session:
         assert self.workspace.data_ptr() % 256 == 0
         self.plan.prepare(ptrs, self.workspace.data_ptr(), self.stream)
         self.tensor_ptrs = {workload.input_id: self.x.data_ptr(), workload.output_id: self.y.data_ptr()}
+        if tune:
+            self.plan.tune(self.tensor_ptrs, self.workspace.data_ptr(), self.stream)
+            torch.cuda.synchronize(self.dev)
 
     @property
     def stream(self) -> int:

@@ -114,3 +114,19 @@ def test_single_convs():
                W.single_conv(2, 20, 9, 11, 24, 3, stride=1, pad=1, bias=False, bn=True, relu=False),
                W.single_conv(1, 8, 7, 7, 8, 1, relu=False)):
         run_both(wl)
+
+
+@pytest.mark.parametrize("cfg,kw", [(1, {}), (2, {"n": 2, "hw": 20}), (3, {}), (4, {"n": 2, "hw": 28}),
+                                    (5, {"n": 2, "hw": 95, "classes": 40})])
+def test_tuned_plans_match_the_oracle(cfg, kw):
+    """xl_tune swaps in other candidates (tiles, workgroup sizes, splits): results must not change."""
+    from paper_2007_06000_amd.session import Session
+    wl = W.config(cfg, **kw)
+    x, params = W.make_tensors(wl)
+    ref = xlo.forward(wl, x, params)
+    s = Session(wl, x, params, tune=True)
+    for fused in (True, False):
+        print(f"[case] tuned {wl.name} fused={fused}", flush=True)
+        check(s.output(fused), ref, f"tuned {wl.name} fused={fused}")
+    q = s.plan.query(0)
+    assert q["lds_bytes"] <= 160 * 1024 and q["workgroups"] > 0
