@@ -688,39 +688,81 @@ hipError_t launch_pack_affine(const float *scale, const float *shift, f32x4 *out
 // ----------------------------------------------------------------------------
 // element-wise layers of the unfused path
 // ----------------------------------------------------------------------------
+// one thread per output element; blockIdx.x = image * C + channel, blockIdx.y = block of pixels
+// (32-bit index math only)
 __global__ void maxpool_kernel(const float *__restrict__ x, float *__restrict__ y, int C, int H, int W, int Ho, int Wo,
-                               int k, int stride, int pad, int Cy, int coff, long long total)
+                               int k, int stride, int pad, int Cy, int coff)
 {
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int ox = (int)(idx % Wo);
-    long long r = idx / Wo;
-    const int oy = (int)(r % Ho);
-    r /= Ho;
-    const int c = (int)(r % C);
-    const int n = (int)(r / C);
-    const float *xc = x + ((size_t)n * C + c) * H * W;
+    const int idx = blockIdx.y * blockDim.x + threadIdx.x;
+    if (idx >= Ho * Wo) return;
+    const int oy = idx / Wo, ox = idx - oy * Wo;
+    const int plane = blockIdx.x;
+    const int n = plane / C, c = plane - n * C;
+    const float *xc = x + (size_t)plane * H * W;
+    const int y0 = oy * stride - pad, x0 = ox * stride - pad;
     float m = -FLT_MAX;
     for (int u = 0; u < k; ++u) {
-        const int yy = oy * stride - pad + u;
+        const int yy = y0 + u;
         if (yy < 0 || yy >= H) continue;
         for (int v = 0; v < k; ++v) {
-            const int xx = ox * stride - pad + v;
+            const int xx = x0 + v;
             if (xx < 0 || xx >= W) continue;
-            m = fmaxf(m, xc[(size_t)yy * W + xx]);
+            m = fmaxf(m, xc[yy * W + xx]);
         }
     }
-    y[(((size_t)n * Cy + coff + c) * Ho + oy) * Wo + ox] = m;
+    y[((size_t)n * Cy + coff + c) * Ho * Wo + idx] = m;
+}
+
+// Planes that fit LDS: one workgroup per (image, channel) plane copies it into LDS with 16-byte
+// loads (any 4-byte alignment), then every thread pools from LDS.
+typedef float f32x4_unaligned __attribute__((ext_vector_type(4), aligned(4)));
+
+__global__ void __launch_bounds__(256) maxpool_plane_kernel(const float *__restrict__ x, float *__restrict__ y, int C,
+                                                            int H, int W, int Ho, int Wo, int k, int stride, int pad,
+                                                            int Cy, int coff)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int plane = blockIdx.x;
+    const int n = plane / C, c = plane - n * C;
+    const int HW = H * W;
+    const float *xc = x + (size_t)plane * HW;
+    const int n4 = HW >> 2;
+    for (int i = threadIdx.x; i < n4; i += blockDim.x) *(f32x4 *)(lds + i * 4) = *(const f32x4_unaligned *)(xc + i * 4);
+    for (int i = (n4 << 2) + threadIdx.x; i < HW; i += blockDim.x) lds[i] = xc[i];
+    __syncthreads();
+    float *yc = y + ((size_t)n * Cy + coff + c) * Ho * Wo;
+    for (int idx = threadIdx.x; idx < Ho * Wo; idx += blockDim.x) {
+        const int oy = idx / Wo, ox = idx - oy * Wo;
+        const int y0 = oy * stride - pad, x0 = ox * stride - pad;
+        float m = -FLT_MAX;
+        for (int u = 0; u < k; ++u) {
+            const int yy = y0 + u;
+            if (yy < 0 || yy >= H) continue;
+            for (int v = 0; v < k; ++v) {
+                const int xx = x0 + v;
+                if (xx < 0 || xx >= W) continue;
+                m = fmaxf(m, lds[yy * W + xx]);
+            }
+        }
+        yc[idx] = m;
+    }
 }
 
 hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, int Ho, int Wo, int k, int stride,
                           int pad, int Cy, int coff, hipStream_t s)
 {
-    const long long total = (long long)N * C * Ho * Wo;
-    if (total == 0) return hipSuccess;
+    if ((long long)N * C * Ho * Wo == 0) return hipSuccess;
     const int threads = 256;
-    hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)((total + threads - 1) / threads)), dim3(threads), 0, s, x, y, C,
-                       H, W, Ho, Wo, k, stride, pad, Cy, coff, total);
+    const size_t plane_bytes = (size_t)H * W * 4;
+    if (plane_bytes <= 64 * 1024) {
+        hipLaunchKernelGGL(maxpool_plane_kernel, dim3(N * C), dim3(threads), (plane_bytes + 15) / 16 * 16, s, x, y, C, H,
+                           W, Ho, Wo, k, stride, pad, Cy, coff);
+        return hipGetLastError();
+    }
+    const int pix_blocks = (Ho * Wo + threads - 1) / threads;
+    if (pix_blocks > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(maxpool_kernel, dim3(N * C, pix_blocks), dim3(threads), 0, s, x, y, C, H, W, Ho, Wo, k, stride,
+                       pad, Cy, coff);
     return hipGetLastError();
 }
 
