@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 matrix cores
 CACHE_BYTES = 512 << 20        # rotate buffers over more than L2 + Infinity Cache (256 MB)
+TUNE = True                    # xl_tune picks tiles by measurement once, outside the timed region
 
 
 def time_steps(fn, steps, warmup, torch):
@@ -42,7 +43,7 @@ def time_steps(fn, steps, warmup, torch):
 def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True):
     wl = W.config(cfg)
     x, params = W.make_tensors(wl)
-    s = Session(wl, x, params)
+    s = Session(wl, x, params, tune=TUNE)
     in_bytes = x.nbytes
     out_bytes = int(np.prod(wl.shapes[wl.output_id])) * 4
     sets = 1
@@ -109,7 +110,10 @@ def main():
                     help="for rocprofv3 --pmc runs: one 256 MiB copy (calibration), then 3 fused and 3 unfused steps")
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident) instead of rotating")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tune", action="store_true", help="use the planner's cost-model choice without xl_tune")
     args = ap.parse_args()
+    global TUNE
+    TUNE = not args.no_tune
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (images are independent; batch sharding needs no "
               "collective); run with --gpus 1", file=sys.stderr)
@@ -142,7 +146,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "launches_per_step": res["launches_fused"],
-                   "buffers": "rotating (cold)" if not args.warm else "single set (warm)"},
+                   "buffers": "rotating (cold)" if not args.warm else "single set (warm)",
+                   "tiles": "xl_tune (measured)" if TUNE else "cost model"},
         "speedup_vs_unfused": res["speedup_vs_unfused"],
         "ms_per_step_unfused": res["ms_unfused"],
         "hbm_gbs_algorithmic": res["hbm_gbs_alg"],
@@ -176,7 +181,7 @@ def traffic_probe(cfg, torch, np, W, Session):
     torch.cuda.synchronize()
     wl = W.config(cfg)
     x, params = W.make_tensors(wl)
-    s = Session(wl, x, params)
+    s = Session(wl, x, params, tune=TUNE)
     for fused in (True, False):
         for _ in range(3):
             xs, ys = s.x.clone(), torch.empty_like(s.y)
@@ -206,7 +211,7 @@ def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
     kernel launch per step) and price it against the roofline that bounds it."""
     wl_full = W.config(cfg)
     x, params = W.make_tensors(wl_full)
-    s = Session(wl_full, x, params)
+    s = Session(wl_full, x, params, tune=False)
     groups = [s.plan.query(g) for g in range(s.plan.num_groups)]
     if len(groups) == 1:
         g = groups[0]
@@ -220,7 +225,7 @@ def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
         g = groups[gi]
         sub = W.subgraph(wl_full, gi)
         xs, ps = W.make_tensors(sub)
-        ss = Session(sub, xs, ps)
+        ss = Session(sub, xs, ps, tune=TUNE)
         in_b, out_b = xs.nbytes, int(np.prod(sub.shapes[sub.output_id])) * 4
         sets = max(1, min(64, -(-CACHE_BYTES // (in_b + out_b)))) if not args.warm else 1
         bx = [ss.x] + [ss.x.clone() for _ in range(sets - 1)]

@@ -357,16 +357,28 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
                     sv[e] = scn[co * plane + pix];
                 }
             }
+            float res[M::NQ * 4];
 #pragma unroll
-            for (int q = 0; q < M::NQ; ++q) {
-                const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
+            for (int e = 0; e < M::NQ * 4; ++e) {
+                float v = acc[r][p][e] * fa[r][e >> 2][e & 3] + fb[r][e >> 2][e & 3];
+                if (c.relu) v = fmaxf(v, 0.f);
+                if constexpr (HAS_SC) v += sv[e];
+                if (relu_out) v = fmaxf(v, 0.f);
+                res[e] = v;
+            }
+            // one mask for the pixel; the per-channel check is only needed in the last, partial row tile
+            const bool full = (rt0 + r + 1) * MF <= c.cout;
+            if (pv) {
+                if (full) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float v = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
-                    if (c.relu) v = fmaxf(v, 0.f);
-                    if constexpr (HAS_SC) v += sv[q * 4 + i];
-                    if (relu_out) v = fmaxf(v, 0.f);
-                    if (pv && cb + i < c.cout) yn[(cb + i) * plane + pix] = v;
+                    for (int e = 0; e < M::NQ * 4; ++e)
+                        yn[((rt0 + r) * MF + M::quad_row(e >> 2, sub) + (e & 3)) * plane + pix] = res[e];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < M::NQ * 4; ++e) {
+                        const int co = (rt0 + r) * MF + M::quad_row(e >> 2, sub) + (e & 3);
+                        if (co < c.cout) yn[co * plane + pix] = res[e];
+                    }
                 }
             }
         }
