@@ -191,6 +191,7 @@ def traffic_probe(cfg, torch, np, W, Session):
             torch.cuda.synchronize()
     groups = [s.plan.query(g) for g in range(s.plan.num_groups)]
     print(json.dumps({"probe": wl.name, "copy_bytes_read": n * 4, "copy_bytes_written": n * 4,
+                      "launches_fused": s.plan.num_launches(True), "launches_unfused": s.plan.num_launches(False),
                       "alg_bytes_fused": sum(g["bytes_fused"] for g in groups),
                       "alg_bytes_unfused": sum(g["bytes_unfused"] for g in groups)}))
 
