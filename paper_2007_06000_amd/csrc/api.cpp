@@ -183,6 +183,7 @@ static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void
                              hipStream_t s)
 {
     xl_plan *mp = const_cast<xl_plan *>(plan);       // only the error string is written
+    if (plan->shapes[st.x_id].n == 0) return XL_OK;  // empty batch: nothing to do, pointers may be NULL
     auto base = [&](int t) -> char * {
         const xl::Storage &sg = plan->storage[t];
         if (sg.external) return static_cast<char *>(const_cast<void *>(tensors[sg.root]));

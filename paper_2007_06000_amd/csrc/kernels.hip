@@ -621,6 +621,7 @@ hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t l
 {
     BlockKernel k = kernel_of(variant);
     if (!k) return hipErrorInvalidValue;
+    if (p.nblocks <= 0) return hipSuccess;
     const int grid = (p.nblocks + 7) / 8 * 8;
     hipLaunchKernelGGL(k, dim3(grid), dim3(threads), lds_bytes, s, p);
     return hipGetLastError();

@@ -337,6 +337,9 @@ struct Builder {
         for (int t = 0; t < nt; ++t) {
             const xl_shape &s = pl.shapes[t];
             if (s.n < 0 || s.c <= 0 || s.h <= 0 || s.w <= 0) return fail(XL_E_SHAPE, "tensor " + std::to_string(t) + ": non-positive extent");
+            // kernels index inside one image with 32-bit offsets and count workgroups in an int
+            if ((long long)s.c * s.h * s.w >= (1LL << 31) || (long long)s.n * s.c * s.h * s.w >= (1LL << 40))
+                return fail(XL_E_UNSUPPORTED, "tensor " + std::to_string(t) + ": more than 2^31 elements per image");
         }
         for (int li = 0; li < nl; ++li) {
             const xl_layer &L = pl.layers[li];

@@ -120,3 +120,23 @@ def test_error_paths():
     with pytest.raises(B.XlError) as e:
         B.Plan(wl)
     assert e.value.status == B.XL_E_GRAPH
+
+
+def test_oversized_tensors_are_rejected_cleanly():
+    wl = W.single_conv(1, 8, 20000, 20000, 8, 1)            # 3.2e9 elements per image
+    with pytest.raises(B.XlError) as e:
+        B.Plan(wl)
+    assert e.value.status == B.XL_E_UNSUPPORTED
+
+
+def test_empty_batch_plans():
+    p = B.Plan(W.config(3, n=0))
+    assert p.query(0)["workgroups"] == 0
+
+
+def test_paper_tuner_only_restricts_tiles():
+    """With paper_tuner_only the tile is one of the square common-factor tiles of section 3.2."""
+    wl = W.config(4, n=4)                       # 56 = 2*2*2*7
+    q = B.Plan(wl, paper_tuner_only=1).query(0)
+    allowed = {t for t, g in B.xl_tuner_candidates(56)}
+    assert q["tile_h"] == q["tile_w"] and q["tile_h"] in allowed

@@ -130,3 +130,29 @@ def test_tuned_plans_match_the_oracle(cfg, kw):
         check(s.output(fused), ref, f"tuned {wl.name} fused={fused}")
     q = s.plan.query(0)
     assert q["lds_bytes"] <= 160 * 1024 and q["workgroups"] > 0
+
+
+def test_degenerate_shapes():
+    """1x1 images, single channels, tiles larger than the image, odd sizes under stride 2."""
+    for wl in (W.single_conv(1, 1, 1, 1, 1, 1),
+               W.single_conv(3, 1, 5, 7, 1, 3, stride=1, pad=1),
+               W.single_conv(2, 5, 9, 9, 3, 3, stride=2, pad=1),
+               W.straight_generic(1, 3, 3, 3, 5, 3, 1, 1, 4, 3, 1, 1),
+               W.straight_generic(2, 17, 6, 5, 33, 1, 0, 1, 9, 3, 1, 1, bn1=True),
+               W.conv_pool_generic(1, 4, 7, 9, 6, 3, 1, 1, 3, 2, 0),
+               W.conv_pool_generic(2, 3, 12, 12, 8, 3, 0, 2, 2, 2, 0, relu=False),
+               W.config(3, n=1, hw=1, cin=8, s=16, e=32),
+               W.config(4, n=1, hw=2, c=16)):
+        run_both(wl)
+
+
+def test_empty_batch_runs_nothing():
+    import torch
+    from paper_2007_06000_amd.session import Session
+    wl = W.config(3, n=0)
+    x, params = W.make_tensors(wl)
+    s = Session(wl, x, params)
+    s.run(True)
+    s.run(False)
+    torch.cuda.synchronize()
+    assert s.y.numel() == 0
