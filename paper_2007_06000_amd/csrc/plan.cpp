@@ -267,7 +267,10 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                 c.csplit = cs;
                                 c.waves_r2 = w2;
                                 c.vw2 = vw;
-                                int buf = buf1;
+                                // staging buffers: passes with several chunks ping-pong between two buffers
+                                // `multi` floats apart, a single-chunk pass only ever touches the first one
+                                int multi = 0, single = 0;
+                                (ceil_div(nkg1, c.chunk_kg) > 1 ? multi : single) = buf1;
                                 bool fits = true;
                                 if (b.kind == KIND_FUSED2) {
                                     const int NRT2 = nrt2_of(v.mf2), NPT2 = npt2_of(v.mf2);
@@ -281,13 +284,18 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                         const double clk2 = (double)(nw / 4.0) * NRT2 * NPT2 * b.c2[i].k * b.c2[i].k * 4 *
                                                             mfma_clk(v.mf2);
                                         c.chunk_kg2[i] = pick_chunk(nkg2, 0, w2_per_kg, threads, clk2);
-                                        if (c.chunk_kg2[i] < 1) fits = false;
-                                        buf = std::max(buf, c.chunk_kg2[i] * w2_per_kg * 4);
+                                        if (c.chunk_kg2[i] < 1) {
+                                            fits = false;
+                                            break;
+                                        }
+                                        const int bytes2 = c.chunk_kg2[i] * w2_per_kg * 4;
+                                        int &slot = ceil_div(nkg2, c.chunk_kg2[i]) > 1 ? multi : single;
+                                        slot = std::max(slot, bytes2);
                                     }
                                 }
                                 if (!fits) continue;
-                                c.buf_floats = buf;
-                                c.lds_bytes = (c.mid_floats + 2 * buf) * 4;
+                                c.buf_floats = multi;
+                                c.lds_bytes = (c.mid_floats + std::max(single, 2 * multi)) * 4;
                                 if (c.lds_bytes > pl.lds_budget) {
                                     any_lds_reject = true;
                                     continue;
