@@ -165,33 +165,23 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #pragma unroll
     for (int r = 0; r < NRT; ++r) rloc[r] = g.wr * NRT + r;
 
-    // ---- filter stager: a straight copy of [K step][tap][wg_rt][64] float4 out of the packed filter
-    const int wrow = g.wg_rt * 64;
-    const int w_items = g.chunk_kg * T * wrow;
+    // ---- filter stager: [K step][tap][wg_rt][64] float4 rows of the packed filter go straight from
+    // global memory into LDS (LDS-direct 16-byte loads: lane l of a wave writes 16 bytes at the
+    // wave-uniform LDS base + 16*l, no staging registers).  One wave instruction moves one
+    // (K step, tap, row tile) row of 64 float4; the waves share the rows round-robin.  Row tiles past
+    // the filter's last one are skipped: what LDS holds there only feeds accumulator rows that are
+    // never stored.
+    const int wave_id = tid >> 6, lane_id = tid & 63, nwaves_wg = nthreads >> 6;
     const int nkt = c.nkg * T;
-    int w_src[STAGE_W], w_kt[STAGE_W];
-#pragma unroll
-    for (int i = 0; i < STAGE_W; ++i) {
-        const int item = i * nthreads + tid;
-        const int kt = item / wrow, rem = item - kt * wrow;
-        const bool ok = item < w_items && g.rt_base + (rem >> 6) < c.nrt;
-        w_kt[i] = ok ? kt : (1 << 28);
-        w_src[i] = kt * c.nrt * 64 + g.rt_base * 64 + rem;
-    }
-    f32x4 wst[STAGE_W];
-    auto load_w = [&](int kg0) {
-        const f32x4 *base = c.wp + (size_t)kg0 * T * c.nrt * 64;
-#pragma unroll
-        for (int i = 0; i < STAGE_W; ++i) {
-            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            wst[i] = (kg0 * T + w_kt[i] < nkt) ? base[w_src[i]] : z;
-        }
-    };
-    auto store_w = [&](float *dst) {
-#pragma unroll
-        for (int i = 0; i < STAGE_W; ++i) {
-            const int item = i * nthreads + tid;
-            if (item < w_items) *(f32x4 *)(dst + item * 4) = wst[i];
+    auto load_w = [&](float *dst, int kg0) {
+        const int rows = min(g.chunk_kg * T, nkt - kg0 * T) * g.wg_rt;      // rows of 64 float4 in this chunk
+        const f32x4 *base = c.wp + ((size_t)kg0 * T * c.nrt + g.rt_base) * 64 + lane_id;
+        for (int row = wave_id; row < rows; row += nwaves_wg) {
+            const int kt = row / g.wg_rt, rl = row - kt * g.wg_rt;
+            if (g.rt_base + rl < c.nrt)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(base + (kt * c.nrt + rl) * 64),
+                    (__attribute__((address_space(3))) void *)(dst + row * 256), 16, 0, 0);
         }
     };
 
@@ -253,10 +243,10 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #ifdef XL_PHASE_TIMING
     long long t_ld = 0, t_mm = 0, t_st = 0, t_pro = clock64();
 #endif
+    load_w(buf + g.w_off, 0);
     load_x(0);
-    load_w(0);
     store_x(buf, 0);
-    store_w(buf + g.w_off);
+    __builtin_amdgcn_s_waitcnt(0);      // this wave's LDS-direct loads have landed
     __syncthreads();
     for (int ch = 0; ch < nchunks; ++ch) {
         float *cur = buf + (ch & 1) * g.buf_stride;
@@ -268,8 +258,8 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         long long t0 = clock64();
 #endif
         if (more) {
+            load_w(nxt + g.w_off, kg0 + g.chunk_kg);
             load_x((kg0 + g.chunk_kg) * M::KC);
-            load_w(kg0 + g.chunk_kg);
         }
 #ifdef XL_PHASE_TIMING
         long long t1 = clock64();
@@ -282,10 +272,8 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #ifdef XL_PHASE_TIMING
         long long t2 = clock64();
 #endif
-        if (more) {
-            store_x(nxt, (kg0 + g.chunk_kg) * M::KC);
-            store_w(nxt + g.w_off);
-        }
+        if (more) store_x(nxt, (kg0 + g.chunk_kg) * M::KC);
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
 #ifdef XL_PHASE_TIMING
         long long t3 = clock64();

@@ -98,9 +98,9 @@ static int pick_chunk(int nkg, int x_items_per_kg, int w_items_per_kg, int threa
 {
     int cap = nkg;
     if (x_items_per_kg > 0) cap = std::min(cap, STAGE_ITEMS * threads / x_items_per_kg);
-    cap = std::min(cap, STAGE_W * threads / std::max(w_items_per_kg, 1));
+    cap = std::min(cap, MAX_W_CHUNK_BYTES / (16 * std::max(w_items_per_kg, 1)));
     if (cap < 1) return 0;
-    int want = (int)std::ceil(6000.0 / std::max(clk_per_kg, 1.0));
+    int want = (int)std::ceil(8000.0 / std::max(clk_per_kg, 1.0));
     int chunk = std::max(1, std::min(cap, want));
     const int nchunks = ceil_div(nkg, chunk);
     return std::min(cap, ceil_div(nkg, nchunks));       // balance the chunks

@@ -143,7 +143,7 @@ constexpr int nrt2_of(int mf2) { return mf2 == 32 ? 2 : 1; }
 constexpr int npt2_of(int mf2) { return mf2 == 32 ? 1 : 2; }
 
 constexpr int STAGE_ITEMS = 4;      // float4 input items each thread stages per chunk
-constexpr int STAGE_W = 6;          // float4 filter items each thread stages per chunk
+constexpr int MAX_W_CHUNK_BYTES = 40 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
 constexpr int MAX_THREADS = 512;
 constexpr int MAX_ALTERNATIVES = 16;  // candidates per block kept for on-device tuning
 #ifndef XL_MIN_WAVES
