@@ -173,15 +173,18 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     // never stored.
     const int wave_id = tid >> 6, lane_id = tid & 63, nwaves_wg = nthreads >> 6;
     const int nkt = c.nkg * T;
+    // The buffer form of the load is used (not the global/flat one): the compiler then keeps counting
+    // outstanding LDS reads exactly instead of waiting for all of them at every use.
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)c.wp, (short)0, nkt * c.nrt * 1024, 0x00020000);
     auto load_w = [&](float *dst, int kg0) {
         const int rows = min(g.chunk_kg * T, nkt - kg0 * T) * g.wg_rt;      // rows of 64 float4 in this chunk
-        const f32x4 *base = c.wp + ((size_t)kg0 * T * c.nrt + g.rt_base) * 64 + lane_id;
+        const int base = ((kg0 * T * c.nrt + g.rt_base) * 64 + lane_id) * 16;   // byte offset of this lane in row 0
         for (int row = wave_id; row < rows; row += nwaves_wg) {
             const int kt = row / g.wg_rt, rl = row - kt * g.wg_rt;
             if (g.rt_base + rl < c.nrt)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(base + (kt * c.nrt + rl) * 64),
-                    (__attribute__((address_space(3))) void *)(dst + row * 256), 16, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (__attribute__((address_space(3))) void *)(dst + row * 256),
+                                                         16, base + (kt * c.nrt + rl) * 1024, 0, 0, 0);
         }
     };
 
@@ -420,7 +423,7 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 // ----------------------------------------------------------------------------
 // The block kernel
 // ----------------------------------------------------------------------------
-template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int K2A, int K2B, bool SC>
+template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC>
 __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const BlockParams P)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -519,7 +522,6 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
             // ---- S4/S5: sibling convolutions from the LDS tile, heavier one first.  Every pass covers
             // (row waves x NRT2) row tiles by (pixel waves x NPT2) pixel tiles; all waves stream the
             // same filter chunks.
-            constexpr int NRT2 = nrt2_of(MF2), NPT2 = npt2_of(MF2);
             typedef MM<MF2> M2;
             const int sub = lane / MF2, col = lane % MF2;
             const int npt2 = (P.th * P.vw2 + MF2 - 1) / MF2;
@@ -576,9 +578,10 @@ typedef void (*BlockKernel)(const BlockParams);
 static BlockKernel kernel_of(int variant)
 {
     switch (variant) {
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC) \
-    case ID:                                                \
-        return block_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0)>;
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC)                            \
+    case ID:                                                                                       \
+        return block_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2), (NRT2 == 0 ? 1 : NRT2), \
+                            (NPT2 == 0 ? 1 : NPT2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0)>;
         XL_VARIANT_LIST(X)
 #undef X
     }
@@ -588,7 +591,8 @@ static BlockKernel kernel_of(int variant)
 const std::vector<Variant> &variants()
 {
     static const std::vector<Variant> v = {
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC) Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC},
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC) \
+    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC},
         XL_VARIANT_LIST(X)
 #undef X
     };

@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstdio>
 #include <cstring>
 #include <map>
@@ -129,7 +130,7 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     double t2 = 0;
     long long flops2 = 0;
     if (b.kind == KIND_FUSED2) {
-        const int mf2 = v.mf2, NRT2 = nrt2_of(mf2), NPT2 = npt2_of(mf2);
+        const int mf2 = v.mf2, NRT2 = v.nrt2, NPT2 = v.npt2;
         const int npt2 = ceil_div(c.th * c.vw2, mf2);
         const int wg_rt2 = c.waves_r2 * NRT2, wg_pt2 = (nw / c.waves_r2) * NPT2;
         for (int ci = 0; ci < b.n2; ++ci) {
@@ -193,6 +194,10 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     bool any_lds_reject = false;
     for (const Variant &v : variants()) {
         if (v.kind != b.kind || v.k1 != b.c1.k) continue;
+#ifdef XL_DEV_HOOKS     // development builds only: restrict the search to one kernel variant
+        if (const char *only = std::getenv("XL_ONLY_VARIANT"))
+            if (b.kind != KIND_SINGLE && std::atoi(only) != v.id) continue;
+#endif
         if (b.kind == KIND_FUSED2) {
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
@@ -273,7 +278,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                 (ceil_div(nkg1, c.chunk_kg) > 1 ? multi : single) = buf1;
                                 bool fits = true;
                                 if (b.kind == KIND_FUSED2) {
-                                    const int NRT2 = nrt2_of(v.mf2), NPT2 = npt2_of(v.mf2);
+                                    const int NRT2 = v.nrt2, NPT2 = v.npt2;
                                     int max_per = 0;
                                     for (int i = 0; i < b.n2; ++i)
                                         max_per = std::max(max_per, ceil_div(ceil_div(b.c2[i].cout, v.mf2), cs));

@@ -80,67 +80,66 @@ struct Variant {
     int id;
     int kind;
     int mf1, k1, nrt1, npt1;    // stage 1: matrix-core tile, filter size, tiles per wave
-    int mf2;                    // stage 2 matrix-core tile (0 when unused)
+    int mf2, nrt2, npt2;        // stage 2: matrix-core tile, tiles per wave (0 when unused)
     int k2a, k2b;               // stage 2 filter sizes, heavier sibling first (0 = absent)
     int sc;                     // 1: adds a shortcut tensor in the epilogue (merge mode)
 };
 
-// id, kind, MF1, K1, NRT1, NPT1, MF2, K2A, K2B, SC
+// id, kind, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC
 #define XL_VARIANT_LIST(X)                                \
-    X(0, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0)            \
-    X(1, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0)            \
-    X(2, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0)            \
-    X(42, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0)           \
-    X(43, KIND_SINGLE, 32, 1, 1, 3, 0, 0, 0, 0)           \
-    X(44, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0)           \
-    X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0)            \
-    X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0)            \
-    X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0)            \
-    X(6, KIND_SINGLE, 16, 1, 1, 1, 0, 0, 0, 0)            \
-    X(7, KIND_SINGLE, 16, 1, 1, 2, 0, 0, 0, 0)            \
-    X(8, KIND_SINGLE, 16, 1, 3, 2, 0, 0, 0, 0)            \
-    X(9, KIND_SINGLE, 16, 3, 1, 1, 0, 0, 0, 0)            \
-    X(10, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0)           \
+    X(0, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0)            \
+    X(1, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0)            \
+    X(2, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0)            \
+    X(42, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 0, 0)           \
+    X(43, KIND_SINGLE, 32, 1, 1, 3, 0, 0, 0, 0, 0, 0)           \
+    X(44, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0)           \
+    X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0)            \
+    X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0)            \
+    X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0, 0, 0)            \
+    X(6, KIND_SINGLE, 16, 1, 1, 1, 0, 0, 0, 0, 0, 0)            \
+    X(7, KIND_SINGLE, 16, 1, 1, 2, 0, 0, 0, 0, 0, 0)            \
+    X(8, KIND_SINGLE, 16, 1, 3, 2, 0, 0, 0, 0, 0, 0)            \
+    X(9, KIND_SINGLE, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0)            \
+    X(10, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0, 0, 0)           \
     /* split (fire-like): 1x1 -> {3x3, 1x1} */            \
-    X(11, KIND_FUSED2, 32, 1, 1, 1, 32, 3, 1, 0)          \
-    X(12, KIND_FUSED2, 32, 1, 2, 1, 32, 3, 1, 0)          \
-    X(13, KIND_FUSED2, 16, 1, 1, 1, 32, 3, 1, 0)          \
-    X(14, KIND_FUSED2, 16, 1, 1, 2, 32, 3, 1, 0)          \
-    X(15, KIND_FUSED2, 16, 1, 1, 3, 32, 3, 1, 0)          \
-    X(16, KIND_FUSED2, 16, 1, 3, 2, 32, 3, 1, 0)          \
-    X(17, KIND_FUSED2, 16, 1, 1, 1, 16, 3, 1, 0)          \
-    X(18, KIND_FUSED2, 32, 1, 1, 1, 16, 3, 1, 0)          \
+    X(11, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0)          \
+    X(12, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0)          \
+    X(13, KIND_FUSED2, 16, 1, 1, 1, 32, 2, 1, 3, 1, 0)          \
+    X(14, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0)          \
+    X(15, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0)          \
+    X(16, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0)          \
+    X(17, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 1, 0)          \
+    X(18, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0)          \
     /* straight conv -> conv, and merge (with shortcut) */ \
-    X(19, KIND_FUSED2, 32, 3, 2, 1, 32, 3, 0, 0)          \
-    X(20, KIND_FUSED2, 32, 3, 2, 1, 32, 3, 0, 1)          \
-    X(21, KIND_FUSED2, 32, 3, 1, 1, 32, 3, 0, 0)          \
-    X(22, KIND_FUSED2, 32, 3, 1, 1, 32, 3, 0, 1)          \
-    X(23, KIND_FUSED2, 16, 3, 1, 1, 16, 3, 0, 0)          \
-    X(24, KIND_FUSED2, 16, 3, 1, 3, 16, 3, 0, 0)          \
-    X(25, KIND_FUSED2, 16, 3, 1, 1, 16, 3, 0, 1)          \
-    X(26, KIND_FUSED2, 32, 1, 1, 1, 32, 3, 0, 0)          \
-    X(27, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 0, 0)          \
-    X(28, KIND_FUSED2, 32, 3, 1, 1, 32, 1, 0, 0)          \
-    X(29, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 0, 0)          \
-    X(30, KIND_FUSED2, 16, 1, 1, 1, 16, 3, 0, 0)          \
-    X(31, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 0, 0)          \
-    X(32, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 0, 1)          \
-    X(33, KIND_FUSED2, 32, 1, 1, 1, 32, 3, 0, 1)          \
-    X(34, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 0, 1)          \
-    X(35, KIND_FUSED2, 16, 1, 1, 1, 16, 3, 0, 1)          \
+    X(19, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0)          \
+    X(20, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1)          \
+    X(21, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0)          \
+    X(22, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 1)          \
+    X(23, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 3, 0, 0)          \
+    X(24, KIND_FUSED2, 16, 3, 1, 3, 16, 1, 2, 3, 0, 0)          \
+    X(25, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 3, 0, 1)          \
+    X(26, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 0)          \
+    X(27, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 0)          \
+    X(28, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0)          \
+    X(29, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 0)          \
+    X(30, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 0, 0)          \
+    X(31, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 1, 0, 0)          \
+    X(32, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 1)          \
+    X(33, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 1)          \
+    X(34, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 1)          \
+    X(35, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 0, 1)          \
+    /* stage 2 on 16-pixel tiles, 7 per wave: finer padding of small tiles */ \
+    X(45, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 1)          \
+    X(46, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 0)          \
     /* conv -> maxpool */                                 \
-    X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0)             \
-    X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0)             \
-    X(38, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0)             \
-    X(39, KIND_POOL, 32, 3, 2, 1, 0, 0, 0, 0)             \
-    X(40, KIND_POOL, 16, 1, 1, 1, 0, 0, 0, 0)             \
-    X(41, KIND_POOL, 16, 3, 1, 1, 0, 0, 0, 0)
+    X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0)             \
+    X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0)             \
+    X(38, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0)             \
+    X(39, KIND_POOL, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0)             \
+    X(40, KIND_POOL, 16, 1, 1, 1, 0, 0, 0, 0, 0, 0)             \
+    X(41, KIND_POOL, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0)
 
 const std::vector<Variant> &variants();
-
-// Stage-2 tiles per wave are fixed by the matrix-core tile.
-constexpr int nrt2_of(int mf2) { return mf2 == 32 ? 2 : 1; }
-constexpr int npt2_of(int mf2) { return mf2 == 32 ? 1 : 2; }
 
 constexpr int STAGE_ITEMS = 4;      // float4 input items each thread stages per chunk
 constexpr int MAX_W_CHUNK_BYTES = 40 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
