@@ -31,6 +31,7 @@ namespace xl {
 // Development aid: per-workgroup phase timestamps (only in builds with -DXL_PHASE_TIMING).
 #ifdef XL_PHASE_TIMING
 __device__ unsigned long long g_phase[16 * 8192];
+__device__ unsigned long long g_wtrace[8 * 8 * 16 * 4];     // [block][wave][chunk][stamp], stage-1 pass
 #define XL_PHASE(L, i)                                                        \
     do {                                                                      \
         if (threadIdx.x == 0 && (L) < 8192) {                                 \
@@ -156,8 +157,9 @@ struct PassGeom {
 template <int MF, int KS, int NRT, int NPT, bool STAGE_X>
 __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P, const ConvW &c,
                                           const PassGeom &g, const float *bsrc, const int (&off)[NPT], float *buf,
-                                          const float *__restrict__ ximg, int iy0, int ix0)
+                                          const float *__restrict__ ximg, unsigned long long x_bytes, int iy0, int ix0)
 {
+    // ximg: first element of this image of the block input, x_bytes: bytes from there to the end of the tensor
     typedef MM<MF> M;
     constexpr int T = KS * KS;
     const int tid = threadIdx.x, nthreads = blockDim.x;
@@ -166,77 +168,118 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     for (int r = 0; r < NRT; ++r) rloc[r] = g.wr * NRT + r;
 
     // ---- filter stager: [K step][tap][wg_rt][64] float4 rows of the packed filter go straight from
-    // global memory into LDS (LDS-direct 16-byte loads: lane l of a wave writes 16 bytes at the
+    // global memory into LDS (LDS-direct 16-byte buffer loads: lane l of a wave writes 16 bytes at the
     // wave-uniform LDS base + 16*l, no staging registers).  One wave instruction moves one
     // (K step, tap, row tile) row of 64 float4; the waves share the rows round-robin.  Row tiles past
     // the filter's last one are skipped: what LDS holds there only feeds accumulator rows that are
-    // never stored.
-    const int wave_id = tid >> 6, lane_id = tid & 63, nwaves_wg = nthreads >> 6;
+    // never stored.  Everything but the per-lane offset is wave-uniform, so a row costs a handful of
+    // scalar instructions.  (The buffer form of the load is used, not the global/flat one: the
+    // compiler then keeps counting outstanding LDS reads exactly instead of waiting for all of them.)
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves_wg = nthreads >> 6;
     const int nkt = c.nkg * T;
-    // The buffer form of the load is used (not the global/flat one): the compiler then keeps counting
-    // outstanding LDS reads exactly instead of waiting for all of them at every use.
     const __amdgpu_buffer_rsrc_t wrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)c.wp, (short)0, nkt * c.nrt * 1024, 0x00020000);
+    const int w_lane = (tid & 63) * 16;
+    const int w_dkt = nwaves_wg / g.wg_rt, w_drl = nwaves_wg - w_dkt * g.wg_rt;       // row step = nwaves rows
+    const int w_kt0 = wave_id / g.wg_rt, w_rl0 = wave_id - w_kt0 * g.wg_rt;
     auto load_w = [&](float *dst, int kg0) {
-        const int rows = min(g.chunk_kg * T, nkt - kg0 * T) * g.wg_rt;      // rows of 64 float4 in this chunk
-        const int base = ((kg0 * T * c.nrt + g.rt_base) * 64 + lane_id) * 16;   // byte offset of this lane in row 0
-        for (int row = wave_id; row < rows; row += nwaves_wg) {
-            const int kt = row / g.wg_rt, rl = row - kt * g.wg_rt;
+        const int kts = min(g.chunk_kg * T, nkt - kg0 * T);                     // (K step, tap) rows in this chunk
+        const int base = (kg0 * T * c.nrt + g.rt_base) * 1024;                  // byte offset of the chunk's first row
+        int kt = w_kt0, rl = w_rl0;
+        float *d = dst + wave_id * 256;
+        while (kt < kts) {
             if (g.rt_base + rl < c.nrt)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (__attribute__((address_space(3))) void *)(dst + row * 256),
-                                                         16, base + (kt * c.nrt + rl) * 1024, 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (__attribute__((address_space(3))) void *)d, 16, w_lane,
+                                                         base + (kt * c.nrt + rl) * 1024, 0, 0);
+            d += nwaves_wg * 256;
+            kt += w_dkt;
+            rl += w_drl;
+            if (rl >= g.wg_rt) { rl -= g.wg_rt; ++kt; }
         }
     };
 
-    // ---- input stager: float4 items = 4 channels of one pixel, NCHW -> [group][row][col][4].
-    // Loads use a uniform base (first channel of the chunk) plus a 32-bit per-lane offset and are
-    // issued unconditionally with clamped offsets; pixels outside the image and channels past Cin
-    // are masked when the item is written to LDS (a select right after the load would stall on it).
+    // ---- input stager: NCHW -> [group][row][col][4 channels].  A unit is 4 channels x 4 consecutive
+    // pixels of one tile row: four 16-byte buffer loads (one per channel), transposed in registers into
+    // four float4 LDS writes.  Few, wide loads keep the vector-memory queue short; a wave that has to
+    // wait there cannot issue matrix operations either.  The per-lane byte offset of the unit inside
+    // the chunk's first channel group is fixed for the whole pass; the channel is a scalar offset; the
+    // descriptor starts at the chunk's first channel and ends with the tensor, so whatever a unit
+    // touches outside the image (left/right overhang of a row, channels past Cin) is either inside
+    // the allocation or reads as zero, and is masked when the unit is written to LDS -- a select
+    // right after a load would stall on it.
+    typedef unsigned u32x4 __attribute__((vector_size(16)));     // what the 128-bit buffer load returns
     const int HW = P.H * P.W;
     const int plane = P.ih * P.iw;
-    const int x_items = STAGE_X ? g.chunk_kg * M::GPS * plane : 0;
-    unsigned xoff[STAGE_X ? STAGE_ITEMS : 1];     // chan * HW + pixel offset inside the image
-    int chan[STAGE_X ? STAGE_ITEMS : 1];          // first channel of the item inside the chunk, -1 = zero item
-    f32x4 xst[STAGE_X ? STAGE_ITEMS : 1];
+    // Units start at the first tile column that can lie inside the image: a unit that began left of
+    // column 0 of the tensor's very first row would have a negative buffer offset, for which the
+    // hardware returns zeros for all 16 bytes.  The columns before it are padding and are zero-filled.
+    const int xs = max(0, -ix0);
+    const int qpr = (P.iw - xs + 3) >> 2;                          // units per tile row
+    const int upg = P.ih * qpr;                                    // units per channel group
+    const int x_units = STAGE_X ? g.chunk_kg * M::GPS * upg : 0;
+    constexpr int NU = STAGE_X ? STAGE_UNITS : 1;
+    unsigned xoff[NU];          // byte offset of the unit's first pixel in the group's first channel
+    int xdst[NU];               // float offset of that pixel in the LDS chunk
+    int xgrp[NU];               // first channel of the unit inside the chunk
+    unsigned xmask[NU];         // bit k: pixel k lies in the tile; bit 4 + k: and inside the image; bit 8: see xs
+    f32x4 xst[NU][4];
     if constexpr (STAGE_X) {
 #pragma unroll
-        for (int i = 0; i < STAGE_ITEMS; ++i) {
-            const int item = i * nthreads + tid;
-            const int gr = item / plane, rem = item - gr * plane;
-            const int r = rem / P.iw, cc = rem - r * P.iw;
+        for (int i = 0; i < NU; ++i) {
+            const int u = i * nthreads + tid;
+            const int gr = u / upg, rem = u - gr * upg;
+            const int r = rem / qpr, q = rem - r * qpr;
+            const int cc = xs + 4 * q;                              // first tile column of the unit
             const int gy = iy0 + r, gx = ix0 + cc;
-            const bool in = item < x_items && gy >= 0 && gy < P.H && gx >= 0 && gx < P.W;
-            chan[i] = in ? gr * 4 : -1;
-            xoff[i] = in ? (unsigned)(gr * 4 * HW + gy * P.W + gx) : 0u;
+            const bool rowok = gy >= 0 && gy < P.H;
+            unsigned m = (u < x_units && q == 0) ? 0x100u : 0u;     // bit 8: this lane zero-fills the row's left padding
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (u < x_units && cc + k < P.iw) m |= (rowok && gx + k < P.W) ? (0x11u << k) : (1u << k);
+            }
+            xmask[i] = m;
+            xgrp[i] = gr * 4;
+            xdst[i] = (gr * plane + r * P.iw + cc) * 4;
+            xoff[i] = (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4);
         }
     }
-    auto load_x = [&](int c0) {
+    __amdgpu_buffer_rsrc_t xrsrc;
+    auto load_x = [&](int c0) {                    // chunk whose first channel is c0
         if constexpr (STAGE_X) {
-            const float *__restrict__ cbase = ximg + (size_t)c0 * HW;
-            const int last = P.Cin - 1 - c0;            // last valid channel relative to the chunk
+            const unsigned long long skip = (unsigned long long)c0 * HW * 4ull;
+            const unsigned long long left = x_bytes > skip ? x_bytes - skip : 0ull;
+            xrsrc = __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)ximg + skip), (short)0,
+                                                      (int)(unsigned)min(left, 0xffffffffull), 0x00020000);
 #pragma unroll
-            for (int i = 0; i < STAGE_ITEMS; ++i) {
-                if (i * nthreads < x_items) {           // uniform: skips item slots no thread uses
+            for (int i = 0; i < NU; ++i) {
+                if (i * nthreads < x_units) {      // uniform: skips unit slots no thread uses
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        // channels past Cin re-read the last valid one (masked at the store)
-                        const int over = max(0, max(chan[i], 0) + j - last);
-                        xst[i][j] = cbase[xoff[i] + (unsigned)((j - over) * HW)];
-                    }
+                    for (int j = 0; j < 4; ++j)
+                        xst[i][j] = __builtin_bit_cast(f32x4, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(xrsrc, xoff[i], j * HW * 4, 0));
                 }
             }
         }
     };
     auto store_x = [&](float *dst, int c0) {
         if constexpr (STAGE_X) {
+            const int nch = P.Cin - c0;            // channels of the chunk that exist (uniform)
 #pragma unroll
-            for (int i = 0; i < STAGE_ITEMS; ++i) {
-                const int item = i * nthreads + tid;
-                if (item < x_items) {
-                    f32x4 v;
+            for (int i = 0; i < NU; ++i) {
+                if (i * nthreads < x_units) {
+                    const int live = nch - xgrp[i];        // channels of this unit that exist
+                    if (xs > 0 && (xmask[i] & 0x100u)) {
+                        for (int e = 1; e <= xs; ++e) *(f32x4 *)(dst + xdst[i] - 4 * e) = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] = (chan[i] >= 0 && c0 + chan[i] + j < P.Cin) ? xst[i][j] : 0.f;
-                    *(f32x4 *)(dst + item * 4) = v;
+                    for (int k = 0; k < 4; ++k) {
+                        if (xmask[i] & (1u << k)) {
+                            const bool in = (xmask[i] >> (4 + k)) & 1u;
+                            f32x4 v;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) v[j] = (in && j < live) ? xst[i][j][k] : 0.f;
+                            *(f32x4 *)(dst + xdst[i] + 4 * k) = v;
+                        }
+                    }
                 }
             }
         }
@@ -259,10 +302,15 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #ifdef XL_PHASE_TIMING
         if (ch == 0) t_pro = clock64() - t_pro;
         long long t0 = clock64();
+        const int wt_b = logical_block();
+        const bool wt_on = STAGE_X && wt_b < 8 && ch < 16 && (threadIdx.x & 63) == 0;
+        unsigned long long *wt = g_wtrace + ((wt_b * 8 + (threadIdx.x >> 6)) * 16 + ch) * 4;
+        if (wt_on) wt[0] = t0;
 #endif
+        const int c_next = (kg0 + g.chunk_kg) * M::KC;
         if (more) {
             load_w(nxt + g.w_off, kg0 + g.chunk_kg);
-            load_x((kg0 + g.chunk_kg) * M::KC);
+            load_x(c_next);
         }
 #ifdef XL_PHASE_TIMING
         long long t1 = clock64();
@@ -274,9 +322,16 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         }
 #ifdef XL_PHASE_TIMING
         long long t2 = clock64();
+        if (wt_on) wt[1] = t2;
 #endif
-        if (more) store_x(nxt, (kg0 + g.chunk_kg) * M::KC);
+        if (more) store_x(nxt, c_next);
+#ifdef XL_PHASE_TIMING
+        if (wt_on) wt[2] = clock64();
+#endif
         __builtin_amdgcn_s_waitcnt(0);
+#ifdef XL_PHASE_TIMING
+        if (wt_on) wt[3] = clock64();
+#endif
         __syncthreads();
 #ifdef XL_PHASE_TIMING
         long long t3 = clock64();
@@ -480,7 +535,8 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
         }
     }
     XL_PHASE(L, 0);
-    conv_pass<MF1, K1, NRT1, NPT1, true>(acc, P, P.c1, g1, nullptr, off1, buf, ximg, iy0, ix0);
+    conv_pass<MF1, K1, NRT1, NPT1, true>(acc, P, P.c1, g1, nullptr, off1, buf, ximg,
+                                         (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
     XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {
@@ -556,7 +612,7 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
                             const int oy = min(pidx / P.vw2, P.th - 1), ox = min(pidx % P.vw2, P.tw - 1);
                             off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * P.mid_gstride;
                         }
-                        conv_pass<MF2, KS2, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0, 0);
+                        conv_pass<MF2, KS2, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0ull, 0, 0);
                         if (g2.active)
                             store_global<MF2, NRT2, NPT2, SC>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
                                                               p0, P.relu_out);
@@ -828,6 +884,11 @@ hipError_t launch_gap(const float *x, float *y, int NC, int HW, hipStream_t s)
 }  // namespace xl
 
 #ifdef XL_PHASE_TIMING
+extern "C" int xl_debug_read_wtrace(unsigned long long *host, int count)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(xl::g_wtrace), sizeof(unsigned long long) * count);
+}
+
 extern "C" int xl_debug_read_phases(unsigned long long *host, int count)
 {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(xl::g_phase), sizeof(unsigned long long) * count);

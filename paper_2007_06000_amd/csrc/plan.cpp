@@ -95,10 +95,10 @@ static double mfma_clk(int mf) { return mf == 32 ? 64.0 : 32.0; }
 
 // Largest number of K steps per chunk the stagers can hold, shortened so that one chunk keeps
 // the matrix cores busy for a few thousand cycles (amortises the per-chunk barrier) and no more.
-static int pick_chunk(int nkg, int x_items_per_kg, int w_items_per_kg, int threads, double clk_per_kg)
+static int pick_chunk(int nkg, int x_units_per_kg, int w_items_per_kg, int threads, double clk_per_kg)
 {
     int cap = nkg;
-    if (x_items_per_kg > 0) cap = std::min(cap, STAGE_ITEMS * threads / x_items_per_kg);
+    if (x_units_per_kg > 0) cap = std::min(cap, STAGE_UNITS * threads / x_units_per_kg);
     cap = std::min(cap, MAX_W_CHUNK_BYTES / (16 * std::max(w_items_per_kg, 1)));
     if (cap < 1) return 0;
     int want = (int)std::ceil(8000.0 / std::max(clk_per_kg, 1.0));
@@ -243,7 +243,8 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     const int x_per_kg = gps_of(mf1) * c.ih * c.iw;
                     const int w_per_kg = taps1 * wg_rt * 64;
                     const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * 4 * mfma_clk(mf1);
-                    c.chunk_kg = pick_chunk(nkg1, x_per_kg, w_per_kg, threads, clk1);
+                    const int x_units_per_kg = gps_of(mf1) * c.ih * ceil_div(c.iw, 4);     // 4-pixel row pieces
+                    c.chunk_kg = pick_chunk(nkg1, x_units_per_kg, w_per_kg, threads, clk1);
                     if (c.chunk_kg < 1) continue;
                     c.w_off1 = c.chunk_kg * x_per_kg * 4;
                     const int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
@@ -350,9 +351,9 @@ struct Builder {
         for (int t = 0; t < nt; ++t) {
             const xl_shape &s = pl.shapes[t];
             if (s.n < 0 || s.c <= 0 || s.h <= 0 || s.w <= 0) return fail(XL_E_SHAPE, "tensor " + std::to_string(t) + ": non-positive extent");
-            // kernels index inside one image with 32-bit offsets and count workgroups in an int
-            if ((long long)s.c * s.h * s.w >= (1LL << 31) || (long long)s.n * s.c * s.h * s.w >= (1LL << 40))
-                return fail(XL_E_UNSUPPORTED, "tensor " + std::to_string(t) + ": more than 2^31 elements per image");
+            // kernels address inside one image with 32-bit byte offsets and count workgroups in an int
+            if ((long long)s.c * s.h * s.w >= (1LL << 30) || (long long)s.n * s.c * s.h * s.w >= (1LL << 40))
+                return fail(XL_E_UNSUPPORTED, "tensor " + std::to_string(t) + ": 2^30 or more elements per image");
         }
         for (int li = 0; li < nl; ++li) {
             const xl_layer &L = pl.layers[li];

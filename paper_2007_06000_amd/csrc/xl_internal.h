@@ -141,7 +141,7 @@ struct Variant {
 
 const std::vector<Variant> &variants();
 
-constexpr int STAGE_ITEMS = 4;      // float4 input items each thread stages per chunk
+constexpr int STAGE_UNITS = 1;      // input units (4 channels x 4 pixels) each thread stages per chunk
 constexpr int MAX_W_CHUNK_BYTES = 40 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
 constexpr int MAX_THREADS = 512;
 constexpr int MAX_ALTERNATIVES = 16;  // candidates per block kept for on-device tuning
