@@ -209,7 +209,7 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     // right after a load would stall on it.
     typedef unsigned u32x4 __attribute__((vector_size(16)));     // what the 128-bit buffer load returns
     const int HW = P.H * P.W;
-    const int plane = P.ih * P.iw;
+    const int plane = P.ih * P.iws;                                // LDS pixels per channel group (rows of iws)
     // Units start at the first tile column that can lie inside the image: a unit that began left of
     // column 0 of the tensor's very first row would have a negative buffer offset, for which the
     // hardware returns zeros for all 16 bytes.  The columns before it are padding and are zero-filled.
@@ -221,7 +221,7 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     unsigned xoff[NU];          // byte offset of the unit's first pixel in the group's first channel
     int xdst[NU];               // float offset of that pixel in the LDS chunk
     int xgrp[NU];               // first channel of the unit inside the chunk
-    unsigned xmask[NU];         // bit k: pixel k lies in the tile; bit 4 + k: and inside the image; bit 8: see xs
+    unsigned xmask[NU];         // bit k: pixel k of the unit lies in the tile and inside the image; bits 4, 8: see below
     f32x4 xst[NU][4];
     if constexpr (STAGE_X) {
 #pragma unroll
@@ -232,14 +232,14 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             const int cc = xs + 4 * q;                              // first tile column of the unit
             const int gy = iy0 + r, gx = ix0 + cc;
             const bool rowok = gy >= 0 && gy < P.H;
-            unsigned m = (u < x_units && q == 0) ? 0x100u : 0u;     // bit 8: this lane zero-fills the row's left padding
+            unsigned m = u < x_units ? (q == 0 ? 0x110u : 0x10u) : 0u;      // bit 4: lane owns a unit; bit 8: and zero-fills the row's left padding
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                if (u < x_units && cc + k < P.iw) m |= (rowok && gx + k < P.W) ? (0x11u << k) : (1u << k);
+                if (u < x_units && cc + k < P.iw && rowok && gx + k < P.W) m |= 1u << k;
             }
             xmask[i] = m;
             xgrp[i] = gr * 4;
-            xdst[i] = (gr * plane + r * P.iw + cc) * 4;
+            xdst[i] = (gr * plane + r * P.iws + cc) * 4;
             xoff[i] = (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4);
         }
     }
@@ -260,25 +260,28 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             }
         }
     };
+    // LDS rows are iws = iw rounded up to 4 pixels long, so a unit is always written whole: pixels
+    // outside the tile or the image are written as zeros.  A unit of a left-edge tile (xs > 0) may run
+    // up to xs pixels past its row's end; there it lands on the next row's left padding (or on the
+    // slack behind the chunk), which holds zeros as well.
     auto store_x = [&](float *dst, int c0) {
         if constexpr (STAGE_X) {
             const int nch = P.Cin - c0;            // channels of the chunk that exist (uniform)
+            const bool whole = nch >= g.chunk_kg * M::KC;
 #pragma unroll
             for (int i = 0; i < NU; ++i) {
-                if (i * nthreads < x_units) {
-                    const int live = nch - xgrp[i];        // channels of this unit that exist
+                if (i * nthreads < x_units && (xmask[i] & 0x10u)) {
                     if (xs > 0 && (xmask[i] & 0x100u)) {
                         for (int e = 1; e <= xs; ++e) *(f32x4 *)(dst + xdst[i] - 4 * e) = f32x4{0.f, 0.f, 0.f, 0.f};
                     }
+                    const int live = whole ? 4 : nch - xgrp[i];        // channels of this unit that exist
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
-                        if (xmask[i] & (1u << k)) {
-                            const bool in = (xmask[i] >> (4 + k)) & 1u;
-                            f32x4 v;
+                        const bool in = (xmask[i] >> k) & 1u;
+                        f32x4 v;
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) v[j] = (in && j < live) ? xst[i][j][k] : 0.f;
-                            *(f32x4 *)(dst + xdst[i] + 4 * k) = v;
-                        }
+                        for (int j = 0; j < 4; ++j) v[j] = (in && j < live) ? xst[i][j][k] : 0.f;
+                        *(f32x4 *)(dst + xdst[i] + 4 * k) = v;
                     }
                 }
             }
@@ -289,10 +292,15 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #ifdef XL_PHASE_TIMING
     long long t_ld = 0, t_mm = 0, t_st = 0, t_pro = clock64();
 #endif
+    // The input runs two chunks ahead in registers: the units of chunk i + 1 are written to LDS at the
+    // start of chunk i, by the few waves that own units, while the other wave of their SIMD already
+    // streams matrix operations (vector ALU work squeezed in after a wave's own matrix operations would
+    // leave the pipe idle instead); the loads of chunk i + 2 follow into the same registers.
     load_w(buf + g.w_off, 0);
     load_x(0);
     store_x(buf, 0);
     __builtin_amdgcn_s_waitcnt(0);      // this wave's LDS-direct loads have landed
+    if (nchunks > 1) load_x(g.chunk_kg * M::KC);
     __syncthreads();
     for (int ch = 0; ch < nchunks; ++ch) {
         float *cur = buf + (ch & 1) * g.buf_stride;
@@ -309,8 +317,9 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #endif
         const int c_next = (kg0 + g.chunk_kg) * M::KC;
         if (more) {
+            store_x(nxt, c_next);
             load_w(nxt + g.w_off, kg0 + g.chunk_kg);
-            load_x(c_next);
+            if (ch + 2 < nchunks) load_x(c_next + g.chunk_kg * M::KC);
         }
 #ifdef XL_PHASE_TIMING
         long long t1 = clock64();
@@ -324,7 +333,6 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         long long t2 = clock64();
         if (wt_on) wt[1] = t2;
 #endif
-        if (more) store_x(nxt, c_next);
 #ifdef XL_PHASE_TIMING
         if (wt_on) wt[2] = clock64();
 #endif
@@ -365,15 +373,47 @@ __device__ __forceinline__ void load_affine(const ConvW &c, int rt, int q, f32x4
 // Pixel p of the tile sits at (p / vw, p % vw); columns >= tw of the virtual row are padding.
 // HAS_SC (merge mode): the shortcut values of one row tile are fetched together before they are
 // used; invalid lanes read element 0.
+// 4 x 4 transpose inside each group of 4 adjacent lanes: on entry lane t of a group holds v[e] =
+// M[e][t] (four channels of its own pixel), on exit v[k] = M[t][k] (its own channel for the four
+// pixels of the group).  Two butterfly steps of cross-lane moves (lane ^ 1, then lane ^ 2).
+__device__ __forceinline__ void quad_transpose(float (&v)[4])
+{
+    const int t = threadIdx.x & 3;
+    auto xor1 = [](float x) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+    };
+    auto xor2 = [](float x) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+    };
+    const bool odd = t & 1, hi = t & 2;
+    // step 1: 2 x 2 blocks -- lanes t, t^1 and register pairs (0,1), (2,3)
+    const float y01 = xor1(odd ? v[0] : v[1]);
+    const float y23 = xor1(odd ? v[2] : v[3]);
+    const float c0 = odd ? y01 : v[0], c1 = odd ? v[1] : y01;
+    const float d0 = odd ? y23 : v[2], d1 = odd ? v[3] : y23;
+    // step 2: lanes t, t^2 exchange the pair they do not keep
+    const float r0 = xor2(hi ? c0 : d0), r1 = xor2(hi ? c1 : d1);
+    v[0] = hi ? r0 : c0;
+    v[1] = hi ? r1 : c1;
+    v[2] = hi ? d0 : r0;
+    v[3] = hi ? d1 : r1;
+}
+
+// Epilogue into global memory: scale / shift / activation, optional shortcut add, store.
+// When the tile's pixel order keeps every aligned group of 4 pixels in one output row (`wide`), the
+// accumulators are transposed inside groups of 4 lanes so that a lane holds 4 consecutive pixels of
+// one channel and moves them with one 16-byte buffer access; otherwise each lane stores its own
+// pixel's channels one by one.
 template <int MF, int NRT, int NPT, bool HAS_SC>
 __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
                                              const ConvW &c, int coff, int n, int oy0, int ox0, int th, int tw, int vw,
                                              int rt0, int rt_end, int pt0, int relu_out)
 {
     typedef MM<MF> M;
+    typedef unsigned u32x4 __attribute__((vector_size(16)));
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
-    // per-image element counts fit 31 bits (checked by the planner): 32-bit offsets from uniform bases
+    // per-image element counts fit 30 bits (checked by the planner): 32-bit offsets from uniform bases
     const int plane = P.Ho * P.Wo;
     float *__restrict__ yn = P.y + ((size_t)n * P.Cy + coff) * plane;
     const float *__restrict__ scn = HAS_SC ? P.sc + (size_t)n * P.Csc * plane : nullptr;
@@ -385,6 +425,78 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     for (int r = 0; r < NRT; ++r)
 #pragma unroll
         for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[r][q], fb[r][q]);
+
+    const bool wide = (vw & 3) == 0 || th == 1;
+    if (wide) {
+        // descriptors end with the tensors: whatever a 16-byte access would touch past the end is dropped
+        const unsigned long long ybytes = ((unsigned long long)(P.N - n) * P.Cy - coff) * plane * 4ull;
+        const __amdgpu_buffer_rsrc_t yr =
+            __builtin_amdgcn_make_buffer_rsrc((void *)yn, (short)0, (int)(unsigned)min(ybytes, 0xffffffffull), 0x00020000);
+        __amdgpu_buffer_rsrc_t sr = yr;
+        if constexpr (HAS_SC) {
+            const unsigned long long sbytes = (unsigned long long)(P.N - n) * P.Csc * plane * 4ull;
+            sr = __builtin_amdgcn_make_buffer_rsrc((void *)scn, (short)0, (int)(unsigned)min(sbytes, 0xffffffffull), 0x00020000);
+        }
+        const int t = lane & 3;
+        int nvs[NPT];
+        unsigned offs[NPT][NRT][M::NQ];
+        f32x4 sv[NPT][NRT][M::NQ];
+        // addresses first, and every shortcut load in flight before the first one is used
+#pragma unroll
+        for (int p = 0; p < NPT; ++p) {
+            const int pidx = (pt0 + p) * MF + (col & ~3);        // first pixel of this lane's group of 4
+            const int oy = pidx / vw, ox = pidx - oy * vw;
+            const int gy = oy0 + oy, gx = ox0 + ox;
+            nvs[p] = (oy < th && gy < P.Ho) ? min(min(tw - ox, P.Wo - gx), 4) : 0;           // pixels to store
+            const int pix = nvs[p] > 0 ? gy * P.Wo + gx : 0;
+#pragma unroll
+            for (int r = 0; r < NRT; ++r)
+#pragma unroll
+                for (int q = 0; q < M::NQ; ++q) {
+                    const int co = (rt0 + r) * MF + M::quad_row(q, sub) + t;     // the channel this lane ends up with
+                    offs[p][r][q] = (unsigned)((min(co, c.cout - 1) * plane + pix) * 4);
+                    if constexpr (HAS_SC) {
+                        if (rt0 + r < rt_end)
+                            sv[p][r][q] = __builtin_bit_cast(f32x4, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(sr, offs[p][r][q], 0, 0));
+                    }
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int p = 0; p < NPT; ++p) {
+#pragma unroll
+            for (int r = 0; r < NRT; ++r) {
+                if (rt0 + r >= rt_end) continue;
+#pragma unroll
+                for (int q = 0; q < M::NQ; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = acc[r][p][q * 4 + e] * fa[r][q][e] + fb[r][q][e];
+                        if (c.relu) v[e] = fmaxf(v[e], 0.f);
+                    }
+                    quad_transpose(v);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if constexpr (HAS_SC) v[k] += sv[p][r][q][k];
+                        if (relu_out) v[k] = fmaxf(v[k], 0.f);
+                    }
+                    const int nv = (rt0 + r) * MF + M::quad_row(q, sub) + t < c.cout ? nvs[p] : 0;
+                    const unsigned off = offs[p][r][q];
+                    if (nv == 4) {
+                        const f32x4 o = {v[0], v[1], v[2], v[3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), yr, off, 0, 0);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 3; ++k)
+                            if (k < nv) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[k]), yr, off + 4 * k, 0, 0);
+                    }
+                }
+            }
+        }
+        return;
+    }
+
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -512,7 +624,7 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
     g1.rt_base = (KIND == KIND_SINGLE) ? cs * g1.wg_rt : 0;
     g1.wr = wave % P.waves_r1;
     g1.chunk_kg = P.chunk_kg;
-    g1.src_w = P.iw;
+    g1.src_w = P.iws;
     g1.gstride = P.in_gstride;
     g1.w_off = P.w_off1;
     g1.buf_stride = P.buf_stride;
@@ -531,7 +643,7 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
             int pidx = (pt0 + p) * MF1 + col;
             pidx = pidx < npx1 ? pidx : 0;
             const int my = pidx / P.mw, mx = pidx - my * P.mw;
-            off1[p] = ((my * P.c1.stride) * P.iw + mx * P.c1.stride) * 4 + sub * P.in_gstride;
+            off1[p] = ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * P.in_gstride;
         }
     }
     XL_PHASE(L, 0);
@@ -612,10 +724,19 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
                             const int oy = min(pidx / P.vw2, P.th - 1), ox = min(pidx % P.vw2, P.tw - 1);
                             off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * P.mid_gstride;
                         }
+#ifdef XL_PHASE_TIMING
+                        if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 0] = clock64();
+#endif
                         conv_pass<MF2, KS2, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0ull, 0, 0);
+#ifdef XL_PHASE_TIMING
+                        if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 1] = clock64();
+#endif
                         if (g2.active)
                             store_global<MF2, NRT2, NPT2, SC>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
                                                               p0, P.relu_out);
+#ifdef XL_PHASE_TIMING
+                        if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 2] = clock64();
+#endif
                     }
                 }
             };

@@ -240,13 +240,13 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     c.tiles_y = ceil_div(b.Ho, th);
                     c.tiles_x = ceil_div(b.Wo, tw);
                     // stage-1 chunk: input tile chunk + filter chunk per buffer
-                    const int x_per_kg = gps_of(mf1) * c.ih * c.iw;
+                    const int x_per_kg = gps_of(mf1) * c.ih * ((c.iw + 3) / 4 * 4);       // LDS rows hold whole 4-pixel units
                     const int w_per_kg = taps1 * wg_rt * 64;
                     const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * 4 * mfma_clk(mf1);
                     const int x_units_per_kg = gps_of(mf1) * c.ih * ceil_div(c.iw, 4);     // 4-pixel row pieces
                     c.chunk_kg = pick_chunk(nkg1, x_units_per_kg, w_per_kg, threads, clk1);
                     if (c.chunk_kg < 1) continue;
-                    c.w_off1 = c.chunk_kg * x_per_kg * 4;
+                    c.w_off1 = c.chunk_kg * x_per_kg * 4 + 16;        // + slack for a left-edge unit running past the last row
                     const int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
                     c.mid_floats = b.kind == KIND_SINGLE ? 0 : nrt1 * mf1 / 4 * c.mh * c.mw * 4;
 
@@ -262,6 +262,11 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                         for (int w2 = 1; w2 <= nw; w2 *= 2) wr2s.push_back(w2);
                         vws.push_back(tw);
                         if (tw % 16 && (tw + 15) / 16 * 16 - tw <= 4) vws.push_back((tw + 15) / 16 * 16);
+                        // rows of a multiple of 4 pixels let the epilogue move 4 pixels per access
+                        if (tw % 4 && (tw + 3) / 4 * 4 != vws.back()) vws.push_back((tw + 3) / 4 * 4);
+#ifdef XL_DEV_HOOKS
+                        if (const char *f = std::getenv("XL_FORCE_VW2")) vws.assign(1, std::max(tw, std::atoi(f)));
+#endif
                     } else {
                         splits.push_back(b.kind == KIND_SINGLE ? ceil_div(nrt1, wg_rt) : 1);
                         wr2s.push_back(1);
@@ -596,6 +601,7 @@ struct Builder {
         p.mw = ch.mw;
         p.ih = ch.ih;
         p.iw = ch.iw;
+        p.iws = (ch.iw + 3) / 4 * 4;
         p.tiles_x = ch.tiles_x;
         p.tiles_y = ch.tiles_y;
         p.csplit = ch.csplit;
@@ -607,7 +613,7 @@ struct Builder {
         p.waves_r2 = ch.waves_r2;
         p.vw2 = ch.vw2;
         p.mid_gstride = ch.mh * ch.mw * 4;
-        p.in_gstride = ch.ih * ch.iw * 4;
+        p.in_gstride = ch.ih * p.iws * 4;
         p.lds_buf_off = ch.mid_floats;
         p.buf_stride = ch.buf_floats;
         p.w_off1 = ch.w_off1;

@@ -61,6 +61,7 @@ struct BlockParams {
     int th, tw;             // output tile of the block
     int mh, mw;             // stage-1 output tile (incl. halo) -- equals th, tw for SINGLE
     int ih, iw;             // input tile (incl. halo)
+    int iws;                // pixels per row of the staged input in LDS: iw rounded up to 4
     int tiles_x, tiles_y, csplit;
     int nblocks;            // logical workgroups = N * csplit * tiles_y * tiles_x
     int chunk_kg;           // stage 1: K steps staged per chunk
