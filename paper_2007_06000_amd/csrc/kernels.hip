@@ -543,6 +543,73 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     }
 }
 
+// Epilogue of a convolution whose only consumer is a global average pooling, with the whole image in
+// one workgroup tile: scale / shift / activation, then the mean over the pixels.  Each wave sums its
+// accumulators over its pixel tiles and across the lanes that hold different pixels of one channel; the
+// waves along the pixel direction meet in LDS (`red`, free once the K loop has ended); one thread per
+// channel adds their partial sums in a fixed order and stores the mean.  Called by every wave of the
+// workgroup (it contains a barrier); `active` says whether this wave holds real tiles.
+template <int MF, int NRT, int NPT>
+__device__ __forceinline__ void store_gap(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
+                                          const ConvW &c, int coff, int n, int npx, int rt_base, int wg_rt, int wr,
+                                          int wp, int npw, int pt0, bool active, float *red)
+{
+    typedef MM<MF> M;
+    const int lane = threadIdx.x & 63;
+    const int sub = lane / MF, col = lane % MF;
+    const int rows_wg = wg_rt * MF;
+    const int rt0 = rt_base + wr * NRT;
+    if (active) {
+        asm volatile("" ::: "memory");
+        float s[NRT][M::NQ * 4];
+#pragma unroll
+        for (int r = 0; r < NRT; ++r) {
+            f32x4 fa[M::NQ], fb[M::NQ];
+#pragma unroll
+            for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[q], fb[q]);
+#pragma unroll
+            for (int e = 0; e < M::NQ * 4; ++e) {
+                float t = 0.f;
+#pragma unroll
+                for (int p = 0; p < NPT; ++p) {
+                    float v = acc[r][p][e] * fa[e >> 2][e & 3] + fb[e >> 2][e & 3];
+                    if (c.relu) v = fmaxf(v, 0.f);
+                    if (P.relu_out) v = fmaxf(v, 0.f);
+                    t += ((pt0 + p) * MF + col < npx) ? v : 0.f;
+                }
+                // lanes of one `sub` hold the MF pixels of this channel: butterfly over the column bits
+#pragma unroll
+                for (int m = 1; m < MF; m <<= 1) t += __shfl_xor(t, m, 64);
+                s[r][e] = t;
+            }
+        }
+        if (col == 0) {
+#pragma unroll
+            for (int r = 0; r < NRT; ++r)
+#pragma unroll
+                for (int e = 0; e < M::NQ * 4; ++e)
+                    red[wp * rows_wg + (wr * NRT + r) * MF + M::quad_row(e >> 2, sub) + (e & 3)] = s[r][e];
+        }
+    } else if (wr * NRT < wg_rt && col == 0) {
+        // a wave without real tiles still owns a slot per channel: the sum below reads all of them
+#pragma unroll
+        for (int r = 0; r < NRT; ++r)
+#pragma unroll
+            for (int e = 0; e < M::NQ * 4; ++e)
+                red[wp * rows_wg + (wr * NRT + r) * MF + M::quad_row(e >> 2, sub) + (e & 3)] = 0.f;
+    }
+    __syncthreads();
+    const float inv = 1.f / (float)npx;
+    for (int row = threadIdx.x; row < rows_wg; row += blockDim.x) {
+        const int co = rt_base * MF + row;
+        if (co < c.cout) {
+            float t = 0.f;
+            for (int w = 0; w < npw; ++w) t += red[w * rows_wg + row];
+            P.y[(size_t)n * P.Cy + coff + co] = t * inv;
+        }
+    }
+}
+
 // Epilogue of layer 1 into the LDS tile (S2).  `fill` is what the next layer
 // must see outside the image: 0 for a convolution, -FLT_MAX for max pooling.
 template <int MF, int NRT, int NPT>
@@ -652,8 +719,14 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
     XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {
-        store_global<MF1, NRT1, NPT1, false>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mh, P.mw, P.mw, rt0, rt_end1, pt0,
-                                             P.relu_out);
+        if (P.gap) {
+            store_gap<MF1, NRT1, NPT1>(acc, P, P.c1, P.coff1, n, npx1, g1.rt_base, g1.wg_rt, g1.wr, wave / P.waves_r1,
+                                       nwaves / P.waves_r1, pt0, g1.active, buf);
+            return;
+        }
+        if (g1.active)
+            store_global<MF1, NRT1, NPT1, false>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mh, P.mw, P.mw, rt0, rt_end1, pt0,
+                                                 P.relu_out);
         return;
     } else {
         // ---- S2: epilogue of layer 1 into the LDS tile, S3: barrier

@@ -67,6 +67,7 @@ struct BlockSpec {
     int H1 = 0, W1 = 0, Ho = 0, Wo = 0;
     int relu_out = 0;
     bool shortcut = false;
+    bool gap = false;               // KIND_SINGLE followed by a global average pooling: one tile per image
     long long alg_bytes = 0;        // algorithmic HBM bytes of the fused block
 };
 
@@ -180,7 +181,9 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     std::map<std::tuple<int, int, int, int>, Choice> per_key;     // best per (variant, threads, tile)
     const std::vector<int> ths = tile_candidates(b.Ho), tws = tile_candidates(b.Wo);
     std::vector<std::pair<int, int>> tiles;
-    if (pl.opts.force_tile_h > 0 && pl.opts.force_tile_w > 0) {
+    if (b.gap) {
+        tiles.push_back({b.Ho, b.Wo});          // the mean needs every pixel of the image in one workgroup
+    } else if (pl.opts.force_tile_h > 0 && pl.opts.force_tile_w > 0) {
         tiles.push_back({std::min(pl.opts.force_tile_h, b.Ho), std::min(pl.opts.force_tile_w, b.Wo)});
     } else if (pl.opts.paper_tuner_only) {
         int t[64], g[64];
@@ -565,6 +568,7 @@ struct Builder {
         p.W1 = b.W1;
         p.Ho = b.Ho;
         p.Wo = b.Wo;
+        p.gap = b.gap ? 1 : 0;
         const Storage &ys = pl.storage[y_id];
         p.Cy = ys.ctot;
         p.Csc = sc_id >= 0 ? pl.shapes[sc_id].c : 0;
@@ -739,8 +743,11 @@ struct Builder {
                 b.pool_k = L2.k;
                 b.pool_s = L2.stride;
                 b.pool_p = L2.pad;
+            } else if (L2.op == XL_GLOBAL_AVGPOOL) {
+                b.kind = KIND_SINGLE;
+                b.gap = true;
             } else {
-                return fail(XL_E_UNSUPPORTED, at + "straight mode: second layer must be a convolution or max pooling");
+                return fail(XL_E_UNSUPPORTED, at + "straight mode: second layer must be a convolution, max pooling or global average pooling");
             }
         } else if (mode == XL_SPLIT) {
             if (ids.size() != 3 && ids.size() != 4) return fail(XL_E_UNSUPPORTED, at + "split mode is conv -> {conv, conv} [-> concat]");
@@ -793,6 +800,15 @@ struct Builder {
         const xl_shape &ys = pl.shapes[y_id];
         b.Ho = ys.h;
         b.Wo = ys.w;
+        if (b.gap) {
+            // the kernel sees the convolution's own output extent; a pointwise one as a single row
+            b.Ho = ms.h;
+            b.Wo = ms.w;
+            if (L1.k == 1 && L1.stride == 1 && L1.pad == 0) {
+                b.W = b.W1 = b.Wo = xs.h * xs.w;
+                b.H = b.H1 = b.Ho = 1;
+            }
+        }
 
         // algorithmic traffic (paper Table 2 counts stored elements the same way)
         xl_group_info &gi = gp.info;

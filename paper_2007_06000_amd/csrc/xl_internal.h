@@ -58,6 +58,7 @@ struct BlockParams {
     int P2;                 // halo of the LDS tile on the top/left = largest stage-2 pad
     int pool_k;             // KIND_POOL: window size (stride s2, pad P2)
     int relu_out;           // applied after the shortcut add (merge)
+    int gap;                // KIND_SINGLE: the tile is the whole image and y receives the mean over its pixels
     int th, tw;             // output tile of the block
     int mh, mw;             // stage-1 output tile (incl. halo) -- equals th, tw for SINGLE
     int ih, iw;             // input tile (incl. halo)

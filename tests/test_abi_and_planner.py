@@ -129,6 +129,16 @@ def test_oversized_tensors_are_rejected_cleanly():
     assert e.value.status == B.XL_E_UNSUPPORTED
 
 
+def test_global_average_pooling_block_needs_the_image_in_one_tile():
+    ok = B.Plan(W.conv_gap_generic(2, 16, 13, 13, 64, 1, 0, 1))
+    q = ok.query(0)
+    assert q["tiles_y"] * q["tiles_x"] == 1 and q["stores_fused"] == 2 * 64
+    assert q["stores_unfused"] == 2 * 64 * 169 + 2 * 64
+    with pytest.raises(B.XlError) as e:                         # 112 x 112 pixels do not fit one workgroup
+        B.Plan(W.conv_gap_generic(1, 16, 112, 112, 64, 1, 0, 1))
+    assert e.value.status == B.XL_E_UNSUPPORTED
+
+
 def test_empty_batch_plans():
     p = B.Plan(W.config(3, n=0))
     assert p.query(0)["workgroups"] == 0

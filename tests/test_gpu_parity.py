@@ -132,6 +132,18 @@ def test_tuned_plans_match_the_oracle(cfg, kw):
     assert q["lds_bytes"] <= 160 * 1024 and q["workgroups"] > 0
 
 
+@pytest.mark.parametrize("shape", [
+    dict(n=3, cin=40, h=13, w=13, c1=100, k1=1, p1=0, s1=1),            # pointwise, ragged channels: one row of 169 pixels
+    dict(n=2, cin=24, h=9, w=11, c1=70, k1=3, p1=1, s1=1, bn=True),     # 3x3 with folded batch-norm
+    dict(n=2, cin=16, h=7, w=5, c1=33, k1=3, p1=0, s1=1, relu=False),   # no activation: negative values in the mean
+    dict(n=1, cin=8, h=1, w=1, c1=16, k1=1, p1=0, s1=1),                # one pixel
+])
+def test_conv_then_global_average_pooling(shape):
+    """Straight block conv -> global average pooling: the mean is formed inside the convolution kernel."""
+    out, ref, s = run_both(W.conv_gap_generic(**shape))
+    assert s.plan.num_launches(True) == 1 and s.plan.num_launches(False) == 2
+
+
 def test_degenerate_shapes():
     """1x1 images, single channels, tiles larger than the image, odd sizes under stride 2."""
     for wl in (W.single_conv(1, 1, 1, 1, 1, 1),

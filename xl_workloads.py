@@ -186,7 +186,8 @@ def merge_residual(n: int = 32, c: int = 64, hw: int = 56) -> Workload:
     return b.done(t, "relu_normal", 1004)
 
 
-def squeezenet11(n: int = 64, hw: int = 224, classes: int = 1000, fuse_stem: bool = True) -> Workload:
+def squeezenet11(n: int = 64, hw: int = 224, classes: int = 1000, fuse_stem: bool = True,
+                 fuse_head: bool = True) -> Workload:
     """Config 5: SqueezeNet-v1.1-shaped network; 8 split-mode fire blocks (paper section 4.2)."""
     b = _Builder("cfg5_squeezenet11", n, 3, hw, hw)
     first = len(b.layers)
@@ -204,8 +205,11 @@ def squeezenet11(n: int = 64, hw: int = 224, classes: int = 1000, fuse_stem: boo
     t = b.fire(t, 48, 192, "fire7")
     t = b.fire(t, 64, 256, "fire8")
     t = b.fire(t, 64, 256, "fire9")
+    first = len(b.layers)
     t = b.conv(t, classes, 1, bias=True, relu=True, name="conv10")
     t = b.gap(t, name="gap")
+    if fuse_head:
+        b.group("straight", first)
     return b.done(t, "normal", 1005)
 
 
@@ -240,6 +244,15 @@ def conv_pool_generic(n, cin, h, w, c1, k1, p1, s1, pk, ps, pp, bn=False, relu=T
     b = _Builder(f"convpool_{cin}x{h}x{w}_{c1}k{k1}_p{pk}", n, cin, h, w)
     t = b.conv(0, c1, k1, stride=s1, pad=p1, bias=not bn, bn=bn, relu=relu, name="conv")
     t = b.maxpool(t, pk, ps, pp, name="pool")
+    b.group("straight", 0)
+    return b.done(t, dist, seed)
+
+
+def conv_gap_generic(n, cin, h, w, c1, k1, p1, s1, bn=False, relu=True, seed=9, dist="relu_normal") -> Workload:
+    """Convolution -> global average pooling as one straight block (the head of config 5)."""
+    b = _Builder(f"convgap_{cin}x{h}x{w}_{c1}k{k1}", n, cin, h, w)
+    t = b.conv(0, c1, k1, stride=s1, pad=p1, bias=not bn, bn=bn, relu=relu, name="conv")
+    t = b.gap(t, name="gap")
     b.group("straight", 0)
     return b.done(t, dist, seed)
 
