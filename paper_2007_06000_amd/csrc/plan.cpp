@@ -379,7 +379,7 @@ struct Builder {
             switch (L.op) {
             case XL_CONV: {
                 if (L.groups != 1) return fail(XL_E_UNSUPPORTED, at + "grouped convolution is not supported");
-                if (L.k != 1 && L.k != 3) return fail(XL_E_UNSUPPORTED, at + "filter size must be 1 or 3");
+                if (L.k != 1 && L.k != 3 && L.k != 5) return fail(XL_E_UNSUPPORTED, at + "filter size must be 1, 3 or 5");
                 if (L.stride < 1 || L.pad < 0 || L.pad > L.k) return fail(XL_E_SHAPE, at + "bad stride/pad");
                 if (L.k == 1 && L.pad != 0) return fail(XL_E_UNSUPPORTED, at + "1x1 convolution with padding");
                 if (L.cin != x.c || L.cout != y.c) return fail(XL_E_SHAPE, at + "channel counts do not match tensors");

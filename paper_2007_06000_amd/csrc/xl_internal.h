@@ -133,6 +133,15 @@ struct Variant {
     /* stage 2 on 16-pixel tiles, 7 per wave: finer padding of small tiles */ \
     X(45, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 1)          \
     X(46, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 0)          \
+    /* 5x5 filters (paper Table 1, a.1: 1x1 -> 5x5) and their unfused forms */ \
+    X(47, KIND_SINGLE, 32, 5, 1, 1, 0, 0, 0, 0, 0, 0)             \
+    X(48, KIND_SINGLE, 32, 5, 2, 1, 0, 0, 0, 0, 0, 0)             \
+    X(49, KIND_SINGLE, 16, 5, 1, 2, 0, 0, 0, 0, 0, 0)             \
+    X(50, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0)            \
+    X(51, KIND_FUSED2, 16, 1, 1, 2, 32, 1, 1, 5, 0, 0)            \
+    X(52, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 1, 5, 0, 0)            \
+    X(53, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 5, 0, 0)            \
+    X(54, KIND_FUSED2, 32, 3, 1, 1, 32, 1, 1, 5, 0, 0)            \
     /* conv -> maxpool */                                 \
     X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0)             \
     X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0)             \
@@ -144,7 +153,7 @@ struct Variant {
 const std::vector<Variant> &variants();
 
 constexpr int STAGE_UNITS = 1;      // input units (4 channels x 4 pixels) each thread stages per chunk
-constexpr int MAX_W_CHUNK_BYTES = 40 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
+constexpr int MAX_W_CHUNK_BYTES = 52 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
 constexpr int MAX_THREADS = 512;
 constexpr int MAX_ALTERNATIVES = 16;  // candidates per block kept for on-device tuning
 #ifndef XL_MIN_WAVES

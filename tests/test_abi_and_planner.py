@@ -57,8 +57,6 @@ def test_store_counts_follow_paper_table2(row):
     (the paper's counters report 2 and 4 floats per transaction respectively)."""
     case, cin, h, w, c1, k1, p1, c2, k2, p2, ours, cudnn = row[0], *map(int, row[1:])
     wl = W.straight_generic(1, cin, h, w, c1, k1, p1, 1, c2, k2, p2, 1) if case != "b.1" else W.config(3, n=1, cin=cin, hw=h, s=c1, e=c2)
-    if k2 == 5:
-        pytest.skip("5x5 filters are not covered by the kernels yet; accounting checked on the other cases")
     p = B.Plan(wl)
     q = p.query(0)
     assert q["stores_unfused"] == 2 * cudnn

@@ -144,6 +144,17 @@ def test_conv_then_global_average_pooling(shape):
     assert s.plan.num_launches(True) == 1 and s.plan.num_launches(False) == 2
 
 
+@pytest.mark.parametrize("wl", [
+    W.straight_generic(2, 192, 28, 28, 16, 1, 0, 1, 32, 5, 2, 1),       # paper Table 1, a.1 (inception 5x5 branch), batch 2
+    W.straight_generic(1, 20, 11, 9, 24, 1, 0, 1, 40, 5, 2, 1, bn2=True),
+    W.straight_generic(1, 8, 12, 12, 12, 3, 1, 1, 20, 5, 0, 1),         # 3x3 -> 5x5 without padding
+    W.single_conv(2, 6, 13, 10, 35, 5, stride=1, pad=2),
+    W.single_conv(1, 3, 17, 17, 8, 5, stride=2, pad=2),
+], ids=lambda w: w.name)
+def test_five_by_five_filters(wl):
+    run_both(wl)
+
+
 def test_degenerate_shapes():
     """1x1 images, single channels, tiles larger than the image, odd sizes under stride 2."""
     for wl in (W.single_conv(1, 1, 1, 1, 1, 1),
