@@ -67,10 +67,12 @@ typedef struct xl_shape { int n, c, h, w; } xl_shape;        /* dense NCHW fp32 
 /*
  * One layer.  `in` / `out` are tensor ids (indices into the shapes array);
  * in[1] is used by XL_ADD and XL_CONCAT only (-1 otherwise).
- * XL_CONV:   y = act(scale * corr(x, filter) + shift); square K x K filter,
- *            zero padding, groups must be 1.  Slots index the `weights` array of
- *            xl_prepare; scale_slot / shift_slot may be -1 (scale 1 / shift 0).
- *            A bias is a shift with no scale; a folded batch-norm is both.
+ * XL_CONV:   y = act(scale * corr(x, filter) + shift); square K x K filter with
+ *            K = 1, 3 or 5, zero padding.  groups is 1, or equal to cin == cout
+ *            (depthwise, K = 3, filter [C, 1, K, K]; paper Table 1 case a.2).
+ *            Slots index the `weights` array of xl_prepare; scale_slot /
+ *            shift_slot may be -1 (scale 1 / shift 0).  A bias is a shift with no
+ *            scale; a folded batch-norm is both.
  * XL_MAXPOOL: K x K window, stride, pad; out-of-image taps are ignored.
  * XL_GLOBAL_AVGPOOL: mean over H x W -> [N, C, 1, 1].
  * XL_ADD:    y = act(in[0] + in[1]).
@@ -88,7 +90,8 @@ typedef struct xl_layer {
 } xl_layer;
 
 /* A fusion block: `mode` and the layer indices it covers, in graph order.
- *   XL_STRAIGHT: conv -> conv, or conv -> maxpool
+ *   XL_STRAIGHT: conv -> conv, conv -> maxpool, conv -> global average pooling
+ *                (the image must fit one workgroup tile), depthwise conv -> conv
  *   XL_SPLIT:    conv -> {conv, conv} [-> concat]
  *   XL_MERGE:    conv -> conv -> add(., block input)          (residual block)
  *   XL_SINGLE:   any one layer

@@ -163,9 +163,20 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, vo
     char *ws = static_cast<char *>(workspace);
     for (const xl::PackedFilter &p : plan->packed) {
         const xl_layer &L = plan->layers[p.layer];
-        hipError_t e = xl::launch_pack_filter(static_cast<const float *>(weights[L.w_slot]),
-                                              reinterpret_cast<xl::f32x4 *>(ws + p.offset), L.cout, L.cin, L.k, p.mf,
-                                              p.nkg, p.nrt, s);
+        hipError_t e;
+        if (p.mf == 0) {
+            e = xl::launch_pack_depthwise(static_cast<const float *>(weights[L.w_slot]), plan->scale_ptr[p.layer],
+                                          plan->shift_ptr[p.layer], reinterpret_cast<xl::f32x4 *>(ws + p.offset),
+                                          reinterpret_cast<xl::f32x4 *>(ws + p.aff_offset), L.cout, L.k, s);
+            if (e != hipSuccess) {
+                plan->error = std::string("filter re-layout launch failed: ") + hipGetErrorString(e);
+                return XL_E_LAUNCH;
+            }
+            continue;
+        }
+        e = xl::launch_pack_filter(static_cast<const float *>(weights[L.w_slot]),
+                                   reinterpret_cast<xl::f32x4 *>(ws + p.offset), L.cout, L.cin, L.k, p.mf,
+                                   p.nkg, p.nrt, s);
         if (e == hipSuccess)
             e = xl::launch_pack_affine(plan->scale_ptr[p.layer], plan->shift_ptr[p.layer],
                                        reinterpret_cast<xl::f32x4 *>(ws + p.aff_offset), L.cout, p.mf, p.nrt, s);
@@ -228,6 +239,13 @@ static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void
         }
         e = xl::launch_add(reinterpret_cast<const float *>(x), reinterpret_cast<const float *>(b),
                            reinterpret_cast<float *>(y), st.count, st.relu, s);
+    } else if (st.type == xl::STEP_DEPTHWISE) {
+        const xl::Storage &ys = plan->storage[st.y_id];
+        const xl::PackedFilter &pf = plan->packed[st.packed[0]];
+        e = xl::launch_depthwise(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y),
+                                 reinterpret_cast<const xl::f32x4 *>(ws + pf.offset),
+                                 reinterpret_cast<const xl::f32x4 *>(ws + pf.aff_offset), st.N, st.C, st.H, st.W, st.Ho,
+                                 st.Wo, st.k, st.stride, st.pad, st.relu, ys.ctot, ys.coff, s);
     } else if (st.type == xl::STEP_GAP) {
         if (plan->storage[st.y_id].root != st.y_id) {
             mp->error = "global pooling writing into a concat slice is not supported";

@@ -655,6 +655,73 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 }
 
 // ----------------------------------------------------------------------------
+// Depthwise stage 1 (paper Table 1, a.2: a 3x3 convolution with one filter per channel feeding a
+// pointwise one).  No reduction over channels, so no matrix cores: the halo-extended input tile of
+// all channels is staged as [channel group][row][col][4], then every thread walks (channel group,
+// pixel) items, one float4 multiply-add per tap, and writes scale / shift / activation results into
+// the LDS tile the pointwise stage reads -- zero where the intermediate lies outside the image.
+// Filter: [channel group][tap] float4, scale / shift: [channel group][2] float4 (re-laid out once).
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mid, float *xs, const float *ximg,
+                                                 unsigned long long x_bytes, int my0, int mx0, int iy0, int ix0)
+{
+    const ConvW &c = P.c1;
+    const int ncg = (P.Cin + 3) >> 2;
+    const int HW = P.H * P.W;
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)ximg, (short)0, (int)(unsigned)min(x_bytes, 0xffffffffull), 0x00020000);
+    const int in_px = P.ih * P.iw;
+    for (int it = threadIdx.x; it < ncg * in_px; it += blockDim.x) {
+        const int g = it / in_px, rem = it - g * in_px;
+        const int r = rem / P.iw, cc = rem - r * P.iw;
+        const int gy = iy0 + r, gx = ix0 + cc;
+        const bool in = gy >= 0 && gy < P.H && gx >= 0 && gx < P.W;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (in) {
+            const unsigned off = (unsigned)((g * 4 * HW + gy * P.W + gx) * 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)     // channels past Cin of the last image read as zero (end of the buffer)
+                v[j] = (g * 4 + j < P.Cin)
+                           ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xr, off, j * HW * 4, 0))
+                           : 0.f;
+        }
+        *(f32x4 *)(xs + (g * P.ih * P.iws + r * P.iws + cc) * 4) = v;
+    }
+    __syncthreads();
+    const int T = c.k * c.k;
+    const int mid_px = P.mh * P.mw;
+    // the pointwise stage reads whole K steps of 8 or 16 channels: groups past the last real one hold zeros
+    const int ncg_all = ((P.Cin + 15) >> 4) << 2;
+    for (int it = threadIdx.x; it < ncg_all * mid_px; it += blockDim.x) {
+        const int g = it / mid_px, pidx = it - g * mid_px;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        if (g < ncg) {
+            const int my = pidx / P.mw, mx = pidx - my * P.mw;
+            const float *s = xs + (g * P.ih * P.iws + (my * c.stride) * P.iws + mx * c.stride) * 4;
+            const f32x4 *w = c.wp + g * T;
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
+            for (int u = 0; u < c.k; ++u)
+                for (int v = 0; v < c.k; ++v) {
+                    const f32x4 xv = *(const f32x4 *)(s + (u * P.iws + v) * 4);
+                    const f32x4 wv = w[u * c.k + v];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) a[j] = fmaf(xv[j], wv[j], a[j]);
+                }
+            const f32x4 sc = c.aff[g * 2], sh = c.aff[g * 2 + 1];
+            const int gy = my0 + my, gx = mx0 + mx;
+            const bool inside = gy >= 0 && gy < P.H1 && gx >= 0 && gx < P.W1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float t = a[j] * sc[j] + sh[j];
+                if (c.relu) t = fmaxf(t, 0.f);
+                o[j] = (inside && g * 4 + j < P.Cin) ? t : 0.f;
+            }
+        }
+        *(f32x4 *)(mid + g * P.mid_gstride + pidx * 4) = o;
+    }
+}
+
+// ----------------------------------------------------------------------------
 // The block kernel
 // ----------------------------------------------------------------------------
 template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC>
@@ -684,6 +751,10 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
     float *buf = lds + P.lds_buf_off;
     const float *ximg = P.x + (size_t)n * P.Cin * P.H * P.W;
 
+    if constexpr (KIND == KIND_DW) {
+        // ---- S1/S2 for a depthwise first layer: vector ALU from a staged input tile into the LDS tile
+        depthwise_stage1(P, mid, buf, ximg, (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, my0, mx0, iy0, ix0);
+    } else {
     // ---- S1: layer 1 over the (halo-extended) tile
     const int npx1 = P.mh * P.mw;
     PassGeom g1;
@@ -729,9 +800,13 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
                                                  P.relu_out);
         return;
     } else {
-        // ---- S2: epilogue of layer 1 into the LDS tile, S3: barrier
+        // ---- S2: epilogue of layer 1 into the LDS tile
         store_mid<MF1, NRT1, NPT1>(acc, P, mid, my0, mx0, rt0, rt_end1, pt0, npx1,
                                    KIND == KIND_POOL ? -FLT_MAX : 0.f);
+    }
+    }
+    if constexpr (KIND != KIND_SINGLE) {
+        // ---- S3: barrier between producing and consuming the LDS tile
         __syncthreads();
         XL_PHASE(L, 2);
 
@@ -1072,6 +1147,88 @@ hipError_t launch_gap(const float *x, float *y, int NC, int HW, hipStream_t s)
     const int threads = 256;
     const int wpb = threads / 64;
     hipLaunchKernelGGL(gap_kernel, dim3((NC + wpb - 1) / wpb), dim3(threads), 0, s, x, y, NC, HW);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------
+// Depthwise convolution (groups == channels): tables and the per-layer kernel of the unfused path
+// ----------------------------------------------------------------------------
+// [C][1][K][K] -> [channel group][tap] float4, and scale / shift -> [channel group][2] float4
+// (scale 1 / shift 0 where the pointer is null, zero filter and tables for channels past C).
+__global__ void pack_depthwise_kernel(const float *__restrict__ w, const float *__restrict__ scale,
+                                      const float *__restrict__ shift, f32x4 *__restrict__ wp, f32x4 *__restrict__ aff,
+                                      int C, int taps)
+{
+    const int ncg = (C + 3) >> 2;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < ncg * taps) {
+        const int g = idx / taps, t = idx - g * taps;
+        f32x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (g * 4 + j < C) ? w[(g * 4 + j) * taps + t] : 0.f;
+        wp[idx] = v;
+    }
+    if (idx < ncg) {
+        f32x4 a, b;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = idx * 4 + j;
+            a[j] = c < C ? (scale ? scale[c] : 1.f) : 0.f;
+            b[j] = c < C ? (shift ? shift[c] : 0.f) : 0.f;
+        }
+        aff[idx * 2] = a;
+        aff[idx * 2 + 1] = b;
+    }
+}
+
+hipError_t launch_pack_depthwise(const float *w, const float *scale, const float *shift, f32x4 *wp, f32x4 *aff, int C,
+                                 int k, hipStream_t s)
+{
+    const int items = ((C + 3) / 4) * k * k;
+    hipLaunchKernelGGL(pack_depthwise_kernel, dim3((items + 255) / 256), dim3(256), 0, s, w, scale, shift, wp, aff, C,
+                       k * k);
+    return hipGetLastError();
+}
+
+// one thread per output element; consecutive threads run along W
+__global__ void depthwise_kernel(const float *__restrict__ x, float *__restrict__ y, const f32x4 *__restrict__ wp,
+                                 const f32x4 *__restrict__ aff, int C, int H, int W, int Ho, int Wo, int k, int stride,
+                                 int pad, int relu, int Cy, int coff, long long total)
+{
+    const long long idx = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int ox = (int)(idx % Wo);
+    long long r = idx / Wo;
+    const int oy = (int)(r % Ho);
+    r /= Ho;
+    const int c = (int)(r % C);
+    const long long n = r / C;
+    const float *xc = x + ((size_t)n * C + c) * H * W;
+    const int g = c >> 2, j = c & 3;
+    float a = 0.f;
+    for (int u = 0; u < k; ++u) {
+        const int iy = oy * stride - pad + u;
+        if (iy < 0 || iy >= H) continue;
+        for (int v = 0; v < k; ++v) {
+            const int ix = ox * stride - pad + v;
+            if (ix < 0 || ix >= W) continue;
+            a = fmaf(xc[iy * W + ix], wp[g * k * k + u * k + v][j], a);
+        }
+    }
+    float t = a * aff[g * 2][j] + aff[g * 2 + 1][j];
+    if (relu) t = fmaxf(t, 0.f);
+    y[(((size_t)n * Cy + coff + c) * Ho + oy) * Wo + ox] = t;
+}
+
+hipError_t launch_depthwise(const float *x, float *y, const f32x4 *wp, const f32x4 *aff, int N, int C, int H, int W,
+                            int Ho, int Wo, int k, int stride, int pad, int relu, int Cy, int coff, hipStream_t s)
+{
+    const long long total = (long long)N * C * Ho * Wo;
+    if (total == 0) return hipSuccess;
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(depthwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, y, wp, aff, C, H, W, Ho, Wo, k, stride,
+                       pad, relu, Cy, coff, total);
     return hipGetLastError();
 }
 

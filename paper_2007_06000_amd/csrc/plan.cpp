@@ -128,9 +128,17 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     }
     double t1 = *std::max_element(simd, simd + 4);
     int barriers = ceil_div(nkg1, c.chunk_kg);
+    if (b.kind == KIND_DW) {
+        // vector ALU: staging one float4 per (channel group, input pixel), then per (channel group,
+        // intermediate pixel) one LDS read and 4 multiply-adds per tap; ~8 issue cycles per wave instruction
+        const double ncg = ceil_div(b.Cin, 4);
+        const double waves_per_simd = nw / 4.0;
+        t1 = (ncg * c.ih * c.iw * 12.0 + ncg * npx1 * (taps1 * 6.0 + 16.0)) / c.threads * waves_per_simd * 8.0;
+        barriers = 1;
+    }
     double t2 = 0;
     long long flops2 = 0;
-    if (b.kind == KIND_FUSED2) {
+    if (b.kind == KIND_FUSED2 || b.kind == KIND_DW) {
         const int mf2 = v.mf2, NRT2 = v.nrt2, NPT2 = v.npt2;
         const int npt2 = ceil_div(c.th * c.vw2, mf2);
         const int wg_rt2 = c.waves_r2 * NRT2, wg_pt2 = (nw / c.waves_r2) * NPT2;
@@ -164,14 +172,15 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     // memory side: algorithmic bytes at HBM speed plus per-workgroup cache-line traffic at L2 speed
     auto lines = [](int w) { return (double)((w * 4 + 64 + 127) / 128) * 128.0; };
     const double in_wg = (double)b.Cin * c.ih * lines(c.iw) * c.csplit;
-    const double out_ch = b.kind == KIND_FUSED2 ? (double)(b.c2[0].cout + (b.n2 > 1 ? b.c2[1].cout : 0)) : b.c1.cout;
+    const double out_ch = (b.kind == KIND_FUSED2 || b.kind == KIND_DW) ? (double)(b.c2[0].cout + (b.n2 > 1 ? b.c2[1].cout : 0)) : b.c1.cout;
     const double out_wg = out_ch * c.th * lines(c.tw) * (b.shortcut ? 2.0 : 1.0);
     const double t_mem = (double)b.alg_bytes / 8.0e12 + (in_wg + out_wg) * c.tiles_x * c.tiles_y * b.N / 24.0e12;
     c.cost = std::max(t_mfma, t_mem) + 0.15 * std::min(t_mfma, t_mem);
     // executed multiply-adds: stage 1 covers every row tile once per tile (per cout slice when fused),
     // with pixels and channels rounded up to whole matrix-core tiles
     const long long tiles = (long long)c.tiles_x * c.tiles_y * b.N;
-    const long long s1 = 2LL * nrt1 * mf1 * ceil_div(npx1, mf1) * mf1 * nkg1 * kc_of(mf1) * taps1;
+    const long long s1 = b.kind == KIND_DW ? 2LL * b.Cin * npx1 * taps1
+                                           : 2LL * nrt1 * mf1 * ceil_div(npx1, mf1) * mf1 * nkg1 * kc_of(mf1) * taps1;
     c.flops_exec = tiles * (b.kind == KIND_SINGLE ? 1 : c.csplit) * s1 + tiles * c.csplit * flops2;
 }
 
@@ -201,7 +210,9 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
         if (const char *only = std::getenv("XL_ONLY_VARIANT"))
             if (b.kind != KIND_SINGLE && std::atoi(only) != v.id) continue;
 #endif
-        if (b.kind == KIND_FUSED2) {
+        const bool dw = b.kind == KIND_DW;                  // depthwise stage 1: no matrix-core tiling of layer 1
+        const bool two = b.kind == KIND_FUSED2 || dw;       // stage 2 runs convolutions from the LDS tile
+        if (two) {
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
         const int mf1 = v.mf1;
@@ -212,9 +223,10 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
             const int nw = threads / 64;
             for (int wr = 1; wr <= nw; wr *= 2) {
                 const int wg_rt = wr * v.nrt1;
-                if (b.kind != KIND_SINGLE && wg_rt < nrt1) continue;            // stage 1 must produce every channel
-                if (wr > 1 && (wr / 2) * v.nrt1 >= nrt1) continue;              // more row waves than row tiles
-                const int px_cap = (nw / wr) * v.npt1 * mf1;
+                if (dw && wr > 1) continue;
+                if (!dw && b.kind != KIND_SINGLE && wg_rt < nrt1) continue;     // stage 1 must produce every channel
+                if (!dw && wr > 1 && (wr / 2) * v.nrt1 >= nrt1) continue;       // more row waves than row tiles
+                const int px_cap = dw ? (1 << 30) : (nw / wr) * v.npt1 * mf1;
                 for (auto [th, tw] : tiles) {
                     Choice c;
                     c.v = v;
@@ -247,14 +259,20 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     const int w_per_kg = taps1 * wg_rt * 64;
                     const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * 4 * mfma_clk(mf1);
                     const int x_units_per_kg = gps_of(mf1) * c.ih * ceil_div(c.iw, 4);     // 4-pixel row pieces
-                    c.chunk_kg = pick_chunk(nkg1, x_units_per_kg, w_per_kg, threads, clk1);
+                    c.chunk_kg = dw ? 1 : pick_chunk(nkg1, x_units_per_kg, w_per_kg, threads, clk1);
                     if (c.chunk_kg < 1) continue;
                     c.w_off1 = c.chunk_kg * x_per_kg * 4 + 16;        // + slack for a left-edge unit running past the last row
-                    const int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
+                    int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
                     c.mid_floats = b.kind == KIND_SINGLE ? 0 : nrt1 * mf1 / 4 * c.mh * c.mw * 4;
+                    if (dw) {       // the whole input tile, every channel, staged once; no filter chunk
+                        const int ncg = ceil_div(b.Cin, 4);
+                        c.w_off1 = 0;
+                        buf1 = ncg * c.ih * ((c.iw + 3) / 4 * 4) * 4;
+                        c.mid_floats = ceil_div(b.Cin, 16) * 4 * c.mh * c.mw * 4;     // whole K steps of the pointwise stage
+                    }
 
                     std::vector<int> splits, wr2s, vws;
-                    if (b.kind == KIND_FUSED2) {
+                    if (two) {
                         if (pl.opts.force_cout_split > 0) {
                             splits.push_back(pl.opts.force_cout_split);
                         } else {
@@ -284,9 +302,9 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                 // staging buffers: passes with several chunks ping-pong between two buffers
                                 // `multi` floats apart, a single-chunk pass only ever touches the first one
                                 int multi = 0, single = 0;
-                                (ceil_div(nkg1, c.chunk_kg) > 1 ? multi : single) = buf1;
+                                ((!dw && ceil_div(nkg1, c.chunk_kg) > 1) ? multi : single) = buf1;
                                 bool fits = true;
-                                if (b.kind == KIND_FUSED2) {
+                                if (two) {
                                     const int NRT2 = v.nrt2, NPT2 = v.npt2;
                                     int max_per = 0;
                                     for (int i = 0; i < b.n2; ++i)
@@ -378,7 +396,9 @@ struct Builder {
             if (x.n != y.n) return fail(XL_E_SHAPE, at + "batch differs between input and output");
             switch (L.op) {
             case XL_CONV: {
-                if (L.groups != 1) return fail(XL_E_UNSUPPORTED, at + "grouped convolution is not supported");
+                if (L.groups != 1 && !(L.groups == L.cin && L.cin == L.cout))
+                    return fail(XL_E_UNSUPPORTED, at + "grouped convolution other than depthwise (groups == Cin == Cout)");
+                if (L.groups != 1 && L.k != 3) return fail(XL_E_UNSUPPORTED, at + "depthwise filter size must be 3");
                 if (L.k != 1 && L.k != 3 && L.k != 5) return fail(XL_E_UNSUPPORTED, at + "filter size must be 1, 3 or 5");
                 if (L.stride < 1 || L.pad < 0 || L.pad > L.k) return fail(XL_E_SHAPE, at + "bad stride/pad");
                 if (L.k == 1 && L.pad != 0) return fail(XL_E_UNSUPPORTED, at + "1x1 convolution with padding");
@@ -479,7 +499,7 @@ struct Builder {
     {
         const xl_layer &L = pl.layers[li];
         if (L.op != XL_CONV) return 0;
-        long long b = 4LL * L.cout * L.cin * L.k * L.k;
+        long long b = 4LL * L.cout * (L.cin / std::max(L.groups, 1)) * L.k * L.k;
         if (L.scale_slot >= 0) b += 4LL * L.cout;
         if (L.shift_slot >= 0) b += 4LL * L.cout;
         return b;
@@ -489,7 +509,7 @@ struct Builder {
         const xl_layer &L = pl.layers[li];
         if (L.op != XL_CONV) return 0;
         const xl_shape &y = pl.shapes[L.out];
-        return 2LL * y.n * y.c * y.h * y.w * L.cin * L.k * L.k;
+        return 2LL * y.n * y.c * y.h * y.w * (L.cin / std::max(L.groups, 1)) * L.k * L.k;
     }
     // HBM bytes / stored elements of one layer run on its own
     void layer_traffic(int li, long long &bytes, long long &stores) const
@@ -510,11 +530,17 @@ struct Builder {
         PackedFilter p;
         p.layer = layer;
         p.mf = mf;
-        p.nkg = ceil_div(L.cin, kc_of(mf));
-        p.nrt = ceil_div(L.cout, mf);
-        p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16;
+        if (mf == 0) {      // depthwise: [channel group][tap] float4 and [channel group][scale, shift] float4
+            p.nkg = p.nrt = 0;
+            p.bytes = (size_t)ceil_div(L.cout, 4) * L.k * L.k * 16;
+            p.aff_bytes = (size_t)ceil_div(L.cout, 4) * 2 * 16;
+        } else {
+            p.nkg = ceil_div(L.cin, kc_of(mf));
+            p.nrt = ceil_div(L.cout, mf);
+            p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16;
+            p.aff_bytes = (size_t)p.nrt * (mf == 32 ? 4 : 1) * 2 * 64 * 16;
+        }
         p.offset = 0;
-        p.aff_bytes = (size_t)p.nrt * (mf == 32 ? 4 : 1) * 2 * 64 * 16;
         p.aff_offset = 0;
         pl.packed.push_back(p);
         return (int)pl.packed.size() - 1;
@@ -556,7 +582,7 @@ struct Builder {
         st.sc_id = sc_id;
         st.conv_layer[0] = b.c1.layer;
         st.conv_layer[1] = st.conv_layer[2] = -1;
-        st.packed[0] = packed_index(b.c1.layer, ch.v.mf1);
+        st.packed[0] = packed_index(b.c1.layer, b.kind == KIND_DW ? 0 : ch.v.mf1);
         st.packed[1] = st.packed[2] = -1;
         BlockParams &p = st.bp;
         memset(&p, 0, sizeof p);
@@ -586,7 +612,8 @@ struct Builder {
         };
         fill(p.c1, b.c1, ch.v.mf1);
         p.coff1 = ys.coff + coff1;
-        p.n2 = b.kind == KIND_FUSED2 ? b.n2 : 0;
+        const bool two = b.kind == KIND_FUSED2 || b.kind == KIND_DW;
+        p.n2 = two ? b.n2 : 0;
         int P2 = 0;
         for (int i = 0; i < p.n2; ++i) {
             fill(p.c2[i], b.c2[i], ch.v.mf2);
@@ -595,8 +622,8 @@ struct Builder {
             st.packed[1 + i] = packed_index(b.c2[i].layer, ch.v.mf2);
             P2 = std::max(P2, b.c2[i].pad);
         }
-        p.s2 = b.kind == KIND_FUSED2 ? b.c2[0].stride : (b.kind == KIND_POOL ? b.pool_s : 1);
-        p.P2 = b.kind == KIND_FUSED2 ? P2 : (b.kind == KIND_POOL ? b.pool_p : 0);
+        p.s2 = two ? b.c2[0].stride : (b.kind == KIND_POOL ? b.pool_s : 1);
+        p.P2 = two ? P2 : (b.kind == KIND_POOL ? b.pool_p : 0);
         p.pool_k = b.pool_k;
         p.relu_out = b.relu_out;
         p.th = ch.th;
@@ -667,7 +694,11 @@ struct Builder {
         st.stride = L.stride;
         st.pad = L.pad;
         st.relu = L.relu;
-        if (L.op == XL_CONV) {
+        if (L.op == XL_CONV && L.groups != 1) {
+            st.type = STEP_DEPTHWISE;
+            st.conv_layer[0] = li;
+            st.packed[0] = packed_index(li, 0);
+        } else if (L.op == XL_CONV) {
             BlockSpec b;
             b.kind = KIND_SINGLE;
             conv_spec(li, b.c1);
@@ -717,6 +748,11 @@ struct Builder {
             if (ids[i] <= ids[i - 1]) return fail(XL_E_GRAPH, at + "layer ids must ascend");
         const xl_layer &L1 = pl.layers[ids[0]];
         if (L1.op != XL_CONV) return fail(XL_E_UNSUPPORTED, at + "first layer of a fused block must be a convolution");
+        for (size_t i = 1; i < ids.size(); ++i)
+            if (pl.layers[ids[i]].op == XL_CONV && pl.layers[ids[i]].groups != 1)
+                return fail(XL_E_UNSUPPORTED, at + "a depthwise convolution can only be the first layer of a block");
+        if (L1.groups != 1 && (mode != XL_STRAIGHT || ids.size() != 2 || pl.layers[ids[1]].op != XL_CONV))
+            return fail(XL_E_UNSUPPORTED, at + "a depthwise convolution fuses only with one following convolution (straight mode)");
         const int t_in = L1.in[0], t_mid = L1.out;
         const xl_shape &xs = pl.shapes[t_in], &ms = pl.shapes[t_mid];
         BlockSpec b;
@@ -735,7 +771,7 @@ struct Builder {
             if (!only_consumers(t_mid, {ids[1]})) return fail(XL_E_UNSUPPORTED, at + "the intermediate has a consumer outside the block");
             y_id = L2.out;
             if (L2.op == XL_CONV) {
-                b.kind = KIND_FUSED2;
+                b.kind = L1.groups != 1 ? KIND_DW : KIND_FUSED2;
                 b.n2 = 1;
                 conv_spec(ids[1], b.c2[0]);
             } else if (L2.op == XL_MAXPOOL) {
@@ -793,7 +829,7 @@ struct Builder {
         } else {
             return fail(XL_E_UNSUPPORTED, at + "unknown fusion mode");
         }
-        if (b.kind == KIND_FUSED2) {
+        if (b.kind == KIND_FUSED2 || b.kind == KIND_DW) {
             for (int i = 0; i < b.n2; ++i)
                 if (b.c2[i].cin != b.c1.cout) return fail(XL_E_SHAPE, at + "channel mismatch inside the block");
         }

@@ -9,12 +9,12 @@
 
 namespace xl {
 
-enum StepType { STEP_BLOCK = 0, STEP_MAXPOOL = 1, STEP_ADD = 2, STEP_GAP = 3 };
+enum StepType { STEP_BLOCK = 0, STEP_MAXPOOL = 1, STEP_ADD = 2, STEP_GAP = 3, STEP_DEPTHWISE = 4 };
 
 // A filter re-laid out for one matrix-core tile size.
 struct PackedFilter {
     int layer;
-    int mf;
+    int mf;             // 32 or 16; 0 = depthwise tables ([channel group][tap], [channel group][scale, shift])
     int nkg, nrt;
     size_t offset;      // bytes into the workspace
     size_t bytes;

@@ -31,7 +31,7 @@ struct ConvW {
     int nrt;                // row tiles = ceil(cout / MF)
 };
 
-enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2 };
+enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3 };
 
 // Kernel argument of every convolution-stage kernel.
 //   KIND_SINGLE: stage 1 writes its result to global memory (one layer, the
@@ -41,6 +41,9 @@ enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2 };
 //                tile (straight / split), optionally adding a shortcut tensor
 //                in the epilogue (merge).
 //   KIND_POOL:   stage 1 as above; stage 2 is a max pooling from the LDS tile.
+//   KIND_DW:     stage 1 is a depthwise convolution (one filter per channel, vector ALU) into the
+//                LDS tile; stage 2 as KIND_FUSED2.  c1.wp / c1.aff then hold the plain depthwise
+//                tables ([channel group][tap] and [channel group][scale, shift] float4).
 struct BlockParams {
     const float *x;         // block input  [N, Cin, H, W]
     float *y;               // tensor the block writes into [N, Cy, Ho, Wo]
@@ -142,6 +145,12 @@ struct Variant {
     X(52, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 1, 5, 0, 0)            \
     X(53, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 5, 0, 0)            \
     X(54, KIND_FUSED2, 32, 3, 1, 1, 32, 1, 1, 5, 0, 0)            \
+    /* depthwise -> pointwise (paper Table 1, a.2); MF1 / NRT1 / NPT1 unused */ \
+    X(55, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0)                \
+    X(56, KIND_DW, 32, 3, 1, 1, 32, 1, 1, 1, 0, 0)                \
+    X(57, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 1, 0, 0)                \
+    X(58, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0)                \
+    X(59, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 3, 0, 0)                \
     /* conv -> maxpool */                                 \
     X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0)             \
     X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0)             \
@@ -172,5 +181,9 @@ hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, 
                           int k, int stride, int pad, int Cy, int coff, hipStream_t s);
 hipError_t launch_add(const float *a, const float *b, float *y, long long count, int relu, hipStream_t s);
 hipError_t launch_gap(const float *x, float *y, int NC, int HW, hipStream_t s);
+hipError_t launch_pack_depthwise(const float *w, const float *scale, const float *shift, f32x4 *wp, f32x4 *aff, int C,
+                                 int k, hipStream_t s);
+hipError_t launch_depthwise(const float *x, float *y, const f32x4 *wp, const f32x4 *aff, int N, int C, int H, int W,
+                            int Ho, int Wo, int k, int stride, int pad, int relu, int Cy, int coff, hipStream_t s);
 
 }  // namespace xl

@@ -63,6 +63,22 @@ def test_store_counts_follow_paper_table2(row):
     assert q["stores_fused"] == 4 * ours
 
 
+def test_store_counts_of_the_depthwise_case_of_table2():
+    """Table 2, a.2 (depthwise 3x3 -> pointwise on [16,80,80]): 25600 fused vs 102400 per-layer
+    transactions, i.e. 4 and 2 floats per transaction over 102400 and 204800 stored elements."""
+    q = B.Plan(W.depthwise_pointwise(1, 16, 80, 80, 16)).query(0)
+    assert q["stores_fused"] == 4 * 25600 and q["stores_unfused"] == 2 * 102400
+    assert q["mode"] == B.XL_STRAIGHT and q["mid_h"] == q["tile_h"] and q["in_h"] == q["tile_h"] + 2
+
+
+def test_grouped_convolutions_other_than_depthwise_are_rejected():
+    wl = W.single_conv(1, 8, 9, 9, 8, 3, pad=1)
+    wl.layers[0].groups = 2
+    with pytest.raises(B.XlError) as e:
+        B.Plan(wl)
+    assert e.value.status == B.XL_E_UNSUPPORTED
+
+
 def test_algorithmic_traffic_of_the_block_configs():
     want = {1: (51.3e3, 84.1e3), 2: (8.05e6, 20.89e6), 3: (43.41e6, 52.71e6), 4: (51.68e6, 180.13e6)}
     for cfg, (fused, unfused) in want.items():

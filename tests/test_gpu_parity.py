@@ -155,6 +155,18 @@ def test_five_by_five_filters(wl):
     run_both(wl)
 
 
+@pytest.mark.parametrize("wl", [
+    W.depthwise_pointwise(2, 16, 80, 80, 16),                                # paper Table 1, a.2, batch 2
+    W.depthwise_pointwise(1, 10, 13, 9, 24, bn1=True),                       # channels not a multiple of 4
+    W.depthwise_pointwise(2, 32, 17, 17, 40, s1=2, relu1=False),             # strided depthwise, negative intermediate
+    W.depthwise_pointwise(1, 64, 14, 14, 64, k2=3, p2=1, bn2=True),          # depthwise -> 3x3: halo of the intermediate
+    W.depthwise_pointwise(1, 3, 5, 5, 4, p1=0),
+], ids=lambda w: w.name)
+def test_depthwise_then_convolution(wl):
+    out, ref, s = run_both(wl)
+    assert s.plan.num_launches(True) == 1 and s.plan.num_launches(False) == 2
+
+
 def test_degenerate_shapes():
     """1x1 images, single channels, tiles larger than the image, odd sizes under stride 2."""
     for wl in (W.single_conv(1, 1, 1, 1, 1, 1),

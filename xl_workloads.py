@@ -248,6 +248,17 @@ def conv_pool_generic(n, cin, h, w, c1, k1, p1, s1, pk, ps, pp, bn=False, relu=T
     return b.done(t, dist, seed)
 
 
+def depthwise_pointwise(n, c, h, w, c2, k1=3, p1=1, s1=1, k2=1, p2=0, bn1=False, bn2=False, relu1=True, relu2=True,
+                        seed=10, dist="normal") -> Workload:
+    """Depthwise k1 x k1 convolution (one filter per channel) -> convolution, one straight block
+    (paper Table 1, case a.2: [16,80,80], 3x3 depthwise pad 1, then 1x1 16 -> 16)."""
+    b = _Builder(f"dwpw_{c}x{h}x{w}_k{k1}s{s1}_{c2}k{k2}", n, c, h, w)
+    t = b.conv(0, c, k1, stride=s1, pad=p1, groups=c, bias=not bn1, bn=bn1, relu=relu1, name="depthwise")
+    t = b.conv(t, c2, k2, stride=1, pad=p2, bias=not bn2, bn=bn2, relu=relu2, name="pointwise")
+    b.group("straight", 0)
+    return b.done(t, dist, seed)
+
+
 def conv_gap_generic(n, cin, h, w, c1, k1, p1, s1, bn=False, relu=True, seed=9, dist="relu_normal") -> Workload:
     """Convolution -> global average pooling as one straight block (the head of config 5)."""
     b = _Builder(f"convgap_{cin}x{h}x{w}_{c1}k{k1}", n, cin, h, w)
