@@ -93,7 +93,8 @@ typedef struct xl_layer {
  *   XL_STRAIGHT: conv -> conv, conv -> maxpool, conv -> global average pooling
  *                (the image must fit one workgroup tile), depthwise conv -> conv
  *   XL_SPLIT:    conv -> {conv, conv} [-> concat]
- *   XL_MERGE:    conv -> conv -> add(., block input)          (residual block)
+ *   XL_MERGE:    conv -> conv -> add(., block input)          (residual block), or
+ *                {conv, conv}(block input) -> add -> conv      (two producers, all 1x1)
  *   XL_SINGLE:   any one layer
  * Layers not listed in any block are planned as XL_SINGLE. */
 typedef struct xl_group {

@@ -219,8 +219,8 @@ static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void
             p.sc = reinterpret_cast<const float *>(base(st.sc_id));
             if (!p.sc) return XL_E_NULL;
         }
-        xl::ConvW *cw[3] = {&p.c1, &p.c2[0], &p.c2[1]};
-        for (int i = 0; i < 3; ++i) {
+        xl::ConvW *cw[4] = {&p.c1, &p.c2[0], &p.c2[1], &p.c1b};
+        for (int i = 0; i < 4; ++i) {
             if (st.conv_layer[i] < 0) continue;
             cw[i]->wp = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].offset);
             cw[i]->aff = reinterpret_cast<const xl::f32x4 *>(ws + plan->packed[st.packed[i]].aff_offset);

@@ -612,13 +612,14 @@ __device__ __forceinline__ void store_gap(const typename MM<MF>::Acc (&acc)[NRT]
 
 // Epilogue of layer 1 into the LDS tile (S2).  `fill` is what the next layer
 // must see outside the image: 0 for a convolution, -FLT_MAX for max pooling.
+// With `add` the result is added to what the tile already holds (the first of two producer layers
+// of a merge block, written by this same lane) and `relu_sum` is applied to the sum.
 template <int MF, int NRT, int NPT>
 __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
-                                          float *mid, int my0, int mx0, int rt0, int rt_end, int pt0, int npx,
-                                          float fill)
+                                          const ConvW &c, float *mid, int my0, int mx0, int rt0, int rt_end, int pt0,
+                                          int npx, float fill, bool add = false, bool relu_sum = false)
 {
     typedef MM<MF> M;
-    const ConvW &c = P.c1;
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
     asm volatile("" ::: "memory");      // keep the loads below from being hoisted over the K loop
@@ -640,15 +641,22 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
                 f32x4 v;
+                float *dst = mid + (cb >> 2) * P.mid_gstride + pidx * 4;
+                f32x4 old = {0.f, 0.f, 0.f, 0.f};
+                if (add && pidx < npx) old = *(const f32x4 *)dst;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
                     if (c.relu) z = fmaxf(z, 0.f);
+                    if (add) {
+                        z += old[i];
+                        if (relu_sum) z = fmaxf(z, 0.f);
+                    }
                     if (!inside) z = fill;
                     if (cb + i >= c.cout) z = 0.f;
                     v[i] = z;
                 }
-                if (pidx < npx) *(f32x4 *)(mid + (cb >> 2) * P.mid_gstride + pidx * 4) = v;
+                if (pidx < npx) *(f32x4 *)dst = v;
             }
         }
     }
@@ -801,8 +809,22 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
         return;
     } else {
         // ---- S2: epilogue of layer 1 into the LDS tile
-        store_mid<MF1, NRT1, NPT1>(acc, P, mid, my0, mx0, rt0, rt_end1, pt0, npx1,
+        store_mid<MF1, NRT1, NPT1>(acc, P, P.c1, mid, my0, mx0, rt0, rt_end1, pt0, npx1,
                                    KIND == KIND_POOL ? -FLT_MAX : 0.f);
+        if constexpr (KIND == KIND_FUSED2 && K1 == 1 && K2A == 1 && K2B == 0 && !SC) {
+            if (P.n1 == 2) {
+                // second producer of a merge block (paper Fig. 4c): same input, same geometry, its own
+                // filter; its result is added to the first one's in the LDS tile
+#pragma unroll
+                for (int p = 0; p < NPT1; ++p)
+#pragma unroll
+                    for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
+                conv_pass<MF1, K1, NRT1, NPT1, true>(acc, P, P.c1b, g1, nullptr, off1, buf, ximg,
+                                                     (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
+                store_mid<MF1, NRT1, NPT1>(acc, P, P.c1b, mid, my0, mx0, rt0, rt_end1, pt0, npx1, 0.f, true,
+                                           P.relu_mid != 0);
+            }
+        }
     }
     }
     if constexpr (KIND != KIND_SINGLE) {

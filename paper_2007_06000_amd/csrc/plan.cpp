@@ -59,6 +59,9 @@ struct ConvSpec {
 struct BlockSpec {
     int kind = KIND_SINGLE;
     ConvSpec c1;
+    ConvSpec c1b;                   // second producer of a two-producer merge block
+    int n1 = 1;                     // stage-1 convolutions summed in the LDS tile
+    int relu_mid = 0;               // activation of that sum
     int n2 = 0;
     ConvSpec c2[2];
     int coff2[2] = {0, 0};
@@ -126,8 +129,8 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
         const int rt_end = std::min(nrt1, wg_rt);
         if (rt0 < rt_end && pt0 * mf1 < npx1) simd[w % 4] += wave1;
     }
-    double t1 = *std::max_element(simd, simd + 4);
-    int barriers = ceil_div(nkg1, c.chunk_kg);
+    double t1 = *std::max_element(simd, simd + 4) * b.n1;
+    int barriers = ceil_div(nkg1, c.chunk_kg) * b.n1;
     if (b.kind == KIND_DW) {
         // vector ALU: staging one float4 per (channel group, input pixel), then per (channel group,
         // intermediate pixel) one LDS read and 4 multiply-adds per tap; ~8 issue cycles per wave instruction
@@ -181,7 +184,7 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     const long long tiles = (long long)c.tiles_x * c.tiles_y * b.N;
     const long long s1 = b.kind == KIND_DW ? 2LL * b.Cin * npx1 * taps1
                                            : 2LL * nrt1 * mf1 * ceil_div(npx1, mf1) * mf1 * nkg1 * kc_of(mf1) * taps1;
-    c.flops_exec = tiles * (b.kind == KIND_SINGLE ? 1 : c.csplit) * s1 + tiles * c.csplit * flops2;
+    c.flops_exec = tiles * (b.kind == KIND_SINGLE ? 1 : c.csplit) * s1 * b.n1 + tiles * c.csplit * flops2;
 }
 
 static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &lds_rejected)
@@ -215,6 +218,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
         if (two) {
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
+        if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0)) continue;
         const int mf1 = v.mf1;
         const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
         const int taps1 = b.c1.k * b.c1.k;
@@ -611,6 +615,15 @@ struct Builder {
             w.nrt = ceil_div(s.cout, mf);
         };
         fill(p.c1, b.c1, ch.v.mf1);
+        p.n1 = b.n1;
+        p.relu_mid = b.relu_mid;
+        st.conv_layer[3] = -1;
+        st.packed[3] = -1;
+        if (b.n1 == 2) {
+            fill(p.c1b, b.c1b, ch.v.mf1);
+            st.conv_layer[3] = b.c1b.layer;
+            st.packed[3] = packed_index(b.c1b.layer, ch.v.mf1);
+        }
         p.coff1 = ys.coff + coff1;
         const bool two = b.kind == KIND_FUSED2 || b.kind == KIND_DW;
         p.n2 = two ? b.n2 : 0;
@@ -810,8 +823,28 @@ struct Builder {
             b.coff2[0] = pl.storage[pl.layers[first].out].coff - pl.storage[sa.root].coff;
             b.coff2[1] = pl.storage[pl.layers[second].out].coff - pl.storage[sa.root].coff;
             y_id = sa.root;
+        } else if (mode == XL_MERGE && ids.size() == 4) {
+            // two producers: {conv A, conv B}(x) -> add -> conv C   (paper Fig. 4c / Table 1 c.1)
+            const xl_layer &B = pl.layers[ids[1]], &S = pl.layers[ids[2]], &C = pl.layers[ids[3]];
+            if (B.op != XL_CONV || S.op != XL_ADD || C.op != XL_CONV) return fail(XL_E_GRAPH, at + "merge mode wiring");
+            if (B.in[0] != t_in) return fail(XL_E_UNSUPPORTED, at + "both producers of a merge block must read the block input");
+            if (!((S.in[0] == t_mid && S.in[1] == B.out) || (S.in[1] == t_mid && S.in[0] == B.out)) || C.in[0] != S.out)
+                return fail(XL_E_GRAPH, at + "merge mode: the add must read both producers and feed the last convolution");
+            if (!only_consumers(t_mid, {ids[2]}) || !only_consumers(B.out, {ids[2]}) || !only_consumers(S.out, {ids[3]}))
+                return fail(XL_E_UNSUPPORTED, at + "an intermediate has a consumer outside the block");
+            if (L1.cout != B.cout || L1.k != B.k || L1.stride != B.stride || L1.pad != B.pad)
+                return fail(XL_E_UNSUPPORTED, at + "the two producers must share filter size, stride, padding and channels");
+            if (L1.k != 1 || C.k != 1)
+                return fail(XL_E_UNSUPPORTED, at + "two-producer merge blocks are built for 1x1 convolutions");
+            b.kind = KIND_FUSED2;
+            conv_spec(ids[1], b.c1b);
+            b.n1 = 2;
+            b.relu_mid = S.relu;
+            b.n2 = 1;
+            conv_spec(ids[3], b.c2[0]);
+            y_id = C.out;
         } else if (mode == XL_MERGE) {
-            if (ids.size() != 3) return fail(XL_E_UNSUPPORTED, at + "merge mode is conv -> conv -> add(., block input)");
+            if (ids.size() != 3) return fail(XL_E_UNSUPPORTED, at + "merge mode is conv -> conv -> add(., block input) or {conv, conv} -> add -> conv");
             const xl_layer &L2 = pl.layers[ids[1]], &L3 = pl.layers[ids[2]];
             if (L2.op != XL_CONV || L3.op != XL_ADD || L2.in[0] != t_mid) return fail(XL_E_GRAPH, at + "merge mode wiring");
             const int other = L3.in[0] == L2.out ? L3.in[1] : (L3.in[1] == L2.out ? L3.in[0] : -1);

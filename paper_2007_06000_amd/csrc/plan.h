@@ -38,8 +38,8 @@ struct Step {
     BlockParams bp;     // pointers filled at run time
     int threads;
     int lds_bytes;
-    int conv_layer[3];  // layer index of c1, c2[0], c2[1] (-1 unused)
-    int packed[3];      // index into Plan::packed
+    int conv_layer[4];  // layer index of c1, c2[0], c2[1], c1b (-1 unused)
+    int packed[4];      // index into Plan::packed
     // tensors
     int x_id, y_id, sc_id;
     // element-wise steps

@@ -53,6 +53,9 @@ struct BlockParams {
     int Ho, Wo;             // extent of the block output
     int Cy, Csc;
     ConvW c1;
+    ConvW c1b;              // second producer of a two-producer merge block (n1 == 2): same geometry as c1
+    int n1;                 // stage-1 convolutions whose results are summed in the LDS tile (1 or 2)
+    int relu_mid;           // activation applied to that sum
     int coff1;              // channel offset into y when stage 1 writes global
     int n2;                 // stage-2 convolutions (0 for SINGLE / POOL)
     ConvW c2[2];
@@ -129,6 +132,8 @@ struct Variant {
     X(29, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 0)          \
     X(30, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 0, 0)          \
     X(31, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 1, 0, 0)          \
+    X(60, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 1, 0, 0)          \
+    X(61, KIND_FUSED2, 16, 1, 2, 2, 16, 1, 2, 1, 0, 0)          \
     X(32, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 1)          \
     X(33, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 1)          \
     X(34, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 1)          \

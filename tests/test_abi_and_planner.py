@@ -79,6 +79,15 @@ def test_grouped_convolutions_other_than_depthwise_are_rejected():
     assert e.value.status == B.XL_E_UNSUPPORTED
 
 
+def test_two_producer_merge_block_plans_as_one_launch():
+    """Table 1, c.1: {1x1 64->256, 1x1 64->256} -> add -> 1x1 256->64 on [64,56,56]."""
+    p = B.Plan(W.merge_two_producers(1))
+    q = p.query(0)
+    assert q["mode"] == B.XL_MERGE and q["nlayers"] == 4 and p.num_launches(True) == 1
+    assert q["stores_fused"] == 64 * 56 * 56 and q["stores_unfused"] == (3 * 256 + 64) * 56 * 56
+    assert q["bytes_fused"] < q["bytes_unfused"] / 5
+
+
 def test_algorithmic_traffic_of_the_block_configs():
     want = {1: (51.3e3, 84.1e3), 2: (8.05e6, 20.89e6), 3: (43.41e6, 52.71e6), 4: (51.68e6, 180.13e6)}
     for cfg, (fused, unfused) in want.items():
@@ -115,7 +124,7 @@ def test_forced_tile_and_redundancy():
 
 def test_error_paths():
     wl = W.config(1)
-    wl.layers[0].groups = 16
+    wl.layers[0].groups = 4                  # grouped but not depthwise
     with pytest.raises(B.XlError) as e:
         B.Plan(wl)
     assert e.value.status == B.XL_E_UNSUPPORTED

@@ -167,6 +167,16 @@ def test_depthwise_then_convolution(wl):
     assert s.plan.num_launches(True) == 1 and s.plan.num_launches(False) == 2
 
 
+@pytest.mark.parametrize("wl", [
+    W.merge_two_producers(2, 64, 56, 56, 256, 64),                           # paper Table 1, c.1, batch 2
+    W.merge_two_producers(1, 24, 9, 11, 72, 40, bn=False),                   # ragged pixels and channels
+    W.merge_two_producers(2, 16, 7, 7, 33, 20, relu_a=True, relu_sum=False), # activation on one producer, none on the sum
+], ids=lambda w: w.name)
+def test_merge_block_with_two_producers(wl):
+    out, ref, s = run_both(wl)
+    assert s.plan.num_launches(True) == 1 and s.plan.num_launches(False) == 4
+
+
 def test_degenerate_shapes():
     """1x1 images, single channels, tiles larger than the image, odd sizes under stride 2."""
     for wl in (W.single_conv(1, 1, 1, 1, 1, 1),

@@ -259,6 +259,19 @@ def depthwise_pointwise(n, c, h, w, c2, k1=3, p1=1, s1=1, k2=1, p2=0, bn1=False,
     return b.done(t, dist, seed)
 
 
+def merge_two_producers(n=1, c=64, h=56, w=56, cmid=256, cout=64, bn=True, relu_a=False, relu_b=False,
+                        relu_sum=True, seed=11, dist="relu_normal") -> Workload:
+    """Merge mode with two producer layers (paper Fig. 4c; Table 1, case c.1: two 1x1 convolutions
+    64 -> 256 of the same input, added, feeding a 1x1 convolution 256 -> 64)."""
+    b = _Builder(f"merge2_{c}x{h}x{w}_{cmid}_{cout}", n, c, h, w)
+    a = b.conv(0, cmid, 1, bias=not bn, bn=bn, relu=relu_a, name="producer_a")
+    bb = b.conv(0, cmid, 1, bias=not bn, bn=bn, relu=relu_b, name="producer_b")
+    t = b.add(a, bb, relu=relu_sum, name="add")
+    t = b.conv(t, cout, 1, bias=not bn, bn=bn, relu=True, name="consumer")
+    b.group("merge", 0)
+    return b.done(t, dist, seed)
+
+
 def conv_gap_generic(n, cin, h, w, c1, k1, p1, s1, bn=False, relu=True, seed=9, dist="relu_normal") -> Workload:
     """Convolution -> global average pooling as one straight block (the head of config 5)."""
     b = _Builder(f"convgap_{cin}x{h}x{w}_{c1}k{k1}", n, cin, h, w)
