@@ -98,14 +98,14 @@ static std::vector<int> tile_candidates(int extent)
 static double mfma_clk(int mf) { return mf == 32 ? 64.0 : 32.0; }
 
 // Largest number of K steps per chunk the stagers can hold, shortened so that one chunk keeps
-// the matrix cores busy for a few thousand cycles (amortises the per-chunk barrier) and no more.
-static int pick_chunk(int nkg, int x_units_per_kg, int w_items_per_kg, int threads, double clk_per_kg)
+// the matrix cores busy for about `want_clk` cycles (amortises the per-chunk barrier) and no more.
+static int pick_chunk(int nkg, int x_units_per_kg, int w_items_per_kg, int threads, double clk_per_kg, double want_clk)
 {
     int cap = nkg;
     if (x_units_per_kg > 0) cap = std::min(cap, STAGE_UNITS * threads / x_units_per_kg);
     cap = std::min(cap, MAX_W_CHUNK_BYTES / (16 * std::max(w_items_per_kg, 1)));
     if (cap < 1) return 0;
-    int want = (int)std::ceil(8000.0 / std::max(clk_per_kg, 1.0));
+    int want = (int)std::ceil(want_clk / std::max(clk_per_kg, 1.0));
     int chunk = std::max(1, std::min(cap, want));
     const int nchunks = ceil_div(nkg, chunk);
     return std::min(cap, ceil_div(nkg, nchunks));       // balance the chunks
@@ -231,7 +231,8 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                 if (!dw && b.kind != KIND_SINGLE && wg_rt < nrt1) continue;     // stage 1 must produce every channel
                 if (!dw && wr > 1 && (wr / 2) * v.nrt1 >= nrt1) continue;       // more row waves than row tiles
                 const int px_cap = dw ? (1 << 30) : (nw / wr) * v.npt1 * mf1;
-                for (auto [th, tw] : tiles) {
+                for (auto [th, tw] : tiles)
+                for (double want_clk : {16000.0, 8000.0}) {     // longer chunks = fewer barriers, if LDS allows
                     Choice c;
                     c.v = v;
                     c.threads = threads;
@@ -263,7 +264,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     const int w_per_kg = taps1 * wg_rt * 64;
                     const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * 4 * mfma_clk(mf1);
                     const int x_units_per_kg = gps_of(mf1) * c.ih * ceil_div(c.iw, 4);     // 4-pixel row pieces
-                    c.chunk_kg = dw ? 1 : pick_chunk(nkg1, x_units_per_kg, w_per_kg, threads, clk1);
+                    c.chunk_kg = dw ? 1 : pick_chunk(nkg1, x_units_per_kg, w_per_kg, threads, clk1, want_clk);
                     if (c.chunk_kg < 1) continue;
                     c.w_off1 = c.chunk_kg * x_per_kg * 4 + 16;        // + slack for a left-edge unit running past the last row
                     int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
@@ -319,7 +320,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                         const int w2_per_kg = b.c2[i].k * b.c2[i].k * w2 * NRT2 * 64;
                                         const double clk2 = (double)(nw / 4.0) * NRT2 * NPT2 * b.c2[i].k * b.c2[i].k * 4 *
                                                             mfma_clk(v.mf2);
-                                        c.chunk_kg2[i] = pick_chunk(nkg2, 0, w2_per_kg, threads, clk2);
+                                        c.chunk_kg2[i] = pick_chunk(nkg2, 0, w2_per_kg, threads, clk2, want_clk);
                                         if (c.chunk_kg2[i] < 1) {
                                             fits = false;
                                             break;
