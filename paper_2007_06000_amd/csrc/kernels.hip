@@ -89,6 +89,18 @@ __device__ __forceinline__ int logical_block()
     return (blockIdx.x & 7) * per + (blockIdx.x >> 3);
 }
 
+// Buffer descriptor over [p, p + bytes) (clamped to 4 GB), raw dword addressing.  Address and size
+// are wave-uniform by construction; reading them through the first lane tells the compiler so --
+// otherwise every buffer access gets a loop over the distinct descriptor values of the wave.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned long long bytes)
+{
+    const unsigned long long a = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    const unsigned n = __builtin_amdgcn_readfirstlane((unsigned)(bytes < 0xffffffffull ? bytes : 0xffffffffull));
+    return __builtin_amdgcn_make_buffer_rsrc((void *)(((unsigned long long)hi << 32) | lo), (short)0, (int)n, 0x00020000);
+}
+
 // ----------------------------------------------------------------------------
 // K loop over one staged chunk: acc[r][p] += filter(row tile r) x pixels(pixel tile p).
 // Both operands come from LDS: `wsrc` holds the filter chunk as
@@ -96,7 +108,11 @@ __device__ __forceinline__ int logical_block()
 // [channel group][row][col][4].  Operands of the next (K step, tap) are fetched
 // while the matrix cores work on the current one.
 // ----------------------------------------------------------------------------
-template <int MF, int KS, int NRT, int NPT>
+// PX > 0: the pixels come from a planar source, [channel][PX * 64 floats] (only for 1x1 filters):
+// `off` then holds the pixel index plus this lane's channel-group offset, and the four channels of a
+// K step quarter are four 4-byte reads PX * 64 floats apart (paired by the compiler into two reads
+// with 64-dword strides) instead of one 16-byte read.
+template <int MF, int KS, int NRT, int NPT, int PX = 0>
 __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT],
                                            const float *bsrc, const int (&off)[NPT], int src_w, int gstride,
                                            const float *wsrc, const int (&rloc)[NRT], int wg_rt, int nkg)
@@ -110,9 +126,18 @@ __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT]
         const float *w = wsrc + ((kg * T + t) * wg_rt * 64 + lane) * 4;
 #pragma unroll
         for (int r = 0; r < NRT; ++r) ra[r] = *(const f32x4 *)(w + rloc[r] * 256);
-        const float *s = bsrc + kg * (M::GPS * gstride) + (u * src_w + v) * 4;
+        if constexpr (PX == 0) {
+            const float *s = bsrc + kg * (M::GPS * gstride) + (u * src_w + v) * 4;
 #pragma unroll
-        for (int p = 0; p < NPT; ++p) rb[p] = *(const f32x4 *)(s + off[p]);
+            for (int p = 0; p < NPT; ++p) rb[p] = *(const f32x4 *)(s + off[p]);
+        } else {
+            static_assert(PX == 0 || KS == 1, "planar pixel source is for 1x1 filters");
+            const float *s = bsrc + kg * (M::KC * PX * 64);
+#pragma unroll
+            for (int p = 0; p < NPT; ++p)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) rb[p][j] = s[off[p] + j * (PX * 64)];
+        }
     };
     fetch(a[0], b[0], 0, 0);
     for (int kg = 0; kg < nkg; ++kg) {
@@ -154,7 +179,7 @@ struct PassGeom {
     bool active;        // this wave owns at least one real tile
 };
 
-template <int MF, int KS, int NRT, int NPT, bool STAGE_X>
+template <int MF, int KS, int NRT, int NPT, bool STAGE_X, int PX = 0>
 __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P, const ConvW &c,
                                           const PassGeom &g, const float *bsrc, const int (&off)[NPT], float *buf,
                                           const float *__restrict__ ximg, unsigned long long x_bytes, int iy0, int ix0)
@@ -175,10 +200,9 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     // never stored.  Everything but the per-lane offset is wave-uniform, so a row costs a handful of
     // scalar instructions.  (The buffer form of the load is used, not the global/flat one: the
     // compiler then keeps counting outstanding LDS reads exactly instead of waiting for all of them.)
-    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves_wg = nthreads >> 6;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves_wg = nthreads >> 6, lane_id = tid & 63;
     const int nkt = c.nkg * T;
-    const __amdgpu_buffer_rsrc_t wrsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)c.wp, (short)0, nkt * c.nrt * 1024, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc = make_rsrc(c.wp, (unsigned long long)nkt * c.nrt * 1024ull);
     const int w_lane = (tid & 63) * 16;
     const int w_dkt = nwaves_wg / g.wg_rt, w_drl = nwaves_wg - w_dkt * g.wg_rt;       // row step = nwaves rows
     const int w_kt0 = wave_id / g.wg_rt, w_rl0 = wave_id - w_kt0 * g.wg_rt;
@@ -197,6 +221,58 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             if (rl >= g.wg_rt) { rl -= g.wg_rt; ++kt; }
         }
     };
+
+    if constexpr (PX > 0) {
+        // ---- planar input (1x1 filter, the tile is one whole row of at most PX * 64 pixels): the chunk
+        // is staged as [channel][PX * 64 floats] with LDS-direct 16-byte loads, exactly like the filter
+        // rows -- no registers, no vector-ALU work.  A wave instruction fills 256 consecutive floats of
+        // the chunk; lane l of load i of this wave holds quad Q = (i * nwaves + wave) * 64 + l, i.e.
+        // pixels 4q .. 4q+3 of channel Q / (PX * 16), q = Q % (PX * 16).  Quads past the row's end read
+        // whatever follows in memory (the next channel, or zeros past the tensor): those LDS columns
+        // only feed pixel lanes that are never stored.  Cin is a multiple of the K step (planner).
+        static_assert(STAGE_X && KS == 1, "planar staging is for stage 1 of 1x1 filters");
+        constexpr int QPR = PX * 16;                                   // quads per channel row in LDS
+        const int HWp = P.H * P.W;
+        const __amdgpu_buffer_rsrc_t xr = make_rsrc(ximg, x_bytes);
+        unsigned xvo[PLANAR_SLOTS];
+#pragma unroll
+        for (int i = 0; i < PLANAR_SLOTS; ++i) {
+            const int Q = (i * nwaves_wg + wave_id) * 64 + lane_id;
+            const int ch = Q / QPR, q = Q - ch * QPR;
+            xvo[i] = (unsigned)((ch * HWp + 4 * q) * 4);
+        }
+        auto load_xp = [&](float *dst, int c0) {
+            const int loads = min(g.chunk_kg, c.nkg - c0 / M::KC) * (M::KC * QPR / 64);     // wave loads in this chunk
+            const int soff = c0 * HWp * 4;
+#pragma unroll
+            for (int i = 0; i < PLANAR_SLOTS; ++i) {
+                const int id = i * nwaves_wg + wave_id;
+                if (id < loads)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(dst + id * 256),
+                                                             16, xvo[i], soff, 0, 0);
+            }
+        };
+        const int nchunks = (c.nkg + g.chunk_kg - 1) / g.chunk_kg;
+        load_w(buf + g.w_off, 0);
+        load_xp(buf, 0);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        for (int ch = 0; ch < nchunks; ++ch) {
+            float *cur = buf + (ch & 1) * g.buf_stride;
+            float *nxt = buf + ((ch + 1) & 1) * g.buf_stride;
+            const int kg0 = ch * g.chunk_kg;
+            if (ch + 1 < nchunks) {
+                load_w(nxt + g.w_off, kg0 + g.chunk_kg);
+                load_xp(nxt, (kg0 + g.chunk_kg) * M::KC);
+            }
+            if (g.active)
+                conv_accum<MF, KS, NRT, NPT, PX>(acc, cur, off, 0, 0, cur + g.w_off, rloc, g.wg_rt,
+                                                 min(g.chunk_kg, c.nkg - kg0));
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+        }
+        return;
+    }
 
     // ---- input stager: NCHW -> [group][row][col][4 channels].  A unit is 4 channels x 4 consecutive
     // pixels of one tile row: four 16-byte buffer loads (one per channel), transposed in registers into
@@ -248,8 +324,7 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         if constexpr (STAGE_X) {
             const unsigned long long skip = (unsigned long long)c0 * HW * 4ull;
             const unsigned long long left = x_bytes > skip ? x_bytes - skip : 0ull;
-            xrsrc = __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)ximg + skip), (short)0,
-                                                      (int)(unsigned)min(left, 0xffffffffull), 0x00020000);
+            xrsrc = make_rsrc((const char *)ximg + skip, left);
 #pragma unroll
             for (int i = 0; i < NU; ++i) {
                 if (i * nthreads < x_units) {      // uniform: skips unit slots no thread uses
@@ -430,12 +505,11 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     if (wide) {
         // descriptors end with the tensors: whatever a 16-byte access would touch past the end is dropped
         const unsigned long long ybytes = ((unsigned long long)(P.N - n) * P.Cy - coff) * plane * 4ull;
-        const __amdgpu_buffer_rsrc_t yr =
-            __builtin_amdgcn_make_buffer_rsrc((void *)yn, (short)0, (int)(unsigned)min(ybytes, 0xffffffffull), 0x00020000);
+        const __amdgpu_buffer_rsrc_t yr = make_rsrc(yn, ybytes);
         __amdgpu_buffer_rsrc_t sr = yr;
         if constexpr (HAS_SC) {
             const unsigned long long sbytes = (unsigned long long)(P.N - n) * P.Csc * plane * 4ull;
-            sr = __builtin_amdgcn_make_buffer_rsrc((void *)scn, (short)0, (int)(unsigned)min(sbytes, 0xffffffffull), 0x00020000);
+            sr = make_rsrc(scn, sbytes);
         }
         const int t = lane & 3;
         int nvs[NPT];
@@ -676,8 +750,7 @@ __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mi
     const ConvW &c = P.c1;
     const int ncg = (P.Cin + 3) >> 2;
     const int HW = P.H * P.W;
-    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)ximg, (short)0, (int)(unsigned)min(x_bytes, 0xffffffffull), 0x00020000);
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(ximg, x_bytes);
     const int in_px = P.ih * P.iw;
     for (int it = threadIdx.x; it < ncg * in_px; it += blockDim.x) {
         const int g = it / in_px, rem = it - g * in_px;
@@ -748,6 +821,9 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     typedef MM<MF1> M1;
+    // single-layer kernels have no second sibling: the K2B slot of their variant names the planar
+    // pixel source of stage 1 (0 = the interleaved one), in units of 64 floats per channel row
+    constexpr int PX1 = (KIND == KIND_SINGLE) ? K2B : 0;
 
     // tile origins: output -> intermediate (stage-2 window) -> input (stage-1 window)
     const int my0 = (KIND == KIND_SINGLE) ? oy0 : oy0 * P.s2 - P.P2;
@@ -789,12 +865,13 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
             int pidx = (pt0 + p) * MF1 + col;
             pidx = pidx < npx1 ? pidx : 0;
             const int my = pidx / P.mw, mx = pidx - my * P.mw;
-            off1[p] = ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * P.in_gstride;
+            off1[p] = PX1 > 0 ? pidx + sub * (4 * PX1 * 64)
+                              : ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * P.in_gstride;
         }
     }
     XL_PHASE(L, 0);
-    conv_pass<MF1, K1, NRT1, NPT1, true>(acc, P, P.c1, g1, nullptr, off1, buf, ximg,
-                                         (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
+    conv_pass<MF1, K1, NRT1, NPT1, true, PX1>(acc, P, P.c1, g1, nullptr, off1, buf, ximg,
+                                              (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
     XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {

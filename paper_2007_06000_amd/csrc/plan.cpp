@@ -219,6 +219,12 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
         if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0)) continue;
+        // single-layer variants with a planar input source (K2B slot = floats per channel row / 64):
+        // pointwise, the tile is the one whole row of the flattened image, whole K steps of channels
+        const int px = v.kind == KIND_SINGLE ? v.k2b : 0;
+        if (px > 0 && !(b.c1.k == 1 && b.c1.stride == 1 && b.c1.pad == 0 && b.H == 1 && b.W <= px * 64 &&
+                        b.c1.cin % kc_of(v.mf1) == 0))
+            continue;
         const int mf1 = v.mf1;
         const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
         const int taps1 = b.c1.k * b.c1.k;
@@ -233,6 +239,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                 const int px_cap = dw ? (1 << 30) : (nw / wr) * v.npt1 * mf1;
                 for (auto [th, tw] : tiles)
                 for (double want_clk : {16000.0, 8000.0}) {     // longer chunks = fewer barriers, if LDS allows
+                    if (px > 0 && (th != 1 || tw != b.W)) continue;
                     Choice c;
                     c.v = v;
                     c.threads = threads;
@@ -264,9 +271,12 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     const int w_per_kg = taps1 * wg_rt * 64;
                     const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * 4 * mfma_clk(mf1);
                     const int x_units_per_kg = gps_of(mf1) * c.ih * ceil_div(c.iw, 4);     // 4-pixel row pieces
-                    c.chunk_kg = dw ? 1 : pick_chunk(nkg1, x_units_per_kg, w_per_kg, threads, clk1, want_clk);
+                    c.chunk_kg = dw ? 1 : pick_chunk(nkg1, px > 0 ? 0 : x_units_per_kg, w_per_kg, threads, clk1, want_clk);
+                    if (px > 0)     // planar chunk: kc x px x 16 quads per K step, at most PLANAR_SLOTS wave loads per wave
+                        c.chunk_kg = std::min(c.chunk_kg, PLANAR_SLOTS * nw * 64 / (kc_of(mf1) * px * 16));
                     if (c.chunk_kg < 1) continue;
                     c.w_off1 = c.chunk_kg * x_per_kg * 4 + 16;        // + slack for a left-edge unit running past the last row
+                    if (px > 0) c.w_off1 = c.chunk_kg * kc_of(mf1) * px * 64;
                     int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
                     c.mid_floats = b.kind == KIND_SINGLE ? 0 : nrt1 * mf1 / 4 * c.mh * c.mw * 4;
                     if (dw) {       // the whole input tile, every channel, staged once; no filter chunk

@@ -101,6 +101,8 @@ struct Variant {
     X(42, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 0, 0)           \
     X(43, KIND_SINGLE, 32, 1, 1, 3, 0, 0, 0, 0, 0, 0)           \
     X(44, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0)           \
+    /* pointwise on one whole row of <= 192 pixels, planar input chunks (K2B slot = 3 x 64 floats per row) */ \
+    X(62, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 3, 0)           \
     X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0)            \
     X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0)            \
     X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0, 0, 0)            \
@@ -168,6 +170,7 @@ const std::vector<Variant> &variants();
 
 constexpr int STAGE_UNITS = 1;      // input units (4 channels x 4 pixels) each thread stages per chunk
 constexpr int MAX_W_CHUNK_BYTES = 52 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
+constexpr int PLANAR_SLOTS = 4;     // LDS-direct loads per wave and chunk of a planar input chunk
 constexpr int MAX_THREADS = 512;
 constexpr int MAX_ALTERNATIVES = 16;  // candidates per block kept for on-device tuning
 #ifndef XL_MIN_WAVES
