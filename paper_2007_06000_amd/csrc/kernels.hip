@@ -139,19 +139,32 @@ __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT]
                 for (int j = 0; j < 4; ++j) rb[p][j] = s[off[p] + j * (PX * 64)];
         }
     };
+    // Two operand sets alternate: a step computes from set `cur` while the other one is being fetched;
+    // `cur` is a constant once the tap loop is unrolled, so the sets are plain registers.
+    static_assert(T % 2 == 1, "filter taps are odd");
+    auto step = [&](int cur, int kg, int t) {
+        if (t + 1 < T || kg + 1 < nkg) fetch(a[cur ^ 1], b[cur ^ 1], kg + (t + 1) / T, (t + 1) % T);
+        __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of this step's matrix ops
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < NRT; ++r)
+#pragma unroll
+                for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(a[cur][r][j], b[cur][p][j], acc[r][p]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
     fetch(a[0], b[0], 0, 0);
-    for (int kg = 0; kg < nkg; ++kg) {
+    if constexpr (T == 1) {
+        for (int kg = 0; kg < nkg; kg += 2) {
+            step(0, kg, 0);
+            if (kg + 1 < nkg) step(1, kg + 1, 0);
+        }
+    } else {
+        // with several taps per K step the two sets swap roles once per K step only: one copy there
+        // costs less than the registers a loop body of two K steps would take
+        for (int kg = 0; kg < nkg; ++kg) {
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            if (t + 1 < T || kg + 1 < nkg) fetch(a[1], b[1], kg + (t + 1) / T, (t + 1) % T);
-            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of this step's matrix ops
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < NRT; ++r)
-#pragma unroll
-                    for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(a[0][r][j], b[0][p][j], acc[r][p]);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int t = 0; t < T; ++t) step(t & 1, kg, t);
 #pragma unroll
             for (int r = 0; r < NRT; ++r) a[0][r] = a[1][r];
 #pragma unroll
