@@ -225,7 +225,7 @@ class Plan:
         self._check(lib().xl_run(self.handle, arr, self.ntensors, ctypes.c_void_p(workspace_ptr),
                                  ctypes.c_void_p(stream), int(fused)))
 
-    def tune(self, tensor_ptrs: Dict[int, int], workspace_ptr: int, stream: int = 0, reps: int = 3):
+    def tune(self, tensor_ptrs: Dict[int, int], workspace_ptr: int, stream: int = 0, reps: int = 5):
         arr = (ctypes.c_void_p * self.ntensors)()
         for t, p in tensor_ptrs.items():
             arr[t] = p

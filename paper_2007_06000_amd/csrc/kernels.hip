@@ -236,23 +236,31 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     };
 
     if constexpr (PX > 0) {
-        // ---- planar input (1x1 filter, the tile is one whole row of at most PX * 64 pixels): the chunk
-        // is staged as [channel][PX * 64 floats] with LDS-direct 16-byte loads, exactly like the filter
-        // rows -- no registers, no vector-ALU work.  A wave instruction fills 256 consecutive floats of
-        // the chunk; lane l of load i of this wave holds quad Q = (i * nwaves + wave) * 64 + l, i.e.
-        // pixels 4q .. 4q+3 of channel Q / (PX * 16), q = Q % (PX * 16).  Quads past the row's end read
-        // whatever follows in memory (the next channel, or zeros past the tensor): those LDS columns
-        // only feed pixel lanes that are never stored.  Cin is a multiple of the K step (planner).
+        // ---- planar input (1x1 filter, stride 1, no padding: the input tile is the tile of layer 1):
+        // the chunk is staged as [channel][PX * 64 floats], each channel holding the ih rows of the tile,
+        // iws floats apart, with LDS-direct 16-byte loads, exactly like the filter rows -- no registers,
+        // no vector-ALU work.  A wave instruction fills 256 consecutive floats of the chunk; lane l of
+        // load i of this wave holds quad Q = (i * nwaves + wave) * 64 + l: channel Q / (PX * 16), and
+        // inside the channel row rq / (iws / 4), pixels 4q .. 4q+3 of that row.  Rows start at the first
+        // tile column inside the image (xs, see below): a quad that began left of the tensor's first
+        // element would read as zeros altogether.  Whatever a quad holds outside the image (rows are
+        // clamped into it, a quad may run past its row's end into the next one, or into zeros past the
+        // tensor) only feeds pixels of layer 1 outside the image, which the epilogue discards or
+        // overwrites.  Cin is a multiple of the K step (planner).
         static_assert(STAGE_X && KS == 1, "planar staging is for stage 1 of 1x1 filters");
-        constexpr int QPR = PX * 16;                                   // quads per channel row in LDS
+        constexpr int QPR = PX * 16;                                   // quads per channel in LDS
         const int HWp = P.H * P.W;
+        const int qrow = P.iws >> 2;                                   // quads per tile row
+        const int xs = max(0, -ix0);
         const __amdgpu_buffer_rsrc_t xr = make_rsrc(ximg, x_bytes);
         unsigned xvo[PLANAR_SLOTS];
 #pragma unroll
         for (int i = 0; i < PLANAR_SLOTS; ++i) {
             const int Q = (i * nwaves_wg + wave_id) * 64 + lane_id;
-            const int ch = Q / QPR, q = Q - ch * QPR;
-            xvo[i] = (unsigned)((ch * HWp + 4 * q) * 4);
+            const int ch = Q / QPR, rq = Q - ch * QPR;
+            const int r = min(rq / qrow, P.ih - 1), q = rq - (rq / qrow) * qrow;
+            const int gy = min(max(iy0 + r, 0), P.H - 1);
+            xvo[i] = (unsigned)((ch * HWp + gy * P.W + ix0 + xs + 4 * q) * 4);
         }
         auto load_xp = [&](float *dst, int c0) {
             const int loads = min(g.chunk_kg, c.nkg - c0 / M::KC) * (M::KC * QPR / 64);     // wave loads in this chunk
@@ -818,7 +826,7 @@ __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mi
 // ----------------------------------------------------------------------------
 // The block kernel
 // ----------------------------------------------------------------------------
-template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC>
+template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC, int PX1>
 __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const BlockParams P)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -834,9 +842,6 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     typedef MM<MF1> M1;
-    // single-layer kernels have no second sibling: the K2B slot of their variant names the planar
-    // pixel source of stage 1 (0 = the interleaved one), in units of 64 floats per channel row
-    constexpr int PX1 = (KIND == KIND_SINGLE) ? K2B : 0;
 
     // tile origins: output -> intermediate (stage-2 window) -> input (stage-1 window)
     const int my0 = (KIND == KIND_SINGLE) ? oy0 : oy0 * P.s2 - P.P2;
@@ -878,7 +883,7 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
             int pidx = (pt0 + p) * MF1 + col;
             pidx = pidx < npx1 ? pidx : 0;
             const int my = pidx / P.mw, mx = pidx - my * P.mw;
-            off1[p] = PX1 > 0 ? pidx + sub * (4 * PX1 * 64)
+            off1[p] = PX1 > 0 ? my * P.iws + max(mx - max(0, -ix0), 0) + sub * (4 * PX1 * 64)
                               : ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * P.in_gstride;
         }
     }
@@ -909,7 +914,7 @@ __global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const 
                 for (int p = 0; p < NPT1; ++p)
 #pragma unroll
                     for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
-                conv_pass<MF1, K1, NRT1, NPT1, true>(acc, P, P.c1b, g1, nullptr, off1, buf, ximg,
+                conv_pass<MF1, K1, NRT1, NPT1, true, PX1>(acc, P, P.c1b, g1, nullptr, off1, buf, ximg,
                                                      (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
                 store_mid<MF1, NRT1, NPT1>(acc, P, P.c1b, mid, my0, mx0, rt0, rt_end1, pt0, npx1, 0.f, true,
                                            P.relu_mid != 0);
@@ -1015,10 +1020,10 @@ typedef void (*BlockKernel)(const BlockParams);
 static BlockKernel kernel_of(int variant)
 {
     switch (variant) {
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC)                            \
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1)                       \
     case ID:                                                                                       \
         return block_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2), (NRT2 == 0 ? 1 : NRT2), \
-                            (NPT2 == 0 ? 1 : NPT2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0)>;
+                            (NPT2 == 0 ? 1 : NPT2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0), PX1>;
         XL_VARIANT_LIST(X)
 #undef X
     }
@@ -1028,8 +1033,8 @@ static BlockKernel kernel_of(int variant)
 const std::vector<Variant> &variants()
 {
     static const std::vector<Variant> v = {
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC) \
-    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC},
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1) \
+    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1},
         XL_VARIANT_LIST(X)
 #undef X
     };

@@ -130,6 +130,7 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
         if (rt0 < rt_end && pt0 * mf1 < npx1) simd[w % 4] += wave1;
     }
     double t1 = *std::max_element(simd, simd + 4) * b.n1;
+    if (v.px1 > 0) t1 *= 0.9;       // planar input chunks: no register staging, no vector-ALU work in the K loop
     int barriers = ceil_div(nkg1, c.chunk_kg) * b.n1;
     if (b.kind == KIND_DW) {
         // vector ALU: staging one float4 per (channel group, input pixel), then per (channel group,
@@ -219,12 +220,10 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
         if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0)) continue;
-        // single-layer variants with a planar input source (K2B slot = floats per channel row / 64):
-        // pointwise, the tile is the one whole row of the flattened image, whole K steps of channels
-        const int px = v.kind == KIND_SINGLE ? v.k2b : 0;
-        if (px > 0 && !(b.c1.k == 1 && b.c1.stride == 1 && b.c1.pad == 0 && b.H == 1 && b.W <= px * 64 &&
-                        b.c1.cin % kc_of(v.mf1) == 0))
-            continue;
+        // variants whose stage 1 reads planar input chunks: a 1x1 filter, stride 1, no padding, whole
+        // K steps of channels; the tile's ih rows of iws floats must fit px * 64 floats per channel
+        const int px = v.px1;
+        if (px > 0 && !(b.c1.k == 1 && b.c1.stride == 1 && b.c1.pad == 0 && b.c1.cin % kc_of(v.mf1) == 0)) continue;
         const int mf1 = v.mf1;
         const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
         const int taps1 = b.c1.k * b.c1.k;
@@ -239,7 +238,6 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                 const int px_cap = dw ? (1 << 30) : (nw / wr) * v.npt1 * mf1;
                 for (auto [th, tw] : tiles)
                 for (double want_clk : {16000.0, 8000.0}) {     // longer chunks = fewer barriers, if LDS allows
-                    if (px > 0 && (th != 1 || tw != b.W)) continue;
                     Choice c;
                     c.v = v;
                     c.threads = threads;
@@ -264,6 +262,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     if (c.mh * c.mw > px_cap) continue;
                     c.ih = required_extent(c.mh, b.c1.k, b.c1.stride);
                     c.iw = required_extent(c.mw, b.c1.k, b.c1.stride);
+                    if (px > 0 && c.ih * ((c.iw + 3) / 4 * 4) > px * 64) continue;
                     c.tiles_y = ceil_div(b.Ho, th);
                     c.tiles_x = ceil_div(b.Wo, tw);
                     // stage-1 chunk: input tile chunk + filter chunk per buffer

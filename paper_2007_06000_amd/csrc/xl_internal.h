@@ -91,88 +91,102 @@ struct Variant {
     int mf2, nrt2, npt2;        // stage 2: matrix-core tile, tiles per wave (0 when unused)
     int k2a, k2b;               // stage 2 filter sizes, heavier sibling first (0 = absent)
     int sc;                     // 1: adds a shortcut tensor in the epilogue (merge mode)
+    int px1;                    // > 0: stage 1 (1x1 filter) reads a planar input chunk, px1 * 64 floats per channel
 };
 
-// id, kind, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC
+// id, kind, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1
 #define XL_VARIANT_LIST(X)                                \
-    X(0, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0)            \
-    X(1, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0)            \
-    X(2, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0)            \
-    X(42, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 0, 0)           \
-    X(43, KIND_SINGLE, 32, 1, 1, 3, 0, 0, 0, 0, 0, 0)           \
-    X(44, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0)           \
-    /* pointwise on one whole row of <= 192 pixels, planar input chunks (K2B slot = 3 x 64 floats per row) */ \
-    X(62, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 3, 0)           \
-    X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0)            \
-    X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0)            \
-    X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0, 0, 0)            \
-    X(6, KIND_SINGLE, 16, 1, 1, 1, 0, 0, 0, 0, 0, 0)            \
-    X(7, KIND_SINGLE, 16, 1, 1, 2, 0, 0, 0, 0, 0, 0)            \
-    X(8, KIND_SINGLE, 16, 1, 3, 2, 0, 0, 0, 0, 0, 0)            \
-    X(9, KIND_SINGLE, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0)            \
-    X(10, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0, 0, 0)           \
+    X(0, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(1, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(2, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0, 0)            \
+    X(42, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 0, 0, 0)           \
+    X(43, KIND_SINGLE, 32, 1, 1, 3, 0, 0, 0, 0, 0, 0, 0)           \
+    X(44, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0, 0)           \
+    /* 1x1 first layer with planar input chunks staged by LDS-direct loads (PX1 x 64 floats per channel) */ \
+    X(62, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 0, 0, 3)          \
+    X(63, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0, 2)          \
+    X(64, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0, 4)          \
+    X(65, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0, 4)          \
+    X(66, KIND_FUSED2, 16, 1, 1, 1, 32, 2, 1, 3, 1, 0, 2)         \
+    X(67, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 4)         \
+    X(68, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 4)         \
+    X(69, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 2)         \
+    X(70, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 4)         \
+    X(71, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 4)         \
+    X(72, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 4)         \
+    X(73, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0, 2)         \
+    X(74, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0, 4)         \
+    X(75, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 1, 0, 0, 2)           \
+    X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0, 0, 0, 0)            \
+    X(6, KIND_SINGLE, 16, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(7, KIND_SINGLE, 16, 1, 1, 2, 0, 0, 0, 0, 0, 0, 0)            \
+    X(8, KIND_SINGLE, 16, 1, 3, 2, 0, 0, 0, 0, 0, 0, 0)            \
+    X(9, KIND_SINGLE, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(10, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)           \
     /* split (fire-like): 1x1 -> {3x3, 1x1} */            \
-    X(11, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0)          \
-    X(12, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0)          \
-    X(13, KIND_FUSED2, 16, 1, 1, 1, 32, 2, 1, 3, 1, 0)          \
-    X(14, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0)          \
-    X(15, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0)          \
-    X(16, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0)          \
-    X(17, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 1, 0)          \
-    X(18, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0)          \
+    X(11, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)          \
+    X(12, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 0)          \
+    X(13, KIND_FUSED2, 16, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)          \
+    X(14, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)          \
+    X(15, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 0)          \
+    X(16, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 0)          \
+    X(17, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 1, 0, 0)          \
+    X(18, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0, 0)          \
     /* straight conv -> conv, and merge (with shortcut) */ \
-    X(19, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0)          \
-    X(20, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1)          \
-    X(21, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0)          \
-    X(22, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 1)          \
-    X(23, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 3, 0, 0)          \
-    X(24, KIND_FUSED2, 16, 3, 1, 3, 16, 1, 2, 3, 0, 0)          \
-    X(25, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 3, 0, 1)          \
-    X(26, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 0)          \
-    X(27, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 0)          \
-    X(28, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0)          \
-    X(29, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 0)          \
-    X(30, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 0, 0)          \
-    X(31, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 1, 0, 0)          \
-    X(60, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 1, 0, 0)          \
-    X(61, KIND_FUSED2, 16, 1, 2, 2, 16, 1, 2, 1, 0, 0)          \
-    X(32, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 1)          \
-    X(33, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 1)          \
-    X(34, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 1)          \
-    X(35, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 0, 1)          \
+    X(19, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0, 0)          \
+    X(20, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1, 0)          \
+    X(21, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0, 0)          \
+    X(22, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 1, 0)          \
+    X(23, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 3, 0, 0, 0)          \
+    X(24, KIND_FUSED2, 16, 3, 1, 3, 16, 1, 2, 3, 0, 0, 0)          \
+    X(25, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 3, 0, 1, 0)          \
+    X(26, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 0, 0)          \
+    X(27, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 0, 0)          \
+    X(28, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0, 0)          \
+    X(29, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 0, 0)          \
+    X(30, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 0, 0, 0)          \
+    X(31, KIND_FUSED2, 16, 3, 1, 1, 16, 1, 2, 1, 0, 0, 0)          \
+    X(60, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 1, 0, 0, 0)          \
+    X(61, KIND_FUSED2, 16, 1, 2, 2, 16, 1, 2, 1, 0, 0, 0)          \
+    X(32, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 1, 0)          \
+    X(33, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 1, 0)          \
+    X(34, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 1, 0, 1, 0)          \
+    X(35, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 0, 1, 0)          \
     /* stage 2 on 16-pixel tiles, 7 per wave: finer padding of small tiles */ \
-    X(45, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 1)          \
-    X(46, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 0)          \
+    X(45, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 1, 0)          \
+    X(46, KIND_FUSED2, 32, 3, 2, 1, 16, 1, 7, 3, 0, 0, 0)          \
     /* 5x5 filters (paper Table 1, a.1: 1x1 -> 5x5) and their unfused forms */ \
-    X(47, KIND_SINGLE, 32, 5, 1, 1, 0, 0, 0, 0, 0, 0)             \
-    X(48, KIND_SINGLE, 32, 5, 2, 1, 0, 0, 0, 0, 0, 0)             \
-    X(49, KIND_SINGLE, 16, 5, 1, 2, 0, 0, 0, 0, 0, 0)             \
-    X(50, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0)            \
-    X(51, KIND_FUSED2, 16, 1, 1, 2, 32, 1, 1, 5, 0, 0)            \
-    X(52, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 1, 5, 0, 0)            \
-    X(53, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 5, 0, 0)            \
-    X(54, KIND_FUSED2, 32, 3, 1, 1, 32, 1, 1, 5, 0, 0)            \
+    X(47, KIND_SINGLE, 32, 5, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
+    X(48, KIND_SINGLE, 32, 5, 2, 1, 0, 0, 0, 0, 0, 0, 0)             \
+    X(49, KIND_SINGLE, 16, 5, 1, 2, 0, 0, 0, 0, 0, 0, 0)             \
+    X(50, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0, 0)            \
+    X(51, KIND_FUSED2, 16, 1, 1, 2, 32, 1, 1, 5, 0, 0, 0)            \
+    X(52, KIND_FUSED2, 32, 1, 1, 1, 32, 1, 1, 5, 0, 0, 0)            \
+    X(53, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 5, 0, 0, 0)            \
+    X(54, KIND_FUSED2, 32, 3, 1, 1, 32, 1, 1, 5, 0, 0, 0)            \
     /* depthwise -> pointwise (paper Table 1, a.2); MF1 / NRT1 / NPT1 unused */ \
-    X(55, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0)                \
-    X(56, KIND_DW, 32, 3, 1, 1, 32, 1, 1, 1, 0, 0)                \
-    X(57, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 1, 0, 0)                \
-    X(58, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0)                \
-    X(59, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 3, 0, 0)                \
+    X(55, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0, 0)                \
+    X(56, KIND_DW, 32, 3, 1, 1, 32, 1, 1, 1, 0, 0, 0)                \
+    X(57, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 1, 0, 0, 0)                \
+    X(58, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0, 0)                \
+    X(59, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 3, 0, 0, 0)                \
     /* conv -> maxpool */                                 \
-    X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0)             \
-    X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0)             \
-    X(38, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0)             \
-    X(39, KIND_POOL, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0)             \
-    X(40, KIND_POOL, 16, 1, 1, 1, 0, 0, 0, 0, 0, 0)             \
-    X(41, KIND_POOL, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0)
+    X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
+    X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)             \
+    X(38, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
+    X(39, KIND_POOL, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)             \
+    X(40, KIND_POOL, 16, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
+    X(41, KIND_POOL, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)
 
 const std::vector<Variant> &variants();
 
 constexpr int STAGE_UNITS = 1;      // input units (4 channels x 4 pixels) each thread stages per chunk
 constexpr int MAX_W_CHUNK_BYTES = 52 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
-constexpr int PLANAR_SLOTS = 4;     // LDS-direct loads per wave and chunk of a planar input chunk
+constexpr int PLANAR_SLOTS = 8;     // LDS-direct loads per wave and chunk of a planar input chunk
 constexpr int MAX_THREADS = 512;
-constexpr int MAX_ALTERNATIVES = 16;  // candidates per block kept for on-device tuning
+constexpr int MAX_ALTERNATIVES = 24;  // candidates per block kept for on-device tuning
 #ifndef XL_MIN_WAVES
 #define XL_MIN_WAVES 2
 #endif
