@@ -145,6 +145,28 @@ def test_conv_then_global_average_pooling(shape):
 
 
 @pytest.mark.parametrize("wl", [
+    W.single_conv(2, 64, 13, 13, 100, 1),               # one row of 169 pixels: width not a multiple of 4
+    W.single_conv(3, 32, 27, 27, 48, 1, bn=True),       # 729 pixels: several tiles per image, ragged last one
+    W.single_conv(1, 16, 5, 7, 8, 1),
+    W.single_conv(2, 128, 1, 1, 64, 1),                 # a single pixel
+    W.straight_generic(2, 64, 13, 11, 32, 1, 0, 1, 48, 3, 1, 1),        # 1x1 -> 3x3: halo rows/columns outside the image
+    W.straight_generic(1, 48, 9, 30, 16, 1, 0, 1, 24, 3, 1, 1, bn1=True),
+    W.config(3, n=2, hw=21, cin=64, s=16, e=32),                        # fire block, image not a multiple of any tile
+], ids=lambda w: w.name)
+def test_pointwise_first_layers_with_whole_k_steps_of_channels(wl):
+    """1x1 first layers whose channel count is a multiple of the K step may use the planar input
+    staging (LDS-direct loads); the cases cover unaligned rows, ragged tiles and image borders."""
+    for tune in (False, True):
+        from paper_2007_06000_amd.session import Session
+        x, params = W.make_tensors(wl)
+        ref = xlo.forward(wl, x, params)
+        s = Session(wl, x, params, tune=tune)
+        for fused in (True, False):
+            print(f"[case] {wl.name} tune={tune} fused={fused}", flush=True)
+            check(s.output(fused), ref, f"{wl.name} tune={tune} fused={fused}")
+
+
+@pytest.mark.parametrize("wl", [
     W.straight_generic(2, 192, 28, 28, 16, 1, 0, 1, 32, 5, 2, 1),       # paper Table 1, a.1 (inception 5x5 branch), batch 2
     W.straight_generic(1, 20, 11, 9, 24, 1, 0, 1, 40, 5, 2, 1, bn2=True),
     W.straight_generic(1, 8, 12, 12, 12, 3, 1, 1, 20, 5, 0, 1),         # 3x3 -> 5x5 without padding
