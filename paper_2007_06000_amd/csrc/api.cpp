@@ -1,5 +1,6 @@
 // C ABI of libxl (see include/xl.h).
 #include <cstdint>
+#include <algorithm>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -300,13 +301,10 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
                 if (rc != XL_OK) break;
                 continue;
             }
-            int best = 0;
-            float best_ms = 0.f;
-            for (size_t a = 0; a < st.alts.size() && rc == XL_OK; ++a) {
-                rc = launch_step(plan, st.alts[a], tensors, ws, s);         // warm-up (code, filters in L2)
-                if (rc != XL_OK) break;
-                float t_min = 1e30f;
-                for (int r = 0; r < reps && rc == XL_OK; ++r) {
+            // first a quick look at every candidate, then the few fastest again with more repetitions
+            auto time_alt = [&](size_t a, int n, float &t_min) {
+                t_min = 1e30f;
+                for (int r = 0; r < n && rc == XL_OK; ++r) {
                     (void)hipEventRecord(e0, s);
                     rc = launch_step(plan, st.alts[a], tensors, ws, s);
                     (void)hipEventRecord(e1, s);
@@ -319,9 +317,26 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
                     (void)hipEventElapsedTime(&ms, e0, e1);
                     t_min = ms < t_min ? ms : t_min;
                 }
-                if (rc == XL_OK && (a == 0 || t_min < best_ms)) {
-                    best = (int)a;
-                    best_ms = t_min;
+            };
+            std::vector<std::pair<float, int>> quick;
+            for (size_t a = 0; a < st.alts.size() && rc == XL_OK; ++a) {
+                rc = launch_step(plan, st.alts[a], tensors, ws, s);         // warm-up (code, filters in L2)
+                if (rc != XL_OK) break;
+                float t;
+                time_alt(a, 2, t);
+                quick.push_back({t, (int)a});
+            }
+            int best = 0;
+            float best_ms = 1e30f;
+            if (rc == XL_OK) {
+                std::sort(quick.begin(), quick.end());
+                for (size_t i = 0; i < quick.size() && i < 4 && rc == XL_OK; ++i) {
+                    float t;
+                    time_alt((size_t)quick[i].second, reps, t);
+                    if (t < best_ms) {
+                        best_ms = t;
+                        best = quick[i].second;
+                    }
                 }
             }
             if (rc != XL_OK) break;
