@@ -117,6 +117,15 @@ struct Variant {
     X(73, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0, 2)         \
     X(74, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0, 4)         \
     X(75, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 1, 0, 0, 2)           \
+    /* split blocks with 16-pixel stage-2 tiles, 7 per wave (finer padding of 14-wide tiles) */ \
+    X(76, KIND_FUSED2, 16, 1, 1, 2, 16, 1, 7, 3, 1, 0, 4)         \
+    X(77, KIND_FUSED2, 16, 1, 1, 3, 16, 1, 7, 3, 1, 0, 4)         \
+    X(78, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 7, 3, 1, 0, 4)         \
+    X(79, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 7, 3, 1, 0, 2)         \
+    X(80, KIND_FUSED2, 16, 1, 3, 2, 16, 1, 7, 3, 1, 0, 4)         \
+    X(81, KIND_FUSED2, 16, 1, 3, 2, 16, 1, 7, 3, 1, 0, 2)         \
+    X(82, KIND_FUSED2, 32, 1, 2, 1, 16, 1, 7, 3, 1, 0, 4)         \
+    X(83, KIND_FUSED2, 16, 1, 1, 2, 16, 1, 7, 3, 1, 0, 0)           \
     X(3, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
     X(4, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)            \
     X(5, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0, 0, 0, 0)            \
