@@ -827,7 +827,7 @@ __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mi
 // The block kernel
 // ----------------------------------------------------------------------------
 template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC, int PX1>
-__global__ void __launch_bounds__(MAX_THREADS, XL_MIN_WAVES) block_kernel(const BlockParams P)
+__global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_WAVES)) block_kernel(const BlockParams P)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int L = logical_block();

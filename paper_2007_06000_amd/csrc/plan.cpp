@@ -346,8 +346,11 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                     any_lds_reject = true;
                                     continue;
                                 }
+                                // waves per SIMD the registers allow: the conv -> pool kernels are built for 4
+                                // (at most 128 registers), the others for 2
+                                const int reg_waves = b.kind == KIND_POOL ? 16 : 8;
                                 c.occ = std::max(1, std::min({pl.lds_per_cu / std::max(c.lds_bytes, 1), 2048 / threads,
-                                                              8 / nw}));
+                                                              reg_waves / nw}));
                                 evaluate(b, pl, c);
                                 c.ok = true;
                                 if (!best.ok || c.cost < best.cost) best = c;
