@@ -104,7 +104,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=5, help="BASELINE config number 1..5 timed as the headline")
+    ap.add_argument("--workload", type=int, default=5, help="benchmark config number 1..5 timed as the headline")
     ap.add_argument("--headline-only", action="store_true", help="skip the per-config table reported under 'blocks'")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 256 MiB copy (calibration), then 3 fused and 3 unfused steps")
