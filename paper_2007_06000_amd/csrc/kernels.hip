@@ -1013,17 +1013,186 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
 }
 
 // ----------------------------------------------------------------------------
+// conv -> max pooling over a stream of tiles (KIND_POOLS).  For a first layer whose whole reduction
+// fits one chunk (a few input channels: the stem of an image network) a workgroup's life in
+// block_kernel is one long dependency chain: input latency, a short K loop, epilogue, pooling, stores.
+// Here a workgroup stays resident and walks tiles L, L + gridDim, ...: the filter is brought to LDS
+// once, and the input units of the next tile are requested before the matrix work of the current one,
+// so their latency hides behind K loop, epilogue and pooling.  Three barriers per tile:
+//   units -> LDS | barrier | request next tile's units, K loop, epilogue -> LDS tile | barrier |
+//   pooling -> HBM            (the next tile's "units -> LDS" follows; the first barrier of that tile
+//   separates it from this tile's K loop reads, the second from this tile's pooling reads)
+// LDS: [intermediate tile][input chunk][filter].  Geometry and parameters as in block_kernel.
+// ----------------------------------------------------------------------------
+template <int MF1, int K1, int NRT1, int NPT1>
+__global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const BlockParams P)
+{
+    typedef MM<MF1> M1;
+    typedef unsigned u32x4 __attribute__((vector_size(16)));
+    constexpr int T = K1 * K1;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float *mid = lds;
+    float *xbuf = lds + P.lds_buf_off;
+    float *wbuf = xbuf + P.w_off1;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int tiles = P.tiles_x * P.tiles_y;
+    const int HW = P.H * P.W;
+    const int npx1 = P.mh * P.mw;
+
+    // ---- the whole filter, once
+    {
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        const __amdgpu_buffer_rsrc_t wr = make_rsrc(P.c1.wp, (unsigned long long)P.c1.nkg * T * P.c1.nrt * 1024ull);
+        const int wg_rt = P.waves_r1 * NRT1;
+        const int rows = P.c1.nkg * T * wg_rt;
+        for (int row = wave_u; row < rows; row += nwaves) {
+            const int kt = row / wg_rt, rl = row - kt * wg_rt;
+            if (rl < P.c1.nrt)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wbuf + row * 256), 16,
+                                                         lane * 16, (kt * P.c1.nrt + rl) * 1024, 0, 0);
+        }
+    }
+
+    // ---- per-wave tile assignment inside a workgroup tile: as in block_kernel
+    const int wg_rt = P.waves_r1 * NRT1;
+    const int wr = wave % P.waves_r1;
+    const int rt_end1 = min(P.c1.nrt, wg_rt);
+    const int rt0 = wr * NRT1, pt0 = (wave / P.waves_r1) * NPT1;
+    const bool active = rt0 < rt_end1 && pt0 * MF1 < npx1;
+    int rloc[NRT1], off1[NPT1];
+#pragma unroll
+    for (int r = 0; r < NRT1; ++r) rloc[r] = wr * NRT1 + r;
+    {
+        const int sub = lane / MF1, col = lane % MF1;
+#pragma unroll
+        for (int p = 0; p < NPT1; ++p) {
+            int pidx = (pt0 + p) * MF1 + col;
+            pidx = pidx < npx1 ? pidx : 0;
+            const int my = pidx / P.mw, mx = pidx - my * P.mw;
+            off1[p] = ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * P.in_gstride;
+        }
+    }
+
+    // ---- input units of one tile (4 channels x 4 pixels, see conv_pass): one per lane
+    const int plane = P.ih * P.iws;
+    unsigned xoff = 0, xmask = 0;
+    int xdst = 0, xgrp = 0, xs = 0;
+    f32x4 xst[4];
+    __amdgpu_buffer_rsrc_t xr;
+    auto request = [&](int L) {         // descriptor, per-lane unit and loads for tile L
+        const int tile = L % tiles, n = L / tiles;
+        const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
+        const int iy0 = (ty * P.th * P.s2 - P.P2) * P.c1.stride - P.c1.pad;
+        const int ix0 = (tx * P.tw * P.s2 - P.P2) * P.c1.stride - P.c1.pad;
+        xs = max(0, -ix0);
+        const int qpr = (P.iw - xs + 3) >> 2;
+        const int upg = P.ih * qpr;
+        const int x_units = P.chunk_kg * M1::GPS * upg;      // the one chunk: every K step of the layer
+        const int u = tid;
+        const int gr = u / upg, rem = u - gr * upg;
+        const int r = rem / qpr, q = rem - r * qpr;
+        const int cc = xs + 4 * q;
+        const int gy = iy0 + r, gx = ix0 + cc;
+        const bool rowok = gy >= 0 && gy < P.H;
+        unsigned m = u < x_units ? (q == 0 ? 0x110u : 0x10u) : 0u;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            if (u < x_units && cc + kk < P.iw && rowok && gx + kk < P.W) m |= 1u << kk;
+        xmask = m;
+        xgrp = gr * 4;
+        xdst = (gr * plane + r * P.iws + cc) * 4;
+        xoff = (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4);
+        xr = make_rsrc(P.x + (size_t)n * P.Cin * HW, (unsigned long long)(P.N - n) * P.Cin * HW * 4ull);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xst[j] = __builtin_bit_cast(f32x4, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(xr, xoff, j * HW * 4, 0));
+    };
+    auto deposit = [&]() {              // the requested units -> LDS, masked (pixels outside the image, channels past Cin)
+        if (xmask & 0x10u) {
+            if (xs > 0 && (xmask & 0x100u)) {
+                for (int e = 1; e <= xs; ++e) *(f32x4 *)(xbuf + xdst - 4 * e) = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            const int live = P.Cin - xgrp;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bool in = (xmask >> kk) & 1u;
+                f32x4 v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = (in && j < live) ? xst[j][kk] : 0.f;
+                *(f32x4 *)(xbuf + xdst + 4 * kk) = v;
+            }
+        }
+    };
+
+    const int first = logical_block();
+    if (first >= P.nblocks) return;     // uniform per workgroup
+    request(first);
+    for (int L = first; L < P.nblocks; L += gridDim.x) {
+        const int tile = L % tiles, n = L / tiles;
+        const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
+        const int oy0 = ty * P.th, ox0 = tx * P.tw;
+        const int my0 = oy0 * P.s2 - P.P2, mx0 = ox0 * P.s2 - P.P2;
+        deposit();
+        __builtin_amdgcn_s_waitcnt(0);          // first tile: this wave's filter rows have landed
+        __syncthreads();
+        if (L + (int)gridDim.x < P.nblocks) request(L + gridDim.x);
+        typename M1::Acc acc[NRT1][NPT1];
+#pragma unroll
+        for (int p = 0; p < NPT1; ++p)
+#pragma unroll
+            for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
+        if (active)
+            conv_accum<MF1, K1, NRT1, NPT1>(acc, xbuf, off1, P.iws, P.in_gstride, wbuf, rloc, wg_rt, P.c1.nkg);
+        store_mid<MF1, NRT1, NPT1>(acc, P, P.c1, mid, my0, mx0, rt0, rt_end1, pt0, npx1, -FLT_MAX);
+        __syncthreads();
+        // pooling from the LDS tile; one float4 (4 channels of one pixel) per item
+        const int ngroups = (P.c1.cout + 3) >> 2;
+        const int npo = P.th * P.tw;
+        const size_t oplane = (size_t)P.Ho * P.Wo;
+        for (int it = tid; it < ngroups * npo; it += nthreads) {
+            const int gq = it / npo, pidx = it - gq * npo;
+            const int oy = pidx / P.tw, ox = pidx - oy * P.tw;
+            const int gy = oy0 + oy, gx = ox0 + ox;
+            if (gy >= P.Ho || gx >= P.Wo) continue;
+            const float *sp = mid + gq * P.mid_gstride + ((oy * P.s2) * P.mw + ox * P.s2) * 4;
+            f32x4 m = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
+            for (int u = 0; u < P.pool_k; ++u)
+                for (int v = 0; v < P.pool_k; ++v) {
+                    const f32x4 t = *(const f32x4 *)(sp + (u * P.mw + v) * 4);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
+                }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int co = gq * 4 + j;
+                if (co < P.c1.cout) P.y[((size_t)n * P.Cy + P.coff1 + co) * oplane + (size_t)gy * P.Wo + gx] = m[j];
+            }
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------
 // launch table
 // ----------------------------------------------------------------------------
 typedef void (*BlockKernel)(const BlockParams);
+
+template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC, int PX1>
+static BlockKernel select_kernel()
+{
+    if constexpr (KIND == KIND_POOLS)
+        return pool_stream_kernel<MF1, K1, NRT1, NPT1>;
+    else
+        return block_kernel<KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1>;
+}
 
 static BlockKernel kernel_of(int variant)
 {
     switch (variant) {
 #define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1)                       \
     case ID:                                                                                       \
-        return block_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2), (NRT2 == 0 ? 1 : NRT2), \
-                            (NPT2 == 0 ? 1 : NPT2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0), PX1>;
+        return select_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2), (NRT2 == 0 ? 1 : NRT2), \
+                             (NPT2 == 0 ? 1 : NPT2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0), PX1>();
         XL_VARIANT_LIST(X)
 #undef X
     }
@@ -1056,7 +1225,8 @@ hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t l
     BlockKernel k = kernel_of(variant);
     if (!k) return hipErrorInvalidValue;
     if (p.nblocks <= 0) return hipSuccess;
-    const int grid = (p.nblocks + 7) / 8 * 8;
+    int grid = (p.nblocks + 7) / 8 * 8;
+    if (p.stream_wgs > 0) grid = std::min(grid, (p.stream_wgs + 7) / 8 * 8);     // resident workgroups walking the tiles
     hipLaunchKernelGGL(k, dim3(grid), dim3(threads), lds_bytes, s, p);
     return hipGetLastError();
 }

@@ -167,7 +167,7 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     } else if (b.kind == KIND_POOL) {
         t2 = (double)ceil_div(b.c1.cout, 4) * c.th * c.tw * b.pool_k * b.pool_k * 8.0 / c.threads * 4;
     }
-    const double ovh = 6000.0 + 350.0 * barriers;
+    const double ovh = (v.kind == KIND_POOLS ? 2500.0 : 6000.0) + 350.0 * barriers;   // a resident workgroup pays start-up once
     const double wg_clk = t1 + t2 + ovh;
     const long long nwg = (long long)c.tiles_x * c.tiles_y * c.csplit * b.N;
     const double rounds = std::ceil((double)nwg / pl.num_cus);
@@ -209,7 +209,8 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     }
     bool any_lds_reject = false;
     for (const Variant &v : variants()) {
-        if (v.kind != b.kind || v.k1 != b.c1.k) continue;
+        const bool stream = v.kind == KIND_POOLS;          // conv -> pool as a stream of tiles: same block kind
+        if ((v.kind != b.kind && !(stream && b.kind == KIND_POOL)) || v.k1 != b.c1.k) continue;
 #ifdef XL_DEV_HOOKS     // development builds only: restrict the search to one kernel variant
         if (const char *only = std::getenv("XL_ONLY_VARIANT"))
             if (b.kind != KIND_SINGLE && std::atoi(only) != v.id) continue;
@@ -274,6 +275,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     if (px > 0)     // planar chunk: kc x px x 16 quads per K step, at most PLANAR_SLOTS wave loads per wave
                         c.chunk_kg = std::min(c.chunk_kg, PLANAR_SLOTS * nw * 64 / (kc_of(mf1) * px * 16));
                     if (c.chunk_kg < 1) continue;
+                    if (stream && c.chunk_kg < nkg1) continue;        // the stream kernel keeps the whole reduction in one chunk
                     c.w_off1 = c.chunk_kg * x_per_kg * 4 + 16;        // + slack for a left-edge unit running past the last row
                     if (px > 0) c.w_off1 = c.chunk_kg * kc_of(mf1) * px * 64;
                     int buf1 = c.w_off1 + c.chunk_kg * w_per_kg * 4;
@@ -674,6 +676,7 @@ struct Builder {
         p.lds_buf_off = ch.mid_floats;
         p.buf_stride = ch.buf_floats;
         p.w_off1 = ch.w_off1;
+        p.stream_wgs = ch.v.kind == KIND_POOLS ? std::min(p.nblocks, pl.num_cus * std::max(ch.occ, 1)) : 0;
     }
 
     void fill_info(xl_group_info &gi, const BlockSpec &b, const Choice &ch) const

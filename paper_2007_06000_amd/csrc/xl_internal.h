@@ -31,7 +31,7 @@ struct ConvW {
     int nrt;                // row tiles = ceil(cout / MF)
 };
 
-enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3 };
+enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3, KIND_POOLS = 4 };
 
 // Kernel argument of every convolution-stage kernel.
 //   KIND_SINGLE: stage 1 writes its result to global memory (one layer, the
@@ -41,6 +41,8 @@ enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3 };
 //                tile (straight / split), optionally adding a shortcut tensor
 //                in the epilogue (merge).
 //   KIND_POOL:   stage 1 as above; stage 2 is a max pooling from the LDS tile.
+//   KIND_POOLS:  KIND_POOL for a first layer whose reduction fits one chunk, as a stream: resident
+//                workgroups walk the tiles and request the next tile's input ahead (pool_stream_kernel).
 //   KIND_DW:     stage 1 is a depthwise convolution (one filter per channel, vector ALU) into the
 //                LDS tile; stage 2 as KIND_FUSED2.  c1.wp / c1.aff then hold the plain depthwise
 //                tables ([channel group][tap] and [channel group][scale, shift] float4).
@@ -81,6 +83,7 @@ struct BlockParams {
     int lds_buf_off;        // float offset of the two staging buffers in LDS (after the tile)
     int buf_stride;         // floats per staging buffer
     int w_off1;             // stage 1: float offset of the filter chunk inside a buffer (after the input chunk)
+    int stream_wgs;         // KIND_POOLS: workgroups to launch (each walks tiles L, L + stream_wgs, ...)
 };
 
 // A compiled kernel variant.
@@ -181,6 +184,11 @@ struct Variant {
     X(57, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 1, 0, 0, 0)                \
     X(58, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0, 0)                \
     X(59, KIND_DW, 32, 3, 1, 1, 16, 1, 2, 3, 0, 0, 0)                \
+    /* conv -> maxpool as a stream of tiles (first layer of one chunk) */ \
+    X(94, KIND_POOLS, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(95, KIND_POOLS, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(96, KIND_POOLS, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(97, KIND_POOLS, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)           \
     /* conv -> maxpool */                                 \
     X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
     X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)             \
