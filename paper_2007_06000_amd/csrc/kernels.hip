@@ -337,7 +337,8 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             xmask[i] = m;
             xgrp[i] = gr * 4;
             xdst[i] = (gr * plane + r * P.iws + cc) * 4;
-            xoff[i] = (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4);
+            // lanes without a unit aim past the end of the buffer: the load returns zeros and moves no data
+            xoff[i] = u < x_units ? (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4) : 0xfffffff0u;
         }
     }
     __amdgpu_buffer_rsrc_t xrsrc;
@@ -1102,7 +1103,8 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
         xmask = m;
         xgrp = gr * 4;
         xdst = (gr * plane + r * P.iws + cc) * 4;
-        xoff = (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4);
+        // lanes without a unit aim past the end of the buffer: the load returns zeros and moves no data
+        xoff = u < x_units ? (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4) : 0xfffffff0u;
         xr = make_rsrc(P.x + (size_t)n * P.Cin * HW, (unsigned long long)(P.N - n) * P.Cin * HW * 4ull);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
