@@ -199,6 +199,26 @@ def test_merge_block_with_two_producers(wl):
     assert s.plan.num_launches(True) == 1 and s.plan.num_launches(False) == 4
 
 
+@pytest.mark.parametrize("wl", [
+    W.conv_pool_generic(3, 3, 37, 41, 24, 3, 0, 2, 3, 2, 0),            # stem-like: 3 channels, stride 2, ragged tiles
+    W.conv_pool_generic(70, 3, 9, 9, 8, 3, 1, 1, 2, 2, 0),              # many tiny images: more tiles than resident workgroups
+    W.conv_pool_generic(2, 8, 19, 23, 40, 3, 1, 1, 3, 2, 1, bn=True),   # padding on both layers
+    W.conv_pool_generic(1, 16, 30, 30, 64, 1, 0, 1, 3, 2, 1),           # 1x1 first layer, whole reduction in one chunk
+    W.conv_pool_generic(2, 5, 11, 7, 12, 3, 1, 1, 3, 1, 1, relu=False), # stride-1 pooling over negative values
+], ids=lambda w: w.name)
+def test_conv_then_max_pooling_shapes(wl):
+    """conv -> maxpool blocks, among them first layers whose reduction fits one chunk (served by the
+    kernel that walks a stream of tiles per workgroup)."""
+    for tune in (False, True):
+        from paper_2007_06000_amd.session import Session
+        x, params = W.make_tensors(wl)
+        ref = xlo.forward(wl, x, params)
+        s = Session(wl, x, params, tune=tune)
+        for fused in (True, False):
+            print(f"[case] {wl.name} tune={tune} fused={fused}", flush=True)
+            check(s.output(fused), ref, f"{wl.name} tune={tune} fused={fused}")
+
+
 def test_degenerate_shapes():
     """1x1 images, single channels, tiles larger than the image, odd sizes under stride 2."""
     for wl in (W.single_conv(1, 1, 1, 1, 1, 1),
