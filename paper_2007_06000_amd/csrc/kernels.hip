@@ -112,7 +112,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsig
 // `off` then holds the pixel index plus this lane's channel-group offset, and the four channels of a
 // K step quarter are four 4-byte reads PX * 64 floats apart (paired by the compiler into two reads
 // with 64-dword strides) instead of one 16-byte read.
-template <int MF, int KS, int NRT, int NPT, int PX = 0>
+// JN < 4: only the first JN of the 4 channel slots of every lane hold data (a first layer with at most
+// 2 * JN input channels, packed two per slot across the lane halves): the other slots' matrix
+// operations would add zeros and are left out.
+template <int MF, int KS, int NRT, int NPT, int PX = 0, int JN = 4>
 __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT],
                                            const float *bsrc, const int (&off)[NPT], int src_w, int gstride,
                                            const float *wsrc, const int (&rloc)[NRT], int wg_rt, int nkg)
@@ -146,7 +149,7 @@ __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT]
         if (t + 1 < T || kg + 1 < nkg) fetch(a[cur ^ 1], b[cur ^ 1], kg + (t + 1) / T, (t + 1) % T);
         __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of this step's matrix ops
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < JN; ++j)
 #pragma unroll
             for (int r = 0; r < NRT; ++r)
 #pragma unroll
@@ -1025,7 +1028,9 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
 //   separates it from this tile's K loop reads, the second from this tile's pooling reads)
 // LDS: [intermediate tile][input chunk][filter].  Geometry and parameters as in block_kernel.
 // ----------------------------------------------------------------------------
-template <int MF1, int K1, int NRT1, int NPT1>
+// JN < 4 (MF1 = 32, at most 2 * JN input channels): channel c sits in lane half c % 2, slot c / 2, in
+// the staged input as in the filter, and conv_accum skips the empty slots.
+template <int MF1, int K1, int NRT1, int NPT1, int JN>
 __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const BlockParams P)
 {
     typedef MM<MF1> M1;
@@ -1104,18 +1109,24 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
         xgrp = gr * 4;
         xdst = (gr * plane + r * P.iws + cc) * 4;
         // lanes without a unit aim past the end of the buffer: the load returns zeros and moves no data
-        xoff = u < x_units ? (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4) : 0xfffffff0u;
+        const int first_ch = JN < 4 ? gr : gr * 4;                   // channel of slot 0 of this unit
+        xoff = u < x_units ? (unsigned)(((first_ch * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4) : 0xfffffff0u;
         xr = make_rsrc(P.x + (size_t)n * P.Cin * HW, (unsigned long long)(P.N - n) * P.Cin * HW * 4ull);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            xst[j] = __builtin_bit_cast(f32x4, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(xr, xoff, j * HW * 4, 0));
+        for (int j = 0; j < 4; ++j) {
+            if (j < JN)
+                xst[j] = __builtin_bit_cast(f32x4, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(xr, xoff, (JN < 4 ? 2 * j : j) * HW * 4, 0));
+            else
+                xst[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
     };
     auto deposit = [&]() {              // the requested units -> LDS, masked (pixels outside the image, channels past Cin)
         if (xmask & 0x10u) {
             if (xs > 0 && (xmask & 0x100u)) {
                 for (int e = 1; e <= xs; ++e) *(f32x4 *)(xbuf + xdst - 4 * e) = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-            const int live = P.Cin - xgrp;
+            // slot j holds channel xgrp + j, or with two channels per slot pair (xgrp / 4) + 2 * j
+            const int live = JN < 4 ? (P.Cin - (xgrp >> 2) + 1) / 2 : P.Cin - xgrp;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
                 const bool in = (xmask >> kk) & 1u;
@@ -1145,7 +1156,7 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
 #pragma unroll
             for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
         if (active)
-            conv_accum<MF1, K1, NRT1, NPT1>(acc, xbuf, off1, P.iws, P.in_gstride, wbuf, rloc, wg_rt, P.c1.nkg);
+            conv_accum<MF1, K1, NRT1, NPT1, 0, JN>(acc, xbuf, off1, P.iws, P.in_gstride, wbuf, rloc, wg_rt, P.c1.nkg);
         store_mid<MF1, NRT1, NPT1>(acc, P, P.c1, mid, my0, mx0, rt0, rt_end1, pt0, npx1, -FLT_MAX);
         __syncthreads();
         // pooling from the LDS tile; one float4 (4 channels of one pixel) per item
@@ -1183,7 +1194,7 @@ template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int 
 static BlockKernel select_kernel()
 {
     if constexpr (KIND == KIND_POOLS)
-        return pool_stream_kernel<MF1, K1, NRT1, NPT1>;
+        return pool_stream_kernel<MF1, K1, NRT1, NPT1, (PX1 < 0 ? -PX1 : 4)>;
     else
         return block_kernel<KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1>;
 }
@@ -1239,8 +1250,9 @@ hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t l
 //   MF = 16: lane l holds cout = rt*16 + l%16, cin = kg*16 + (l/16)*4 + j
 // zero where cout or cin run past the real extent.
 // ----------------------------------------------------------------------------
+// pairs != 0 (mf = 32, one K step): channel c goes to lane half c % 2, slot c / 2.
 __global__ void pack_filter_kernel(const float *__restrict__ w, f32x4 *__restrict__ wp, int cout, int cin, int k,
-                                   int mf, int nkg, int nrt)
+                                   int mf, int nkg, int nrt, int pairs)
 {
     const int taps = k * k;
     const long long total = (long long)nkg * taps * nrt * 64;
@@ -1258,19 +1270,19 @@ __global__ void pack_filter_kernel(const float *__restrict__ w, f32x4 *__restric
     f32x4 v;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int ci = kg * kc + sub * 4 + j;
+        const int ci = pairs ? 2 * j + sub : kg * kc + sub * 4 + j;
         v[j] = (o < cout && ci < cin) ? w[((size_t)o * cin + ci) * taps + t] : 0.f;
     }
     wp[idx] = v;
 }
 
 hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf, int nkg, int nrt,
-                              hipStream_t s)
+                              hipStream_t s, int pairs)
 {
     const long long total = (long long)nkg * k * k * nrt * 64;
     const int threads = 256;
     const int grid = (int)((total + threads - 1) / threads);
-    hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, wp, cout, cin, k, mf, nkg, nrt);
+    hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, wp, cout, cin, k, mf, nkg, nrt, pairs);
     return hipGetLastError();
 }
 

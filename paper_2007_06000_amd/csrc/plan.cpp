@@ -130,6 +130,7 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
         if (rt0 < rt_end && pt0 * mf1 < npx1) simd[w % 4] += wave1;
     }
     double t1 = *std::max_element(simd, simd + 4) * b.n1;
+    if (v.px1 < 0) t1 *= -v.px1 / 4.0;      // only -px1 of the 4 channel slots carry matrix operations
     if (v.px1 > 0) t1 *= 0.9;       // planar input chunks: no register staging, no vector-ALU work in the K loop
     int barriers = ceil_div(nkg1, c.chunk_kg) * b.n1;
     if (b.kind == KIND_DW) {
@@ -223,7 +224,10 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
         if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0)) continue;
         // variants whose stage 1 reads planar input chunks: a 1x1 filter, stride 1, no padding, whole
         // K steps of channels; the tile's ih rows of iws floats must fit px * 64 floats per channel
-        const int px = v.px1;
+        // px1 < 0: the first layer's channels are packed two per channel slot (-px1 slots used): 32-wide
+        // tile, at most -2 * px1 input channels
+        if (v.px1 < 0 && !(v.mf1 == 32 && b.c1.cin <= -2 * v.px1)) continue;
+        const int px = v.px1 > 0 ? v.px1 : 0;
         if (px > 0 && !(b.c1.k == 1 && b.c1.stride == 1 && b.c1.pad == 0 && b.c1.cin % kc_of(v.mf1) == 0)) continue;
         const int mf1 = v.mf1;
         const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
@@ -541,20 +545,21 @@ struct Builder {
         stores = tensor_elems(L.out);
     }
 
-    int packed_index(int layer, int mf)
+    int packed_index(int layer, int mf, bool pairs = false)
     {
         for (size_t i = 0; i < pl.packed.size(); ++i)
-            if (pl.packed[i].layer == layer && pl.packed[i].mf == mf) return (int)i;
+            if (pl.packed[i].layer == layer && pl.packed[i].mf == mf && pl.packed[i].pairs == pairs) return (int)i;
         const xl_layer &L = pl.layers[layer];
         PackedFilter p;
         p.layer = layer;
         p.mf = mf;
+        p.pairs = pairs;
         if (mf == 0) {      // depthwise: [channel group][tap] float4 and [channel group][scale, shift] float4
             p.nkg = p.nrt = 0;
             p.bytes = (size_t)ceil_div(L.cout, 4) * L.k * L.k * 16;
             p.aff_bytes = (size_t)ceil_div(L.cout, 4) * 2 * 16;
         } else {
-            p.nkg = ceil_div(L.cin, kc_of(mf));
+            p.nkg = pairs ? 1 : ceil_div(L.cin, kc_of(mf));
             p.nrt = ceil_div(L.cout, mf);
             p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16;
             p.aff_bytes = (size_t)p.nrt * (mf == 32 ? 4 : 1) * 2 * 64 * 16;
@@ -601,7 +606,7 @@ struct Builder {
         st.sc_id = sc_id;
         st.conv_layer[0] = b.c1.layer;
         st.conv_layer[1] = st.conv_layer[2] = -1;
-        st.packed[0] = packed_index(b.c1.layer, b.kind == KIND_DW ? 0 : ch.v.mf1);
+        st.packed[0] = packed_index(b.c1.layer, b.kind == KIND_DW ? 0 : ch.v.mf1, ch.v.px1 < 0);
         st.packed[1] = st.packed[2] = -1;
         BlockParams &p = st.bp;
         memset(&p, 0, sizeof p);

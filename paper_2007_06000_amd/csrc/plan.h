@@ -15,6 +15,7 @@ enum StepType { STEP_BLOCK = 0, STEP_MAXPOOL = 1, STEP_ADD = 2, STEP_GAP = 3, ST
 struct PackedFilter {
     int layer;
     int mf;             // 32 or 16; 0 = depthwise tables ([channel group][tap], [channel group][scale, shift])
+    bool pairs = false; // channels packed two per channel slot (c -> lane half c % 2, slot c / 2), one K step
     int nkg, nrt;
     size_t offset;      // bytes into the workspace
     size_t bytes;

@@ -94,7 +94,8 @@ struct Variant {
     int mf2, nrt2, npt2;        // stage 2: matrix-core tile, tiles per wave (0 when unused)
     int k2a, k2b;               // stage 2 filter sizes, heavier sibling first (0 = absent)
     int sc;                     // 1: adds a shortcut tensor in the epilogue (merge mode)
-    int px1;                    // > 0: stage 1 (1x1 filter) reads a planar input chunk, px1 * 64 floats per channel
+    int px1;                    // > 0: stage 1 (1x1 filter) reads a planar input chunk, px1 * 64 floats per channel;
+                                // < 0: stage 1 uses only -px1 of the 4 channel slots (<= -2 * px1 input channels)
 };
 
 // id, kind, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1
@@ -189,6 +190,9 @@ struct Variant {
     X(95, KIND_POOLS, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)           \
     X(96, KIND_POOLS, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)           \
     X(97, KIND_POOLS, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    /* ... with at most 4 input channels packed two per channel slot (PX1 = -2: 2 of 4 slots used) */ \
+    X(98, KIND_POOLS, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, -2)          \
+    X(99, KIND_POOLS, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, -2)          \
     /* conv -> maxpool */                                 \
     X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
     X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)             \
@@ -213,7 +217,7 @@ hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t l
 hipError_t configure_kernels(int max_lds_bytes);      // raises the dynamic-LDS cap of every variant
 
 hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf,
-                              int nkg, int nrt, hipStream_t s);
+                              int nkg, int nrt, hipStream_t s, int pairs = 0);
 hipError_t launch_pack_affine(const float *scale, const float *shift, f32x4 *out, int cout, int mf, int nrt,
                               hipStream_t s);
 hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, int Ho, int Wo,
