@@ -111,6 +111,8 @@ struct Variant {
     X(63, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0, 2)          \
     X(64, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0, 4)          \
     X(65, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0, 4)          \
+    X(100, KIND_SINGLE, 16, 1, 2, 11, 0, 0, 0, 0, 0, 0, 3)        \
+    X(101, KIND_SINGLE, 16, 1, 4, 6, 0, 0, 0, 0, 0, 0, 3)          \
     X(66, KIND_FUSED2, 16, 1, 1, 1, 32, 2, 1, 3, 1, 0, 2)         \
     X(67, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 4)         \
     X(68, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 4)         \
