@@ -41,7 +41,7 @@ def time_steps(fn, steps, warmup, torch):
 
 
 def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True):
-    wl = W.config(cfg)
+    wl = cfg if isinstance(cfg, W.Workload) else W.config(cfg)
     x, params = W.make_tensors(wl)
     s = Session(wl, x, params, tune=TUNE)
     in_bytes = x.nbytes
@@ -163,6 +163,14 @@ def main():
                 blocks.append({k: res[k] for k in res})
                 continue
             r, *_ = bench_workload(c, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm)
+            blocks.append(r)
+        # the paper's four fused structures (its Table 1; b.1 is the family of config 3), at batch 32
+        table1 = {"table1_a1": W.straight_generic(32, 192, 28, 28, 16, 1, 0, 1, 32, 5, 2, 1),
+                  "table1_a2": W.depthwise_pointwise(32, 16, 80, 80, 16),
+                  "table1_c1": W.merge_two_producers(32)}
+        for tag, wl in table1.items():
+            r, *_ = bench_workload(wl, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm)
+            r["workload"] = tag + ":" + r["workload"]
             blocks.append(r)
         out["blocks"] = blocks
     if not args.no_cpu_baseline:
