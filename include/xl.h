@@ -113,7 +113,17 @@ typedef struct xl_options {
     int paper_tuner_only;   /* 1: restrict candidates to the paper's square common-factor
                                (tile, grid) pairs (section 3.2)                               */
     int force_threads;      /* >0: fix the workgroup size (256 or 512) of every block         */
+    int precision;          /* XL_PRECISION_FP32 (0, default): fp32 matrix operations.
+                               XL_PRECISION_BF16X3: every operand of a convolution is split into
+                               two bf16 numbers, hi = bf16(x) and lo = bf16(x - hi), and a product
+                               is hi*hi + hi*lo + lo*hi on the bf16 matrix cores, accumulated in
+                               fp32 (error below 2^-16 of |a||b| per product; operands must be
+                               finite and below 2^127 in magnitude).  Tensors in memory stay fp32.
+                               Blocks no split-bf16 kernel covers (depthwise first layers, the
+                               two-producer merge form) run the fp32 kernels. */
 } xl_options;
+#define XL_PRECISION_FP32   0
+#define XL_PRECISION_BF16X3 1
 
 /* What the planner decided for one block (all sizes in elements unless named bytes). */
 typedef struct xl_group_info {
@@ -136,6 +146,7 @@ typedef struct xl_group_info {
     long long flops;            /* 2*MAC, no halo recompute                                 */
     long long flops_executed;   /* 2*MAC the fused kernel issues incl. halo and tile padding */
     double redundancy;          /* intermediate elements computed / unique elements         */
+    int precision;              /* arithmetic of the block's kernel: XL_PRECISION_*         */
 } xl_group_info;
 
 typedef struct xl_plan xl_plan;

@@ -51,7 +51,7 @@ class xl_options(ctypes.Structure):
     _fields_ = [("lds_budget_bytes", ctypes.c_int), ("num_cus", ctypes.c_int),
                 ("force_tile_h", ctypes.c_int), ("force_tile_w", ctypes.c_int),
                 ("force_cout_split", ctypes.c_int), ("paper_tuner_only", ctypes.c_int),
-                ("force_threads", ctypes.c_int)]
+                ("force_threads", ctypes.c_int), ("precision", ctypes.c_int)]
 
 
 class xl_group_info(ctypes.Structure):
@@ -65,7 +65,7 @@ class xl_group_info(ctypes.Structure):
                 ("bytes_fused", ctypes.c_longlong), ("bytes_unfused", ctypes.c_longlong),
                 ("stores_fused", ctypes.c_longlong), ("stores_unfused", ctypes.c_longlong),
                 ("flops", ctypes.c_longlong), ("flops_executed", ctypes.c_longlong),
-                ("redundancy", ctypes.c_double)]
+                ("redundancy", ctypes.c_double), ("precision", ctypes.c_int)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_}

@@ -15,7 +15,9 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libxl.so")
-SOURCES = ["kernels.hip", "plan.cpp", "api.cpp"]
+# (source, object name, extra defines): kernels.hip is compiled twice, the split-bf16 variants on their own
+SOURCES = [("kernels.hip", "kernels", []), ("kernels.hip", "kernels_b3", ["-DXL_TU_B3"]),
+           ("plan.cpp", "plan", []), ("api.cpp", "api", [])]
 HEADERS = [os.path.join(CSRC, "xl_internal.h"), os.path.join(CSRC, "plan.h"), os.path.join(ROOT, "include", "xl.h")]
 
 # packed-fp32 instructions are switched off for all device code
@@ -37,13 +39,14 @@ def _filter(stderr: str) -> str:
     return "\n".join(keep)
 
 
-def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+def _compile(item, force: bool) -> str:
+    src, name, defines = item
+    obj = os.path.join(OBJ, name + ".o")
     path = os.path.join(CSRC, src)
     newest = max(os.path.getmtime(p) for p in [path] + HEADERS)
     if not force and os.path.exists(obj) and os.path.getmtime(obj) >= newest:
         return obj
-    cmd = [_hipcc()] + HIPCC_FLAGS + ["-x", "hip", "-c", path, "-o", obj]
+    cmd = [_hipcc()] + HIPCC_FLAGS + defines + ["-x", "hip", "-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msg = _filter(r.stderr)
     if msg.strip():

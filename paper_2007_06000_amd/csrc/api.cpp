@@ -64,6 +64,10 @@ xl_status xl_plan_create(const xl_layer *layers, int nlayers, const xl_shape *sh
     pl->layers.assign(layers, layers + nlayers);
     pl->shapes.assign(shapes, shapes + ntensors);
     if (opts) pl->opts = *opts;
+    if (pl->opts.precision != XL_PRECISION_FP32 && pl->opts.precision != XL_PRECISION_BF16X3) {
+        delete pl;
+        return XL_E_UNSUPPORTED;
+    }
     pl->device = device;
     pl->lds_per_cu = GFX950_LDS_BYTES;
     pl->num_cus = GFX950_CUS;
@@ -177,7 +181,7 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, vo
         }
         e = xl::launch_pack_filter(static_cast<const float *>(weights[L.w_slot]),
                                    reinterpret_cast<xl::f32x4 *>(ws + p.offset), L.cout, L.cin, L.k, p.mf,
-                                   p.nkg, p.nrt, s, p.pairs ? 1 : 0);
+                                   p.nkg, p.nrt, s, p.pairs ? 1 : 0, p.pr);
         if (e == hipSuccess)
             e = xl::launch_pack_affine(plan->scale_ptr[p.layer], plan->shift_ptr[p.layer],
                                        reinterpret_cast<xl::f32x4 *>(ws + p.aff_offset), L.cout, p.mf, p.nrt, s);

@@ -46,11 +46,38 @@ __device__ unsigned long long g_wtrace[8 * 8 * 16 * 4];     // [block][wave][chu
 // ----------------------------------------------------------------------------
 // matrix-core wrappers
 // ----------------------------------------------------------------------------
-template <int MF>
+// PR = 0: fp32 operands.  PR = 1: every operand is held as two bf16 numbers, hi = bf16(x) and
+// lo = bf16(x - hi) (round to nearest), and a product is the sum of three bf16 matrix operations
+// hi*hi + hi*lo + lo*hi accumulated in fp32; what is left out is below 2^-16 of |a||b|.  One K step
+// then covers 16 (MF = 32) or 32 (MF = 16) channels, 8 per lane.  The accumulator layout is the
+// same in both modes.
+template <int MF, int PR = 0>
 struct MM;
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
 template <>
-struct MM<32> {
+struct MM<32, 1> {
+    typedef f32x16 Acc;
+    static constexpr int KC = 16, GPS = 4, NQ = 4;
+    static __device__ __forceinline__ Acc mma(f32x4 a, f32x4 b, Acc c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+
+template <>
+struct MM<16, 1> {
+    typedef f32x4 Acc;
+    static constexpr int KC = 32, GPS = 8, NQ = 1;
+    static __device__ __forceinline__ Acc mma(f32x4 a, f32x4 b, Acc c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+
+template <>
+struct MM<32, 0> {
     typedef f32x16 Acc;
     static constexpr int KC = 8, GPS = 2, NQ = 4;
     static __device__ __forceinline__ Acc mma(float a, float b, Acc c)
@@ -62,7 +89,7 @@ struct MM<32> {
 };
 
 template <>
-struct MM<16> {
+struct MM<16, 0> {
     typedef f32x4 Acc;
     static constexpr int KC = 16, GPS = 4, NQ = 1;
     static __device__ __forceinline__ Acc mma(float a, float b, Acc c)
@@ -176,6 +203,81 @@ __device__ __forceinline__ void conv_accum(typename MM<MF>::Acc (&acc)[NRT][NPT]
     }
 }
 
+// The same K loop for split-bf16 operands (PR = 1).  Every operand row exists twice in LDS, a hi and
+// a lo one: the filter chunk is [K step][tap][row tile][hi, lo][lane] 16 bytes, the pixels are 16-byte
+// planes [8-channel group][hi, lo][row][col][8 bf16], `gstride` floats apart (the plane of the
+// lane's 8-channel group is part of `off`).  Three matrix operations per tile pair and K step.
+template <int MF, int KS, int NRT, int NPT>
+__device__ __forceinline__ void conv_accum_b3(typename MM<MF, 1>::Acc (&acc)[NRT][NPT],
+                                              const float *bsrc, const int (&off)[NPT], int src_w, int gstride,
+                                              const float *wsrc, const int (&rloc)[NRT], int wg_rt, int nkg)
+{
+    typedef MM<MF, 1> M;
+    constexpr int T = KS * KS;
+    const int lane = threadIdx.x & 63;
+    f32x4 ah[2][NRT], al[2][NRT], bh[2][NPT], bl[2][NPT];
+    auto fetch = [&](int set, int kg, int t) {
+        const int u = t / KS, v = t % KS;
+        const float *w = wsrc + ((kg * T + t) * wg_rt * 128 + lane) * 4;
+#pragma unroll
+        for (int r = 0; r < NRT; ++r) {
+            ah[set][r] = *(const f32x4 *)(w + rloc[r] * 512);
+            al[set][r] = *(const f32x4 *)(w + rloc[r] * 512 + 256);
+        }
+        const float *s = bsrc + kg * (M::GPS * gstride) + (u * src_w + v) * 4;
+#pragma unroll
+        for (int p = 0; p < NPT; ++p) {
+            bh[set][p] = *(const f32x4 *)(s + off[p]);
+            bl[set][p] = *(const f32x4 *)(s + off[p] + gstride);
+        }
+    };
+    static_assert(T % 2 == 1, "filter taps are odd");
+    auto step = [&](int cur, int kg, int t) {
+        if (t + 1 < T || kg + 1 < nkg) fetch(cur ^ 1, kg + (t + 1) / T, (t + 1) % T);
+        __builtin_amdgcn_sched_barrier(0);
+        // small terms first; the three products of one tile pair are spread over the other pairs
+#pragma unroll
+        for (int r = 0; r < NRT; ++r)
+#pragma unroll
+            for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(al[cur][r], bh[cur][p], acc[r][p]);
+#pragma unroll
+        for (int r = 0; r < NRT; ++r)
+#pragma unroll
+            for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(ah[cur][r], bl[cur][p], acc[r][p]);
+#pragma unroll
+        for (int r = 0; r < NRT; ++r)
+#pragma unroll
+            for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(ah[cur][r], bh[cur][p], acc[r][p]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    fetch(0, 0, 0);
+    if constexpr (T == 1) {
+        for (int kg = 0; kg < nkg; kg += 2) {
+            step(0, kg, 0);
+            if (kg + 1 < nkg) step(1, kg + 1, 0);
+        }
+    } else {
+        for (int kg = 0; kg < nkg; ++kg) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) step(t & 1, kg, t);
+#pragma unroll
+            for (int r = 0; r < NRT; ++r) { ah[0][r] = ah[1][r]; al[0][r] = al[1][r]; }
+#pragma unroll
+            for (int p = 0; p < NPT; ++p) { bh[0][p] = bh[1][p]; bl[0][p] = bl[1][p]; }
+        }
+    }
+}
+
+// hi / lo bf16 halves of two floats, packed (first float in the low half of each word)
+__device__ __forceinline__ void split_bf16(float a, float b, unsigned &hi, unsigned &lo)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    hi = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{a, b}, bf16x2));
+    const float ha = __builtin_bit_cast(float, hi << 16), hb = __builtin_bit_cast(float, hi & 0xffff0000u);
+    lo = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{a - ha, b - hb}, bf16x2));
+}
+
 // ----------------------------------------------------------------------------
 // One pass of a convolution over the tiles this workgroup holds in registers.
 // The filter (and, for STAGE_X, the halo-extended input tile) is streamed
@@ -195,13 +297,15 @@ struct PassGeom {
     bool active;        // this wave owns at least one real tile
 };
 
-template <int MF, int KS, int NRT, int NPT, bool STAGE_X, int PX = 0>
+template <int MF, int KS, int NRT, int NPT, bool STAGE_X, int PX = 0, int PR = 0>
 __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P, const ConvW &c,
                                           const PassGeom &g, const float *bsrc, const int (&off)[NPT], float *buf,
                                           const float *__restrict__ ximg, unsigned long long x_bytes, int iy0, int ix0)
 {
     // ximg: first element of this image of the block input, x_bytes: bytes from there to the end of the tensor
-    typedef MM<MF> M;
+    typedef MM<MF, PR> M;
+    static_assert(PR == 0 || PX == 0, "split-bf16 operands are staged through registers");
+    constexpr int RW = PR ? 2 : 1;      // 1 KB rows per (K step, tap, row tile) of the filter: hi and lo for PR = 1
     constexpr int T = KS * KS;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     int rloc[NRT];
@@ -218,23 +322,24 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     // compiler then keeps counting outstanding LDS reads exactly instead of waiting for all of them.)
     const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves_wg = nthreads >> 6, lane_id = tid & 63;
     const int nkt = c.nkg * T;
-    const __amdgpu_buffer_rsrc_t wrsrc = make_rsrc(c.wp, (unsigned long long)nkt * c.nrt * 1024ull);
+    const int f_nrt = c.nrt * RW, f_wg_rt = g.wg_rt * RW, f_base = g.rt_base * RW;     // in 1 KB rows
+    const __amdgpu_buffer_rsrc_t wrsrc = make_rsrc(c.wp, (unsigned long long)nkt * f_nrt * 1024ull);
     const int w_lane = (tid & 63) * 16;
-    const int w_dkt = nwaves_wg / g.wg_rt, w_drl = nwaves_wg - w_dkt * g.wg_rt;       // row step = nwaves rows
-    const int w_kt0 = wave_id / g.wg_rt, w_rl0 = wave_id - w_kt0 * g.wg_rt;
+    const int w_dkt = nwaves_wg / f_wg_rt, w_drl = nwaves_wg - w_dkt * f_wg_rt;       // row step = nwaves rows
+    const int w_kt0 = wave_id / f_wg_rt, w_rl0 = wave_id - w_kt0 * f_wg_rt;
     auto load_w = [&](float *dst, int kg0) {
         const int kts = min(g.chunk_kg * T, nkt - kg0 * T);                     // (K step, tap) rows in this chunk
-        const int base = (kg0 * T * c.nrt + g.rt_base) * 1024;                  // byte offset of the chunk's first row
+        const int base = (kg0 * T * f_nrt + f_base) * 1024;                     // byte offset of the chunk's first row
         int kt = w_kt0, rl = w_rl0;
         float *d = dst + wave_id * 256;
         while (kt < kts) {
-            if (g.rt_base + rl < c.nrt)
+            if (f_base + rl < f_nrt)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (__attribute__((address_space(3))) void *)d, 16, w_lane,
-                                                         base + (kt * c.nrt + rl) * 1024, 0, 0);
+                                                         base + (kt * f_nrt + rl) * 1024, 0, 0);
             d += nwaves_wg * 256;
             kt += w_dkt;
             rl += w_drl;
-            if (rl >= g.wg_rt) { rl -= g.wg_rt; ++kt; }
+            if (rl >= f_wg_rt) { rl -= f_wg_rt; ++kt; }
         }
     };
 
@@ -339,7 +444,9 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             }
             xmask[i] = m;
             xgrp[i] = gr * 4;
-            xdst[i] = (gr * plane + r * P.iws + cc) * 4;
+            // PR = 1: the hi halves of 4-channel group gr go to plane gr & ~1 (the lo halves to the next
+            // one), 8 bytes per pixel, after those of group gr - 1 when gr is odd
+            xdst[i] = PR ? ((gr & ~1) * plane + r * P.iws + cc) * 4 + (gr & 1) * 2 : (gr * plane + r * P.iws + cc) * 4;
             // lanes without a unit aim past the end of the buffer: the load returns zeros and moves no data
             xoff[i] = u < x_units ? (unsigned)(((gr * 4 * P.H + min(max(gy, 0), P.H - 1)) * P.W + gx) * 4) : 0xfffffff0u;
         }
@@ -372,7 +479,14 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             for (int i = 0; i < NU; ++i) {
                 if (i * nthreads < x_units && (xmask[i] & 0x10u)) {
                     if (xs > 0 && (xmask[i] & 0x100u)) {
-                        for (int e = 1; e <= xs; ++e) *(f32x4 *)(dst + xdst[i] - 4 * e) = f32x4{0.f, 0.f, 0.f, 0.f};
+                        for (int e = 1; e <= xs; ++e) {
+                            if constexpr (PR) {
+                                *(uint2 *)(dst + xdst[i] - 4 * e) = uint2{0u, 0u};
+                                *(uint2 *)(dst + xdst[i] - 4 * e + plane * 4) = uint2{0u, 0u};
+                            } else {
+                                *(f32x4 *)(dst + xdst[i] - 4 * e) = f32x4{0.f, 0.f, 0.f, 0.f};
+                            }
+                        }
                     }
                     const int live = whole ? 4 : nch - xgrp[i];        // channels of this unit that exist
 #pragma unroll
@@ -381,7 +495,15 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
                         f32x4 v;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) v[j] = (in && j < live) ? xst[i][j][k] : 0.f;
-                        *(f32x4 *)(dst + xdst[i] + 4 * k) = v;
+                        if constexpr (PR) {
+                            uint2 hi, lo;
+                            split_bf16(v[0], v[1], hi.x, lo.x);
+                            split_bf16(v[2], v[3], hi.y, lo.y);
+                            *(uint2 *)(dst + xdst[i] + 4 * k) = hi;
+                            *(uint2 *)(dst + xdst[i] + 4 * k + plane * 4) = lo;
+                        } else {
+                            *(f32x4 *)(dst + xdst[i] + 4 * k) = v;
+                        }
                     }
                 }
             }
@@ -427,7 +549,10 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         const int nkg = min(g.chunk_kg, c.nkg - kg0);
         if (g.active) {
             const float *bs = STAGE_X ? cur : bsrc + kg0 * (M::GPS * g.gstride);
-            conv_accum<MF, KS, NRT, NPT>(acc, bs, off, g.src_w, g.gstride, cur + g.w_off, rloc, g.wg_rt, nkg);
+            if constexpr (PR)
+                conv_accum_b3<MF, KS, NRT, NPT>(acc, bs, off, g.src_w, g.gstride, cur + g.w_off, rloc, g.wg_rt, nkg);
+            else
+                conv_accum<MF, KS, NRT, NPT>(acc, bs, off, g.src_w, g.gstride, cur + g.w_off, rloc, g.wg_rt, nkg);
         }
 #ifdef XL_PHASE_TIMING
         long long t2 = clock64();
@@ -713,7 +838,8 @@ __device__ __forceinline__ void store_gap(const typename MM<MF>::Acc (&acc)[NRT]
 // must see outside the image: 0 for a convolution, -FLT_MAX for max pooling.
 // With `add` the result is added to what the tile already holds (the first of two producer layers
 // of a merge block, written by this same lane) and `relu_sum` is applied to the sum.
-template <int MF, int NRT, int NPT>
+// PR = 1: the tile is written as split-bf16 planes (see conv_accum_b3); no accumulation into it.
+template <int MF, int NRT, int NPT, int PR = 0>
 __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
                                           const ConvW &c, float *mid, int my0, int mx0, int rt0, int rt_end, int pt0,
                                           int npx, float fill, bool add = false, bool relu_sum = false)
@@ -740,9 +866,11 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
                 f32x4 v;
-                float *dst = mid + (cb >> 2) * P.mid_gstride + pidx * 4;
+                const int gr = cb >> 2;
+                float *dst = PR ? mid + (gr & ~1) * P.mid_gstride + pidx * 4 + (gr & 1) * 2
+                                : mid + gr * P.mid_gstride + pidx * 4;
                 f32x4 old = {0.f, 0.f, 0.f, 0.f};
-                if (add && pidx < npx) old = *(const f32x4 *)dst;
+                if (!PR && add && pidx < npx) old = *(const f32x4 *)dst;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
@@ -755,7 +883,17 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
                     if (cb + i >= c.cout) z = 0.f;
                     v[i] = z;
                 }
-                if (pidx < npx) *(f32x4 *)dst = v;
+                if constexpr (PR) {
+                    uint2 hi, lo;
+                    split_bf16(v[0], v[1], hi.x, lo.x);
+                    split_bf16(v[2], v[3], hi.y, lo.y);
+                    if (pidx < npx) {
+                        *(uint2 *)dst = hi;
+                        *(uint2 *)(dst + P.mid_gstride) = lo;
+                    }
+                } else {
+                    if (pidx < npx) *(f32x4 *)dst = v;
+                }
             }
         }
     }
@@ -830,9 +968,10 @@ __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mi
 // ----------------------------------------------------------------------------
 // The block kernel
 // ----------------------------------------------------------------------------
-template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC, int PX1>
+template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC, int PX1, int PR = 0>
 __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_WAVES)) block_kernel(const BlockParams P)
 {
+    static_assert(PR == 0 || (KIND != KIND_DW && PX1 == 0), "split-bf16 operands: matrix-core first layers staged through registers");
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int L = logical_block();
     if (L >= P.nblocks) return;
@@ -845,7 +984,8 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    typedef MM<MF1> M1;
+    typedef MM<MF1, PR> M1;
+    constexpr int SUBP = PR ? 2 : 1;    // 16-byte planes per lane group of a K step (hi and lo for PR = 1)
 
     // tile origins: output -> intermediate (stage-2 window) -> input (stage-1 window)
     const int my0 = (KIND == KIND_SINGLE) ? oy0 : oy0 * P.s2 - P.P2;
@@ -888,12 +1028,12 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
             pidx = pidx < npx1 ? pidx : 0;
             const int my = pidx / P.mw, mx = pidx - my * P.mw;
             off1[p] = PX1 > 0 ? my * P.iws + max(mx - max(0, -ix0), 0) + sub * (4 * PX1 * 64)
-                              : ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * P.in_gstride;
+                              : ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * SUBP * P.in_gstride;
         }
     }
     XL_PHASE(L, 0);
-    conv_pass<MF1, K1, NRT1, NPT1, true, PX1>(acc, P, P.c1, g1, nullptr, off1, buf, ximg,
-                                              (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
+    conv_pass<MF1, K1, NRT1, NPT1, true, PX1, PR>(acc, P, P.c1, g1, nullptr, off1, buf, ximg,
+                                                  (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
     XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {
@@ -908,9 +1048,9 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
         return;
     } else {
         // ---- S2: epilogue of layer 1 into the LDS tile
-        store_mid<MF1, NRT1, NPT1>(acc, P, P.c1, mid, my0, mx0, rt0, rt_end1, pt0, npx1,
-                                   KIND == KIND_POOL ? -FLT_MAX : 0.f);
-        if constexpr (KIND == KIND_FUSED2 && K1 == 1 && K2A == 1 && K2B == 0 && !SC) {
+        store_mid<MF1, NRT1, NPT1, (KIND == KIND_POOL ? 0 : PR)>(acc, P, P.c1, mid, my0, mx0, rt0, rt_end1, pt0, npx1,
+                                                                 KIND == KIND_POOL ? -FLT_MAX : 0.f);
+        if constexpr (KIND == KIND_FUSED2 && K1 == 1 && K2A == 1 && K2B == 0 && !SC && !PR) {
             if (P.n1 == 2) {
                 // second producer of a merge block (paper Fig. 4c): same input, same geometry, its own
                 // filter; its result is added to the first one's in the LDS tile
@@ -959,7 +1099,6 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
             // ---- S4/S5: sibling convolutions from the LDS tile, heavier one first.  Every pass covers
             // (row waves x NRT2) row tiles by (pixel waves x NPT2) pixel tiles; all waves stream the
             // same filter chunks.
-            typedef MM<MF2> M2;
             const int sub = lane / MF2, col = lane % MF2;
             const int npt2 = (P.th * P.vw2 + MF2 - 1) / MF2;
             const int wr2 = wave % P.waves_r2, wp2 = wave / P.waves_r2;
@@ -982,7 +1121,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                         g2.rt_base = rp;
                         const int r0 = rp + wr2 * NRT2, p0 = pp + wp2 * NPT2;
                         g2.active = r0 < rte && p0 < npt2;
-                        typename M2::Acc acc2[NRT2][NPT2];
+                        typename MM<MF2>::Acc acc2[NRT2][NPT2];
                         int off2[NPT2];
 #pragma unroll
                         for (int p = 0; p < NPT2; ++p) {
@@ -991,12 +1130,12 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                             for (int r = 1; r < NRT2; ++r) acc2[r][p] = acc2[0][p];
                             const int pidx = (p0 + p) * MF2 + col;
                             const int oy = min(pidx / P.vw2, P.th - 1), ox = min(pidx % P.vw2, P.tw - 1);
-                            off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * P.mid_gstride;
+                            off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * SUBP * P.mid_gstride;
                         }
 #ifdef XL_PHASE_TIMING
                         if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 0] = clock64();
 #endif
-                        conv_pass<MF2, KS2, NRT2, NPT2, false>(acc2, P, c, g2, mid, off2, buf, nullptr, 0ull, 0, 0);
+                        conv_pass<MF2, KS2, NRT2, NPT2, false, 0, PR>(acc2, P, c, g2, mid, off2, buf, nullptr, 0ull, 0, 0);
 #ifdef XL_PHASE_TIMING
                         if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 1] = clock64();
 #endif
@@ -1188,8 +1327,25 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
 // ----------------------------------------------------------------------------
 // launch table
 // ----------------------------------------------------------------------------
+// This file is compiled twice: once for the fp32 variants and everything else, and once with
+// XL_TU_B3 defined for the split-bf16 variants alone (the two halves build in parallel).
 typedef void (*BlockKernel)(const BlockParams);
+BlockKernel kernel_of_b3(int variant);
 
+#ifdef XL_TU_B3
+BlockKernel kernel_of_b3(int variant)
+{
+    switch (variant) {
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1)                                 \
+    case ID:                                                                                                 \
+        return block_kernel<KIND, MF1, K1, NRT1, NPT1, (MF2 == 0 ? 32 : MF2), (NRT2 == 0 ? 1 : NRT2),        \
+                            (NPT2 == 0 ? 1 : NPT2), (K2A == 0 ? 1 : K2A), K2B, (SC != 0), PX1, 1>;
+        XL_VARIANT_LIST_B3(X)
+#undef X
+    }
+    return nullptr;
+}
+#else
 template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC, int PX1>
 static BlockKernel select_kernel()
 {
@@ -1209,15 +1365,19 @@ static BlockKernel kernel_of(int variant)
         XL_VARIANT_LIST(X)
 #undef X
     }
-    return nullptr;
+    return kernel_of_b3(variant);
 }
 
 const std::vector<Variant> &variants()
 {
     static const std::vector<Variant> v = {
 #define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1) \
-    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1},
+    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1, 0},
         XL_VARIANT_LIST(X)
+#undef X
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1) \
+    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1, 1},
+        XL_VARIANT_LIST_B3(X)
 #undef X
     };
     return v;
@@ -1276,13 +1436,52 @@ __global__ void pack_filter_kernel(const float *__restrict__ w, f32x4 *__restric
     wp[idx] = v;
 }
 
-hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf, int nkg, int nrt,
-                              hipStream_t s, int pairs)
+// split-bf16 form: [K step][tap][row tile][hi, lo][lane] of 8 bf16;
+//   lane l holds cout = rt*mf + l%mf, cin = kg*kc + (l/mf)*8 + e, kc = 16 (mf = 32) or 32 (mf = 16);
+//   hi = bf16(w), lo = bf16(w - hi), round to nearest.
+__global__ void pack_filter_b3_kernel(const float *__restrict__ w, uint4 *__restrict__ wp, int cout, int cin, int k,
+                                      int mf, int nkg, int nrt)
 {
-    const long long total = (long long)nkg * k * k * nrt * 64;
+    const int taps = k * k;
+    const long long total = (long long)nkg * taps * nrt * 128;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int lane = (int)(idx & 63);
+    const int part = (int)((idx >> 6) & 1);
+    long long r = idx >> 7;
+    const int rt = (int)(r % nrt);
+    r /= nrt;
+    const int t = (int)(r % taps);
+    const int kg = (int)(r / taps);
+    const int o = rt * mf + lane % mf;
+    const int sub = lane / mf;
+    const int kc = mf == 32 ? 16 : 32;
+    unsigned out[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float v[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ci = kg * kc + sub * 8 + 2 * e + h;
+            v[h] = (o < cout && ci < cin) ? w[((size_t)o * cin + ci) * taps + t] : 0.f;
+        }
+        unsigned hi, lo;
+        split_bf16(v[0], v[1], hi, lo);
+        out[e] = part ? lo : hi;
+    }
+    wp[idx] = uint4{out[0], out[1], out[2], out[3]};
+}
+
+hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf, int nkg, int nrt,
+                              hipStream_t s, int pairs, int pr)
+{
+    const long long total = (long long)nkg * k * k * nrt * (pr ? 128 : 64);
     const int threads = 256;
     const int grid = (int)((total + threads - 1) / threads);
-    hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, wp, cout, cin, k, mf, nkg, nrt, pairs);
+    if (pr)
+        hipLaunchKernelGGL(pack_filter_b3_kernel, dim3(grid), dim3(threads), 0, s, w, (uint4 *)wp, cout, cin, k, mf, nkg, nrt);
+    else
+        hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, wp, cout, cin, k, mf, nkg, nrt, pairs);
     return hipGetLastError();
 }
 
@@ -1533,9 +1732,11 @@ hipError_t launch_depthwise(const float *x, float *y, const f32x4 *wp, const f32
     return hipGetLastError();
 }
 
+#endif  // XL_TU_B3
+
 }  // namespace xl
 
-#ifdef XL_PHASE_TIMING
+#if defined(XL_PHASE_TIMING) && !defined(XL_TU_B3)
 extern "C" int xl_debug_read_wtrace(unsigned long long *host, int count)
 {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(xl::g_wtrace), sizeof(unsigned long long) * count);

@@ -95,7 +95,9 @@ static std::vector<int> tile_candidates(int extent)
     return std::vector<int>(s.begin(), s.end());
 }
 
-static double mfma_clk(int mf) { return mf == 32 ? 64.0 : 32.0; }
+// matrix-pipe cycles of one K step of one (row tile, pixel tile) pair and tap: four fp32 operations of
+// 64 / 32 cycles, or three bf16 ones of 32 / 16 cycles over twice the channels
+static double kstep_clk(int mf, int pr) { return pr ? 3 * (mf == 32 ? 32.0 : 16.0) : 4 * (mf == 32 ? 64.0 : 32.0); }
 
 // Largest number of K steps per chunk the stagers can hold, shortened so that one chunk keeps
 // the matrix cores busy for about `want_clk` cycles (amortises the per-chunk barrier) and no more.
@@ -117,11 +119,11 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     const Variant &v = c.v;
     const int nw = c.threads / 64;
     const int mf1 = v.mf1;
-    const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
+    const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1, v.pr));
     const int taps1 = b.c1.k * b.c1.k;
     const int npx1 = c.mh * c.mw;
     const int wg_rt = c.waves_r1 * v.nrt1;
-    const double wave1 = (double)v.nrt1 * v.npt1 * nkg1 * taps1 * 4 * mfma_clk(mf1);
+    const double wave1 = (double)v.nrt1 * v.npt1 * nkg1 * taps1 * kstep_clk(mf1, v.pr);
     double simd[4] = {0, 0, 0, 0};
     for (int w = 0; w < nw; ++w) {
         const int wr = w % c.waves_r1, wp = w / c.waves_r1;
@@ -149,9 +151,9 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
         const int wg_rt2 = c.waves_r2 * NRT2, wg_pt2 = (nw / c.waves_r2) * NPT2;
         for (int ci = 0; ci < b.n2; ++ci) {
             const ConvSpec &s = b.c2[ci];
-            const int nrt = ceil_div(s.cout, mf2), nkg = ceil_div(s.cin, kc_of(mf2));
+            const int nrt = ceil_div(s.cout, mf2), nkg = ceil_div(s.cin, kc_of(mf2, v.pr));
             const int per = std::min(nrt, ceil_div(nrt, c.csplit));
-            const double wave2 = (double)NRT2 * NPT2 * nkg * s.k * s.k * 4 * mfma_clk(mf2);
+            const double wave2 = (double)NRT2 * NPT2 * nkg * s.k * s.k * kstep_clk(mf2, v.pr);
             for (int rp = 0; rp < per; rp += wg_rt2)
                 for (int pp = 0; pp < npt2; pp += wg_pt2) {
                     double s2[4] = {0, 0, 0, 0};
@@ -162,7 +164,7 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
                     t2 += *std::max_element(s2, s2 + 4) + 2500.0;       // + epilogue / prologue of the pass
                     barriers += ceil_div(nkg, c.chunk_kg2[ci]);
                     flops2 += 2LL * std::min(wg_rt2, per - rp) * mf2 * std::min(wg_pt2, npt2 - pp) * mf2 * nkg *
-                              kc_of(mf2) * s.k * s.k;
+                              kc_of(mf2, v.pr) * s.k * s.k;
                 }
         }
     } else if (b.kind == KIND_POOL) {
@@ -185,11 +187,11 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     // with pixels and channels rounded up to whole matrix-core tiles
     const long long tiles = (long long)c.tiles_x * c.tiles_y * b.N;
     const long long s1 = b.kind == KIND_DW ? 2LL * b.Cin * npx1 * taps1
-                                           : 2LL * nrt1 * mf1 * ceil_div(npx1, mf1) * mf1 * nkg1 * kc_of(mf1) * taps1;
+                                           : 2LL * nrt1 * mf1 * ceil_div(npx1, mf1) * mf1 * nkg1 * kc_of(mf1, v.pr) * taps1;
     c.flops_exec = tiles * (b.kind == KIND_SINGLE ? 1 : c.csplit) * s1 * b.n1 + tiles * c.csplit * flops2;
 }
 
-static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &lds_rejected)
+static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &lds_rejected, int pr)
 {
     Choice best;
     std::map<std::tuple<int, int, int, int>, Choice> per_key;     // best per (variant, threads, tile)
@@ -211,7 +213,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     bool any_lds_reject = false;
     for (const Variant &v : variants()) {
         const bool stream = v.kind == KIND_POOLS;          // conv -> pool as a stream of tiles: same block kind
-        if ((v.kind != b.kind && !(stream && b.kind == KIND_POOL)) || v.k1 != b.c1.k) continue;
+        if ((v.kind != b.kind && !(stream && b.kind == KIND_POOL)) || v.k1 != b.c1.k || v.pr != pr) continue;
 #ifdef XL_DEV_HOOKS     // development builds only: restrict the search to one kernel variant
         if (const char *only = std::getenv("XL_ONLY_VARIANT"))
             if (b.kind != KIND_SINGLE && std::atoi(only) != v.id) continue;
@@ -221,7 +223,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
         if (two) {
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
-        if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0)) continue;
+        if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0 && v.pr == 0)) continue;
         // variants whose stage 1 reads planar input chunks: a 1x1 filter, stride 1, no padding, whole
         // K steps of channels; the tile's ih rows of iws floats must fit px * 64 floats per channel
         // px1 < 0: the first layer's channels are packed two per channel slot (-px1 slots used): 32-wide
@@ -230,7 +232,8 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
         const int px = v.px1 > 0 ? v.px1 : 0;
         if (px > 0 && !(b.c1.k == 1 && b.c1.stride == 1 && b.c1.pad == 0 && b.c1.cin % kc_of(v.mf1) == 0)) continue;
         const int mf1 = v.mf1;
-        const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1));
+        const int nrt1 = ceil_div(b.c1.cout, mf1), nkg1 = ceil_div(b.c1.cin, kc_of(mf1, v.pr));
+        const int frows = v.pr ? 2 : 1;         // 1 KB filter rows per (K step, tap, row tile): hi and lo when split
         const int taps1 = b.c1.k * b.c1.k;
         for (int threads : {256, 512}) {
             if (pl.opts.force_threads > 0 && pl.opts.force_threads != threads) continue;
@@ -271,10 +274,10 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     c.tiles_y = ceil_div(b.Ho, th);
                     c.tiles_x = ceil_div(b.Wo, tw);
                     // stage-1 chunk: input tile chunk + filter chunk per buffer
-                    const int x_per_kg = gps_of(mf1) * c.ih * ((c.iw + 3) / 4 * 4);       // LDS rows hold whole 4-pixel units
-                    const int w_per_kg = taps1 * wg_rt * 64;
-                    const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * 4 * mfma_clk(mf1);
-                    const int x_units_per_kg = gps_of(mf1) * c.ih * ceil_div(c.iw, 4);     // 4-pixel row pieces
+                    const int x_per_kg = gps_of(mf1, v.pr) * c.ih * ((c.iw + 3) / 4 * 4);       // LDS rows hold whole 4-pixel units
+                    const int w_per_kg = taps1 * wg_rt * 64 * frows;
+                    const double clk1 = (double)(nw / 4.0) * v.nrt1 * v.npt1 * taps1 * kstep_clk(mf1, v.pr);
+                    const int x_units_per_kg = gps_of(mf1, v.pr) * c.ih * ceil_div(c.iw, 4);     // 4-pixel row pieces
                     c.chunk_kg = dw ? 1 : pick_chunk(nkg1, px > 0 ? 0 : x_units_per_kg, w_per_kg, threads, clk1, want_clk);
                     if (px > 0)     // planar chunk: kc x px x 16 quads per K step, at most PLANAR_SLOTS wave loads per wave
                         c.chunk_kg = std::min(c.chunk_kg, PLANAR_SLOTS * nw * 64 / (kc_of(mf1) * px * 16));
@@ -331,10 +334,10 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                         max_per = std::max(max_per, ceil_div(ceil_div(b.c2[i].cout, v.mf2), cs));
                                     if (w2 > 1 && (w2 / 2) * NRT2 >= max_per) continue;     // idle row waves
                                     for (int i = 0; i < b.n2; ++i) {
-                                        const int nkg2 = ceil_div(b.c2[i].cin, kc_of(v.mf2));
-                                        const int w2_per_kg = b.c2[i].k * b.c2[i].k * w2 * NRT2 * 64;
-                                        const double clk2 = (double)(nw / 4.0) * NRT2 * NPT2 * b.c2[i].k * b.c2[i].k * 4 *
-                                                            mfma_clk(v.mf2);
+                                        const int nkg2 = ceil_div(b.c2[i].cin, kc_of(v.mf2, v.pr));
+                                        const int w2_per_kg = b.c2[i].k * b.c2[i].k * w2 * NRT2 * 64 * frows;
+                                        const double clk2 = (double)(nw / 4.0) * NRT2 * NPT2 * b.c2[i].k * b.c2[i].k *
+                                                            kstep_clk(v.mf2, v.pr);
                                         c.chunk_kg2[i] = pick_chunk(nkg2, 0, w2_per_kg, threads, clk2, want_clk);
                                         if (c.chunk_kg2[i] < 1) {
                                             fits = false;
@@ -545,23 +548,25 @@ struct Builder {
         stores = tensor_elems(L.out);
     }
 
-    int packed_index(int layer, int mf, bool pairs = false)
+    int packed_index(int layer, int mf, bool pairs = false, int pr = 0)
     {
         for (size_t i = 0; i < pl.packed.size(); ++i)
-            if (pl.packed[i].layer == layer && pl.packed[i].mf == mf && pl.packed[i].pairs == pairs) return (int)i;
+            if (pl.packed[i].layer == layer && pl.packed[i].mf == mf && pl.packed[i].pairs == pairs && pl.packed[i].pr == pr)
+                return (int)i;
         const xl_layer &L = pl.layers[layer];
         PackedFilter p;
         p.layer = layer;
         p.mf = mf;
         p.pairs = pairs;
+        p.pr = pr;
         if (mf == 0) {      // depthwise: [channel group][tap] float4 and [channel group][scale, shift] float4
             p.nkg = p.nrt = 0;
             p.bytes = (size_t)ceil_div(L.cout, 4) * L.k * L.k * 16;
             p.aff_bytes = (size_t)ceil_div(L.cout, 4) * 2 * 16;
         } else {
-            p.nkg = pairs ? 1 : ceil_div(L.cin, kc_of(mf));
+            p.nkg = pairs ? 1 : ceil_div(L.cin, kc_of(mf, pr));
             p.nrt = ceil_div(L.cout, mf);
-            p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16;
+            p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16 * (pr ? 2 : 1);
             p.aff_bytes = (size_t)p.nrt * (mf == 32 ? 4 : 1) * 2 * 64 * 16;
         }
         p.offset = 0;
@@ -575,7 +580,10 @@ struct Builder {
                               const std::string &what)
     {
         bool lds_rejected = false;
-        std::vector<Choice> ranked = search(b, pl, lds_rejected);
+        // split-bf16 kernels where the plan asks for them and a variant covers the block, fp32 ones otherwise
+        std::vector<Choice> ranked;
+        if (pl.opts.precision == XL_PRECISION_BF16X3) ranked = search(b, pl, lds_rejected, 1);
+        if (ranked.empty()) ranked = search(b, pl, lds_rejected, 0);
         if (ranked.empty())
             return fail(lds_rejected ? XL_E_LDS_BUDGET : XL_E_UNSUPPORTED,
                         what + (lds_rejected ? ": no tile fits the LDS budget" : ": no kernel variant covers this block"));
@@ -606,7 +614,7 @@ struct Builder {
         st.sc_id = sc_id;
         st.conv_layer[0] = b.c1.layer;
         st.conv_layer[1] = st.conv_layer[2] = -1;
-        st.packed[0] = packed_index(b.c1.layer, b.kind == KIND_DW ? 0 : ch.v.mf1, ch.v.px1 < 0);
+        st.packed[0] = packed_index(b.c1.layer, b.kind == KIND_DW ? 0 : ch.v.mf1, ch.v.px1 < 0, ch.v.pr);
         st.packed[1] = st.packed[2] = -1;
         BlockParams &p = st.bp;
         memset(&p, 0, sizeof p);
@@ -631,7 +639,7 @@ struct Builder {
             w.stride = s.stride;
             w.pad = s.pad;
             w.relu = s.relu;
-            w.nkg = ceil_div(s.cin, kc_of(mf));
+            w.nkg = ceil_div(s.cin, kc_of(mf, ch.v.pr));
             w.nrt = ceil_div(s.cout, mf);
         };
         fill(p.c1, b.c1, ch.v.mf1);
@@ -652,7 +660,7 @@ struct Builder {
             fill(p.c2[i], b.c2[i], ch.v.mf2);
             p.coff2[i] = ys.coff + b.coff2[i];
             st.conv_layer[1 + i] = b.c2[i].layer;
-            st.packed[1 + i] = packed_index(b.c2[i].layer, ch.v.mf2);
+            st.packed[1 + i] = packed_index(b.c2[i].layer, ch.v.mf2, false, ch.v.pr);
             P2 = std::max(P2, b.c2[i].pad);
         }
         p.s2 = two ? b.c2[0].stride : (b.kind == KIND_POOL ? b.pool_s : 1);
@@ -699,8 +707,9 @@ struct Builder {
         gi.threads = ch.threads;
         gi.lds_bytes = ch.lds_bytes;
         gi.workgroups_per_cu = ch.occ;
-        gi.chunk_channels = ch.chunk_kg * kc_of(ch.v.mf1);
+        gi.chunk_channels = ch.chunk_kg * kc_of(ch.v.mf1, ch.v.pr);
         gi.flops_executed = ch.flops_exec;
+        gi.precision = ch.v.pr ? XL_PRECISION_BF16X3 : XL_PRECISION_FP32;
         if (b.kind == KIND_SINGLE) {
             gi.redundancy = 1.0;
         } else {

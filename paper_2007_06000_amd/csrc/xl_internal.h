@@ -17,12 +17,15 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // Matrix-core tile geometry.  MF = 32 uses V_MFMA_F32_32X32X2_F32 (one K step of
 // the packed filter covers 8 input channels: 2 lane halves x 4 components),
 // MF = 16 uses V_MFMA_F32_16X16X4_F32 (16 channels: 4 lane quarters x 4).
-constexpr int kc_of(int mf) { return mf == 32 ? 8 : 16; }       // channels per K step
-constexpr int gps_of(int mf) { return mf == 32 ? 2 : 4; }       // 4-channel groups per K step
+// With split-bf16 operands (pr = 1: V_MFMA_F32_32X32X16_BF16 / V_MFMA_F32_16X16X32_BF16, three per
+// product) a lane holds 8 channels and a K step covers twice as many.
+constexpr int kc_of(int mf, int pr = 0) { return (mf == 32 ? 8 : 16) << pr; }      // channels per K step
+constexpr int gps_of(int mf, int pr = 0) { return (mf == 32 ? 2 : 4) << pr; }      // 4-channel groups per K step
 
 // One convolution as the kernels see it.
 struct ConvW {
     const f32x4 *wp;        // filter re-laid out as [K step][tap][row tile][lane] of float4
+                            // (split-bf16 kernels: [K step][tap][row tile][hi, lo][lane] of 8 bf16)
     const f32x4 *aff;       // scale / shift in accumulator order: [row tile][quad][scale, shift][lane] float4
     int cin, cout;
     int k, stride, pad;
@@ -96,6 +99,7 @@ struct Variant {
     int sc;                     // 1: adds a shortcut tensor in the epilogue (merge mode)
     int px1;                    // > 0: stage 1 (1x1 filter) reads a planar input chunk, px1 * 64 floats per channel;
                                 // < 0: stage 1 uses only -px1 of the 4 channel slots (<= -2 * px1 input channels)
+    int pr;                     // 0: fp32 matrix operations; 1: split-bf16 operands (3 bf16 operations per product)
 };
 
 // id, kind, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1
@@ -203,6 +207,41 @@ struct Variant {
     X(40, KIND_POOL, 16, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
     X(41, KIND_POOL, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)
 
+// Variants with split-bf16 operands (ids from 200): same columns.  Stage 2 uses 32-row tiles only, so
+// that its K step (16 channels) divides what stage 1 writes into the LDS tile (whole 16- or 32-row tiles).
+#define XL_VARIANT_LIST_B3(X)                                      \
+    X(200, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    X(201, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    X(202, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0, 0)          \
+    X(203, KIND_SINGLE, 32, 1, 2, 4, 0, 0, 0, 0, 0, 0, 0)          \
+    X(204, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0, 0)          \
+    X(205, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    X(206, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    X(207, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0, 0, 0, 0)          \
+    X(208, KIND_SINGLE, 32, 5, 1, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    /* split */                                                    \
+    X(210, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)         \
+    X(211, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 0)         \
+    X(212, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)         \
+    X(213, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 2, 3, 1, 0, 0)         \
+    /* straight and merge */                                       \
+    X(220, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0, 0)         \
+    X(221, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1, 0)         \
+    X(222, KIND_FUSED2, 32, 3, 2, 2, 32, 2, 2, 3, 0, 0, 0)         \
+    X(223, KIND_FUSED2, 32, 3, 2, 2, 32, 2, 2, 3, 0, 1, 0)         \
+    X(224, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0, 0)         \
+    X(225, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 1, 0)         \
+    X(226, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 0, 0)         \
+    X(227, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 1, 0)         \
+    X(228, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 0, 0)         \
+    X(229, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 1, 0)         \
+    X(230, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0, 0)         \
+    X(231, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0, 0)         \
+    /* conv -> maxpool (the LDS tile stays fp32) */                \
+    X(240, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(241, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
+    X(242, KIND_POOL, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)
+
 const std::vector<Variant> &variants();
 
 constexpr int STAGE_UNITS = 1;      // input units (4 channels x 4 pixels) each thread stages per chunk
@@ -219,7 +258,7 @@ hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t l
 hipError_t configure_kernels(int max_lds_bytes);      // raises the dynamic-LDS cap of every variant
 
 hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf,
-                              int nkg, int nrt, hipStream_t s, int pairs = 0);
+                              int nkg, int nrt, hipStream_t s, int pairs = 0, int pr = 0);
 hipError_t launch_pack_affine(const float *scale, const float *shift, f32x4 *out, int cout, int mf, int nrt,
                               hipStream_t s);
 hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, int Ho, int Wo,
