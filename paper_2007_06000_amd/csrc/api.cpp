@@ -1,6 +1,8 @@
 // C ABI of libxl (see include/xl.h).
 #include <cstdint>
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -329,6 +331,14 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
                 float t;
                 time_alt(a, 2, t);
                 quick.push_back({t, (int)a});
+#ifdef XL_DEV_HOOKS     // development builds only: one line per candidate
+                if (std::getenv("XL_TUNE_LOG")) {
+                    const xl::Step &c = st.alts[a];
+                    fprintf(stderr, "[tune] pass %d group %d alt %zu variant %d thr %d tile %dx%d lds %d chunk %d/%d/%d wr %d/%d cs %d vw %d: %.1f us\n",
+                            pass, st.group, a, c.variant, c.threads, c.bp.th, c.bp.tw, c.lds_bytes, c.bp.chunk_kg,
+                            c.bp.chunk_kg2[0], c.bp.chunk_kg2[1], c.bp.waves_r1, c.bp.waves_r2, c.bp.csplit, c.bp.vw2, t * 1e3f);
+                }
+#endif
             }
             int best = 0;
             float best_ms = 1e30f;
@@ -365,6 +375,7 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
                 gi.threads = src.threads; gi.lds_bytes = src.lds_bytes;
                 gi.workgroups_per_cu = src.workgroups_per_cu; gi.chunk_channels = src.chunk_channels;
                 gi.flops_executed = src.flops_executed; gi.redundancy = src.redundancy;
+                gi.precision = src.precision;
             }
         }
     }

@@ -581,9 +581,22 @@ struct Builder {
     {
         bool lds_rejected = false;
         // split-bf16 kernels where the plan asks for them and a variant covers the block, fp32 ones otherwise
-        std::vector<Choice> ranked;
-        if (pl.opts.precision == XL_PRECISION_BF16X3) ranked = search(b, pl, lds_rejected, 1);
-        if (ranked.empty()) ranked = search(b, pl, lds_rejected, 0);
+        std::vector<Choice> ranked = search(b, pl, lds_rejected, 0);
+        if (pl.opts.precision == XL_PRECISION_BF16X3) {
+            // the split-bf16 candidates first (the cost model cannot rank the two kinds against each other
+            // well: blocks that are not bound by the matrix cores gain nothing from the split), then the
+            // best fp32 ones, for xl_tune to choose from
+            bool rej1 = false;
+            std::vector<Choice> split = search(b, pl, rej1, 1);
+            if (!split.empty()) {
+                const size_t keep32 = MAX_ALTERNATIVES / 4;
+                if (split.size() > MAX_ALTERNATIVES - keep32) split.resize(MAX_ALTERNATIVES - keep32);
+                if (ranked.size() > keep32) ranked.resize(keep32);
+                split.insert(split.end(), ranked.begin(), ranked.end());
+                ranked.swap(split);
+                lds_rejected = false;
+            }
+        }
         if (ranked.empty())
             return fail(lds_rejected ? XL_E_LDS_BUDGET : XL_E_UNSUPPORTED,
                         what + (lds_rejected ? ": no tile fits the LDS budget" : ": no kernel variant covers this block"));

@@ -219,11 +219,21 @@ struct Variant {
     X(206, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)          \
     X(207, KIND_SINGLE, 32, 3, 2, 2, 0, 0, 0, 0, 0, 0, 0)          \
     X(208, KIND_SINGLE, 32, 5, 1, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    X(209, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 0, 0, 0)          \
+    X(214, KIND_SINGLE, 32, 1, 4, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    X(215, KIND_SINGLE, 32, 1, 4, 2, 0, 0, 0, 0, 0, 0, 0)          \
+    X(216, KIND_SINGLE, 32, 3, 4, 1, 0, 0, 0, 0, 0, 0, 0)          \
+    X(217, KIND_SINGLE, 32, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)          \
+    X(218, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)          \
     /* split */                                                    \
     X(210, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)         \
     X(211, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 0)         \
     X(212, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)         \
     X(213, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 2, 3, 1, 0, 0)         \
+    X(232, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 2, 3, 1, 0, 0)         \
+    X(233, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 0)         \
+    X(234, KIND_FUSED2, 32, 1, 1, 1, 32, 4, 1, 3, 1, 0, 0)         \
+    X(235, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 0)         \
     /* straight and merge */                                       \
     X(220, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0, 0)         \
     X(221, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1, 0)         \
