@@ -20,6 +20,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 matrix cores
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores
 CACHE_BYTES = 512 << 20        # rotate buffers over more than L2 + Infinity Cache (256 MB)
 TUNE = True                    # xl_tune picks tiles by measurement once, outside the timed region
 
@@ -40,10 +41,10 @@ def time_steps(fn, steps, warmup, torch):
     return ev0.elapsed_time(ev1) / steps, wall / steps
 
 
-def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True):
+def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True, precision=0):
     wl = cfg if isinstance(cfg, W.Workload) else W.config(cfg)
     x, params = W.make_tensors(wl)
-    s = Session(wl, x, params, tune=TUNE)
+    s = Session(wl, x, params, tune=TUNE, precision=precision)
     in_bytes = x.nbytes
     out_bytes = int(np.prod(wl.shapes[wl.output_id])) * 4
     sets = 1
@@ -77,6 +78,9 @@ def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True):
         "mfma_frac": flops / ms_f / 1e9 / MFMA_FP32_PEAK_TFLOPS,
         "buffer_sets": sets,
     }
+    if precision:
+        res["split_bf16_blocks"] = sum(1 for g in groups if g["precision"] == 1)
+        res["blocks_total"] = len(groups)
     return res, s, wl, x, params
 
 
@@ -111,6 +115,8 @@ def main():
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident) instead of rotating")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the planner's cost-model choice without xl_tune")
+    ap.add_argument("--no-bf16x3", action="store_true",
+                    help="skip the separate report of the split-bf16 precision mode (three bf16 matrix operations per product)")
     args = ap.parse_args()
     global TUNE
     TUNE = not args.no_tune
@@ -173,6 +179,24 @@ def main():
             r["workload"] = tag + ":" + r["workload"]
             blocks.append(r)
         out["blocks"] = blocks
+    if not args.no_bf16x3:
+        # reduced-precision operand mode, reported apart from the fp32 headline: same workloads, same
+        # tolerance against the oracle, other arithmetic and other roofline denominator
+        rb, *_ = bench_workload(args.workload, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm,
+                                precision=1)
+        b3 = {"arithmetic": "operands split into hi + lo bf16, 3 bf16 matrix operations per product, fp32 accumulate",
+              "workload": rb["workload"], "value": rb["images_per_s"], "unit": "images/s",
+              "ms_per_step": rb["ms_fused"], "ms_per_step_unfused": rb["ms_unfused"],
+              "speedup_vs_unfused": rb["speedup_vs_unfused"], "speedup_vs_fp32": res["ms_fused"] / rb["ms_fused"],
+              "split_bf16_blocks": rb["split_bf16_blocks"], "blocks_total": rb["blocks_total"],
+              "roofline": dominant_kernel_roofline(args.workload, rb, args, torch, np, W, Session, precision=1)}
+        if not args.headline_only:
+            b3["blocks"] = []
+            for c in (2, 3, 4):
+                r, *_ = bench_workload(c, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm, precision=1)
+                b3["blocks"].append({k: r[k] for k in ("workload", "batch", "ms_fused", "ms_unfused", "images_per_s",
+                                                       "speedup_vs_unfused", "tflops", "split_bf16_blocks")})
+        out["bf16x3"] = b3
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload, W, np)
     print(json.dumps(out))
@@ -216,12 +240,15 @@ def measured_traffic(kernel_name):
     return None
 
 
-def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
+def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session, precision=0):
     """Time the block that dominates the headline workload on its own (one
-    kernel launch per step) and price it against the roofline that bounds it."""
+    kernel launch per step) and price it against the roofline that bounds it.
+    precision = 1: the split-bf16 kernels, priced against the dense bf16 matrix
+    peak divided by the three operations a product costs."""
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS / 3.0 if precision else MFMA_FP32_PEAK_TFLOPS
     wl_full = W.config(cfg)
     x, params = W.make_tensors(wl_full)
-    s = Session(wl_full, x, params, tune=False)
+    s = Session(wl_full, x, params, tune=False, precision=precision)
     groups = [s.plan.query(g) for g in range(s.plan.num_groups)]
     if len(groups) == 1:
         g = groups[0]
@@ -230,12 +257,12 @@ def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
     else:
         # the block with the largest roofline time, rebuilt as a workload of its own
         def t_roof(g):
-            return max(g["flops"] / (MFMA_FP32_PEAK_TFLOPS * 1e12), g["bytes_fused"] / (HBM_PEAK_GBS * 1e9))
+            return max(g["flops"] / (mfma_peak * 1e12), g["bytes_fused"] / (HBM_PEAK_GBS * 1e9))
         gi = max(range(len(groups)), key=lambda i: t_roof(groups[i]))
         g = groups[gi]
         sub = W.subgraph(wl_full, gi)
         xs, ps = W.make_tensors(sub)
-        ss = Session(sub, xs, ps, tune=TUNE)
+        ss = Session(sub, xs, ps, tune=TUNE, precision=precision)
         in_b, out_b = xs.nbytes, int(np.prod(sub.shapes[sub.output_id])) * 4
         sets = max(1, min(64, -(-CACHE_BYTES // (in_b + out_b)))) if not args.warm else 1
         bx = [ss.x] + [ss.x.clone() for _ in range(sets - 1)]
@@ -243,13 +270,16 @@ def dominant_kernel_roofline(cfg, res, args, torch, np, W, Session):
         ms, _ = time_steps(lambda i: ss.run(True, bx[i % sets], by[i % sets]), args.steps, args.warmup, torch)
         g = ss.plan.query(0)
         name = sub.name
-    t_m = g["flops"] / (MFMA_FP32_PEAK_TFLOPS * 1e12)
+    t_m = g["flops"] / (mfma_peak * 1e12)
     t_h = g["bytes_fused"] / (HBM_PEAK_GBS * 1e9)
     if t_m >= t_h:
         ach = g["flops"] / ms / 1e9
-        return {"bound": "mfma", "achieved": ach, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_FP32_PEAK_TFLOPS, "traffic": measured_traffic(name), "kernel": name, "kernel_ms": ms,
-                "flops_per_launch": g["flops"], "bytes_per_launch": g["bytes_fused"]}
+        r = {"bound": "mfma", "achieved": ach, "peak": mfma_peak, "unit": "TFLOP/s",
+             "frac": ach / mfma_peak, "traffic": None if precision else measured_traffic(name), "kernel": name,
+             "kernel_ms": ms, "flops_per_launch": g["flops"], "bytes_per_launch": g["bytes_fused"]}
+        if precision:
+            r["peak_note"] = "bf16 dense matrix peak 2500 TFLOP/s / 3 operations per product; flops = 2*MAC of the layer"
+        return r
     ach = g["bytes_fused"] / ms / 1e6
     return {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
             "traffic": measured_traffic(name), "kernel": name, "kernel_ms": ms,

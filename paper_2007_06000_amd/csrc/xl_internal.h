@@ -213,7 +213,6 @@ struct Variant {
     X(200, KIND_SINGLE, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)          \
     X(201, KIND_SINGLE, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)          \
     X(202, KIND_SINGLE, 32, 1, 2, 2, 0, 0, 0, 0, 0, 0, 0)          \
-    X(203, KIND_SINGLE, 32, 1, 2, 4, 0, 0, 0, 0, 0, 0, 0)          \
     X(204, KIND_SINGLE, 16, 1, 1, 3, 0, 0, 0, 0, 0, 0, 0)          \
     X(205, KIND_SINGLE, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)          \
     X(206, KIND_SINGLE, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)          \
@@ -221,7 +220,6 @@ struct Variant {
     X(208, KIND_SINGLE, 32, 5, 1, 1, 0, 0, 0, 0, 0, 0, 0)          \
     X(209, KIND_SINGLE, 32, 1, 2, 3, 0, 0, 0, 0, 0, 0, 0)          \
     X(214, KIND_SINGLE, 32, 1, 4, 1, 0, 0, 0, 0, 0, 0, 0)          \
-    X(215, KIND_SINGLE, 32, 1, 4, 2, 0, 0, 0, 0, 0, 0, 0)          \
     X(216, KIND_SINGLE, 32, 3, 4, 1, 0, 0, 0, 0, 0, 0, 0)          \
     X(217, KIND_SINGLE, 32, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)          \
     X(218, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)          \
@@ -229,16 +227,11 @@ struct Variant {
     X(210, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)         \
     X(211, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 0)         \
     X(212, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)         \
-    X(213, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 2, 3, 1, 0, 0)         \
-    X(232, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 2, 3, 1, 0, 0)         \
     X(233, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 0)         \
-    X(234, KIND_FUSED2, 32, 1, 1, 1, 32, 4, 1, 3, 1, 0, 0)         \
     X(235, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 0)         \
     /* straight and merge */                                       \
     X(220, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0, 0)         \
     X(221, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1, 0)         \
-    X(222, KIND_FUSED2, 32, 3, 2, 2, 32, 2, 2, 3, 0, 0, 0)         \
-    X(223, KIND_FUSED2, 32, 3, 2, 2, 32, 2, 2, 3, 0, 1, 0)         \
     X(224, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0, 0)         \
     X(225, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 3, 0, 1, 0)         \
     X(226, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 0, 0, 0)         \
@@ -249,8 +242,7 @@ struct Variant {
     X(231, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0, 0)         \
     /* conv -> maxpool (the LDS tile stays fp32) */                \
     X(240, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
-    X(241, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
-    X(242, KIND_POOL, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)
+    X(241, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)
 
 const std::vector<Variant> &variants();
 
