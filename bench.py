@@ -115,6 +115,8 @@ def main():
     ap.add_argument("--warm", action="store_true", help="reuse one buffer set (cache-resident) instead of rotating")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the planner's cost-model choice without xl_tune")
+    ap.add_argument("--precision", choices=["fp32", "bf16x3"], default="fp32",
+                    help="arithmetic of the headline run; bf16x3 times the split-bf16 mode alone (for profiles)")
     ap.add_argument("--no-bf16x3", action="store_true",
                     help="skip the separate report of the split-bf16 precision mode (three bf16 matrix operations per product)")
     args = ap.parse_args()
@@ -139,18 +141,21 @@ def main():
         traffic_probe(args.workload, torch, np, W, Session)
         return
 
+    prec = 1 if args.precision == "bf16x3" else 0
+    if prec:
+        args.no_bf16x3 = True
     res, s, wl, x, params = bench_workload(args.workload, args.steps, args.warmup, torch, np, W, Session,
-                                           cold=not args.warm)
+                                           cold=not args.warm, precision=prec)
 
     # roofline of the dominant kernel of the headline workload
-    roof = dominant_kernel_roofline(args.workload, res, args, torch, np, W, Session)
+    roof = dominant_kernel_roofline(args.workload, res, args, torch, np, W, Session, precision=prec)
 
     out = {
         "metric": "images/sec per fused block + HBM GB/s vs roofline; speedup over unfused",
         "value": res["images_per_s"], "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_fused"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16 hi+lo operands (3 products), f32 accumulate" if prec else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "launches_per_step": res["launches_fused"],
                    "buffers": "rotating (cold)" if not args.warm else "single set (warm)",
                    "tiles": "xl_tune (measured)" if TUNE else "cost model"},
@@ -168,14 +173,14 @@ def main():
             if c == args.workload:
                 blocks.append({k: res[k] for k in res})
                 continue
-            r, *_ = bench_workload(c, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm)
+            r, *_ = bench_workload(c, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm, precision=prec)
             blocks.append(r)
         # the paper's four fused structures (its Table 1; b.1 is the family of config 3), at batch 32
         table1 = {"table1_a1": W.straight_generic(32, 192, 28, 28, 16, 1, 0, 1, 32, 5, 2, 1),
                   "table1_a2": W.depthwise_pointwise(32, 16, 80, 80, 16),
                   "table1_c1": W.merge_two_producers(32)}
         for tag, wl in table1.items():
-            r, *_ = bench_workload(wl, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm)
+            r, *_ = bench_workload(wl, args.steps, args.warmup, torch, np, W, Session, cold=not args.warm, precision=prec)
             r["workload"] = tag + ":" + r["workload"]
             blocks.append(r)
         out["blocks"] = blocks

@@ -117,7 +117,7 @@ typedef struct xl_options {
                                XL_PRECISION_BF16X3: every operand of a convolution is split into
                                two bf16 numbers, hi = bf16(x) and lo = bf16(x - hi), and a product
                                is hi*hi + hi*lo + lo*hi on the bf16 matrix cores, accumulated in
-                               fp32 (error below 2^-16 of |a||b| per product; operands must be
+                               fp32 (error at most 3 * 2^-16 of |a||b| per product, about 4e-6 rms; operands must be
                                finite and below 2^127 in magnitude).  Tensors in memory stay fp32.
                                Blocks no split-bf16 kernel covers (depthwise first layers, the
                                two-producer merge form) run the fp32 kernels. */

@@ -48,7 +48,7 @@ __device__ unsigned long long g_wtrace[8 * 8 * 16 * 4];     // [block][wave][chu
 // ----------------------------------------------------------------------------
 // PR = 0: fp32 operands.  PR = 1: every operand is held as two bf16 numbers, hi = bf16(x) and
 // lo = bf16(x - hi) (round to nearest), and a product is the sum of three bf16 matrix operations
-// hi*hi + hi*lo + lo*hi accumulated in fp32; what is left out is below 2^-16 of |a||b|.  One K step
+// hi*hi + hi*lo + lo*hi accumulated in fp32; what is left out is at most 3 * 2^-16 of |a||b|.  One K step
 // then covers 16 (MF = 32) or 32 (MF = 16) channels, 8 per lane.  The accumulator layout is the
 // same in both modes.
 template <int MF, int PR = 0>

@@ -173,3 +173,48 @@ def test_paper_tuner_only_restricts_tiles():
     q = B.Plan(wl, paper_tuner_only=1).query(0)
     allowed = {t for t, g in B.xl_tuner_candidates(56)}
     assert q["tile_h"] == q["tile_w"] and q["tile_h"] in allowed
+
+
+def test_precision_option_selects_split_bf16_kernels_where_they_exist():
+    q = B.Plan(W.config(4)).query(0)
+    assert q["precision"] == 0
+    q = B.Plan(W.config(4), precision=1).query(0)
+    assert q["precision"] == 1 and q["chunk_channels"] % 16 == 0     # a K step covers 16 or 32 channels
+    # no split-bf16 kernel for a depthwise first layer or the two-producer merge form: fp32 kernels
+    assert B.Plan(W.depthwise_pointwise(1, 16, 80, 80, 16), precision=1).query(0)["precision"] == 0
+    assert B.Plan(W.merge_two_producers(1), precision=1).query(0)["precision"] == 0
+    with pytest.raises(B.XlError):
+        B.Plan(W.config(4), precision=2)
+
+
+def test_split_bf16_error_model():
+    """x = hi + lo + r with hi = bf16(x), lo = bf16(x - hi) (round to nearest even), and
+    a*b ~ hi*hi + hi*lo + lo*hi: the part left out (lo*lo and the two r terms, each at most
+    2^-16 |a||b|) stays below 3 * 2^-16 |a||b| per product, which over
+    the reductions of the benchmark configs (up to 9 * 512 terms of random sign) is far inside the
+    1e-4 parity tolerance."""
+    import numpy as np
+
+    def bf16(x):
+        u = x.astype(np.float32).view(np.uint32).astype(np.uint64)
+        u = (u + 0x7fff + ((u >> 16) & 1)) & 0xffff0000
+        return u.astype(np.uint32).view(np.float32)
+
+    rng = np.random.default_rng(5)
+    a = (rng.standard_normal(1 << 16) * np.exp(rng.uniform(-20, 20, 1 << 16))).astype(np.float32)
+    b = (rng.standard_normal(1 << 16) * np.exp(rng.uniform(-20, 20, 1 << 16))).astype(np.float32)
+    ah, bh = bf16(a), bf16(b)
+    al, bl = bf16(a - ah), bf16(b - bh)
+    assert (np.abs(a - ah) <= 2.0 ** -8 * np.abs(a)).all() and (np.abs(al) <= 2.0 ** -8 * np.abs(a)).all()
+    approx = ah.astype(np.float64) * bh + ah.astype(np.float64) * bl + al.astype(np.float64) * bh
+    exact = a.astype(np.float64) * b
+    assert (np.abs(approx - exact) <= 3 * 2.0 ** -16 * np.abs(exact)).all()
+    # a reduction of the size of config 4's (64 channels x 9 taps), unit-variance operands scaled like the workloads
+    K = 576
+    x = rng.standard_normal((256, K)).astype(np.float32)
+    w = (rng.standard_normal((K, 64)) / np.sqrt(K)).astype(np.float32)
+    xh, wh = bf16(x), bf16(w)
+    xl, wl = bf16(x - xh), bf16(w - wh)
+    y3 = xh.astype(np.float64) @ wh + xh.astype(np.float64) @ wl + xl.astype(np.float64) @ wh
+    y = x.astype(np.float64) @ w
+    assert np.abs(y3 - y).max() < 2e-5      # a fifth of the absolute part of the tolerance
