@@ -899,6 +899,50 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
     }
 }
 
+// Epilogue of a stage-2 pass whose result is max-pooled before it leaves the chip (KIND_FUSED2P):
+// scale / shift / activation, then into an LDS tile [4-channel group of the pass][row][col][4] of the
+// th x tw stage-2 output tile; positions outside the layer's output extent get -FLT_MAX, so the pooling
+// windows ignore them.  rl0: this wave's first row tile relative to the pass.
+template <int MF, int NRT, int NPT>
+__device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
+                                           const ConvW &c, float *tile, int oy0, int ox0, int rl0, int rt0, int rt_end,
+                                           int pt0)
+{
+    typedef MM<MF> M;
+    const int lane = threadIdx.x & 63;
+    const int sub = lane / MF, col = lane % MF;
+    const int npx = P.th * P.tw;
+    asm volatile("" ::: "memory");
+    f32x4 fa[NRT][M::NQ], fb[NRT][M::NQ];
+#pragma unroll
+    for (int r = 0; r < NRT; ++r)
+#pragma unroll
+        for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[r][q], fb[r][q]);
+#pragma unroll
+    for (int p = 0; p < NPT; ++p) {
+        const int pidx = (pt0 + p) * MF + col;
+        const int oy = pidx / P.vw2, ox = pidx - oy * P.vw2;
+        const bool valid = oy < P.th && ox < P.tw;
+        const bool inside = oy0 + oy < P.H2 && ox0 + ox < P.W2;
+#pragma unroll
+        for (int r = 0; r < NRT; ++r) {
+            if (rt0 + r >= rt_end) continue;
+#pragma unroll
+            for (int q = 0; q < M::NQ; ++q) {
+                const int cl = (rl0 + r) * MF + M::quad_row(q, sub);
+                f32x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
+                    if (c.relu) z = fmaxf(z, 0.f);
+                    v[i] = inside ? z : -FLT_MAX;
+                }
+                if (valid) *(f32x4 *)(tile + ((cl >> 2) * npx + oy * P.tw + ox) * 4) = v;
+            }
+        }
+    }
+}
+
 // ----------------------------------------------------------------------------
 // Depthwise stage 1 (paper Table 1, a.2: a 3x3 convolution with one filter per channel feeding a
 // pointwise one).  No reduction over channels, so no matrix cores: the halo-extended input tile of
@@ -980,7 +1024,9 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
     const int cs = (L / tiles) % P.csplit;
     const int n = L / (tiles * P.csplit);
     const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
-    const int oy0 = ty * P.th, ox0 = tx * P.tw;
+    // KIND_FUSED2P: th x tw is the stage-2 tile the pooled pth x ptw output tile needs; neighbours overlap
+    const int oy0 = (KIND == KIND_FUSED2P) ? ty * P.pth * P.ps2 : ty * P.th;
+    const int ox0 = (KIND == KIND_FUSED2P) ? tx * P.ptw * P.ps2 : tx * P.tw;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
@@ -1139,7 +1185,36 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
 #ifdef XL_PHASE_TIMING
                         if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 1] = clock64();
 #endif
-                        if (g2.active)
+                        if constexpr (KIND == KIND_FUSED2P) {
+                            // the pass covers every pixel of the tile (planner): its result goes to an LDS tile
+                            // over the staging buffers, which no wave reads any more, and is pooled from there
+                            if (g2.active)
+                                store_tile<MF2, NRT2, NPT2>(acc2, P, c, buf, oy0, ox0, wr2 * NRT2, r0, rte, p0);
+                            __syncthreads();
+                            const int ngr = (min(rte - rp, g2.wg_rt) * MF2) >> 2;
+                            const int npo = P.pth * P.ptw, npx2 = P.th * P.tw;
+                            const size_t plane = (size_t)P.Ho * P.Wo;
+                            for (int it = threadIdx.x; it < ngr * npo; it += blockDim.x) {
+                                const int gq = it / npo, pidx = it - gq * npo;
+                                const int py = pidx / P.ptw, px = pidx - py * P.ptw;
+                                const int gy = ty * P.pth + py, gx = tx * P.ptw + px;
+                                if (gy >= P.Ho || gx >= P.Wo) continue;
+                                const float *sp = buf + (gq * npx2 + (py * P.ps2) * P.tw + px * P.ps2) * 4;
+                                f32x4 m = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
+                                for (int u = 0; u < P.pool_k; ++u)
+                                    for (int v = 0; v < P.pool_k; ++v) {
+                                        const f32x4 t = *(const f32x4 *)(sp + (u * P.tw + v) * 4);
+#pragma unroll
+                                        for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
+                                    }
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const int co = rp * MF2 + gq * 4 + j;
+                                    if (co < c.cout) P.y[((size_t)n * P.Cy + coff + co) * plane + (size_t)gy * P.Wo + gx] = m[j];
+                                }
+                            }
+                            __syncthreads();
+                        } else if (g2.active)
                             store_global<MF2, NRT2, NPT2, SC>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
                                                               p0, P.relu_out);
 #ifdef XL_PHASE_TIMING

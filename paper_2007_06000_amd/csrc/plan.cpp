@@ -68,6 +68,7 @@ struct BlockSpec {
     int pool_k = 0, pool_s = 1, pool_p = 0;
     int N = 0, Cin = 0, H = 0, W = 0;
     int H1 = 0, W1 = 0, Ho = 0, Wo = 0;
+    int H2 = 0, W2 = 0;             // KIND_FUSED2P: stage-2 output extent, pooled (pool_k, pool_s) into Ho x Wo
     int relu_out = 0;
     bool shortcut = false;
     bool gap = false;               // KIND_SINGLE followed by a global average pooling: one tile per image
@@ -80,6 +81,7 @@ struct Choice {
     Variant v{};
     int threads = 0, waves_r1 = 0, waves_r2 = 1, csplit = 1;
     int th = 0, tw = 0, mh = 0, mw = 0, ih = 0, iw = 0, vw2 = 0;
+    int pth = 0, ptw = 0;           // KIND_FUSED2P: tile of the pooled output (th x tw: the stage-2 tile under it)
     int tiles_y = 0, tiles_x = 0;
     int chunk_kg = 0, chunk_kg2[2] = {1, 1};
     int mid_floats = 0, buf_floats = 0, w_off1 = 0;
@@ -145,7 +147,7 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     }
     double t2 = 0;
     long long flops2 = 0;
-    if (b.kind == KIND_FUSED2 || b.kind == KIND_DW) {
+    if (b.kind == KIND_FUSED2 || b.kind == KIND_DW || b.kind == KIND_FUSED2P) {
         const int mf2 = v.mf2, NRT2 = v.nrt2, NPT2 = v.npt2;
         const int npt2 = ceil_div(c.th * c.vw2, mf2);
         const int wg_rt2 = c.waves_r2 * NRT2, wg_pt2 = (nw / c.waves_r2) * NPT2;
@@ -162,6 +164,9 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
                         if (r0 < per && p0 < npt2) s2[w % 4] += wave2;
                     }
                     t2 += *std::max_element(s2, s2 + 4) + 2500.0;       // + epilogue / prologue of the pass
+                    if (b.kind == KIND_FUSED2P)     // pooling of the pass from LDS: two barriers, one float4 window per item
+                        t2 += 700.0 + (double)std::min(wg_rt2, per - rp) * mf2 / 4 * c.pth * c.ptw * b.pool_k * b.pool_k * 8.0 /
+                                          c.threads * 4;
                     barriers += ceil_div(nkg, c.chunk_kg2[ci]);
                     flops2 += 2LL * std::min(wg_rt2, per - rp) * mf2 * std::min(wg_pt2, npt2 - pp) * mf2 * nkg *
                               kc_of(mf2, v.pr) * s.k * s.k;
@@ -179,8 +184,10 @@ static void evaluate(const BlockSpec &b, const xl_plan &pl, Choice &c)
     // memory side: algorithmic bytes at HBM speed plus per-workgroup cache-line traffic at L2 speed
     auto lines = [](int w) { return (double)((w * 4 + 64 + 127) / 128) * 128.0; };
     const double in_wg = (double)b.Cin * c.ih * lines(c.iw) * c.csplit;
-    const double out_ch = (b.kind == KIND_FUSED2 || b.kind == KIND_DW) ? (double)(b.c2[0].cout + (b.n2 > 1 ? b.c2[1].cout : 0)) : b.c1.cout;
-    const double out_wg = out_ch * c.th * lines(c.tw) * (b.shortcut ? 2.0 : 1.0);
+    const bool two_stage = b.kind == KIND_FUSED2 || b.kind == KIND_DW || b.kind == KIND_FUSED2P;
+    const double out_ch = two_stage ? (double)(b.c2[0].cout + (b.n2 > 1 ? b.c2[1].cout : 0)) : b.c1.cout;
+    const double out_wg = b.kind == KIND_FUSED2P ? out_ch * c.pth * lines(c.ptw)
+                                                 : out_ch * c.th * lines(c.tw) * (b.shortcut ? 2.0 : 1.0);
     const double t_mem = (double)b.alg_bytes / 8.0e12 + (in_wg + out_wg) * c.tiles_x * c.tiles_y * b.N / 24.0e12;
     c.cost = std::max(t_mfma, t_mem) + 0.15 * std::min(t_mfma, t_mem);
     // executed multiply-adds: stage 1 covers every row tile once per tile (per cout slice when fused),
@@ -219,7 +226,8 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
             if (b.kind != KIND_SINGLE && std::atoi(only) != v.id) continue;
 #endif
         const bool dw = b.kind == KIND_DW;                  // depthwise stage 1: no matrix-core tiling of layer 1
-        const bool two = b.kind == KIND_FUSED2 || dw;       // stage 2 runs convolutions from the LDS tile
+        const bool pool2 = b.kind == KIND_FUSED2P;          // stage 2 is pooled before it is stored
+        const bool two = b.kind == KIND_FUSED2 || dw || pool2;       // stage 2 runs convolutions from the LDS tile
         if (two) {
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
@@ -252,7 +260,13 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     c.waves_r1 = wr;
                     c.th = th;
                     c.tw = tw;
-                    c.vw2 = tw;
+                    if (pool2) {        // (th, tw) walks the pooled output; the stage-2 tile is what its windows cover
+                        c.pth = th;
+                        c.ptw = tw;
+                        c.th = required_extent(th, b.pool_k, b.pool_s);
+                        c.tw = required_extent(tw, b.pool_k, b.pool_s);
+                    }
+                    c.vw2 = c.tw;
                     if (b.kind == KIND_SINGLE) {
                         c.mh = th;
                         c.mw = tw;
@@ -264,8 +278,8 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                         for (int i = 0; i < b.n2; ++i) P = std::max(P, b.c2[i].pad);
                         for (int i = 0; i < b.n2; ++i) ext = std::max(ext, b.c2[i].k - b.c2[i].pad);
                         const int s2 = b.c2[0].stride;
-                        c.mh = (th - 1) * s2 + ext + P;
-                        c.mw = (tw - 1) * s2 + ext + P;
+                        c.mh = (c.th - 1) * s2 + ext + P;
+                        c.mw = (c.tw - 1) * s2 + ext + P;
                     }
                     if (c.mh * c.mw > px_cap) continue;
                     c.ih = required_extent(c.mh, b.c1.k, b.c1.stride);
@@ -304,17 +318,20 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                             for (int s = 1; s <= 8 && s <= min_nrt; s *= 2) splits.push_back(s);
                         }
                         for (int w2 = 1; w2 <= nw; w2 *= 2) wr2s.push_back(w2);
-                        vws.push_back(tw);
-                        if (tw % 16 && (tw + 15) / 16 * 16 - tw <= 4) vws.push_back((tw + 15) / 16 * 16);
-                        // rows of a multiple of 4 pixels let the epilogue move 4 pixels per access
-                        if (tw % 4 && (tw + 3) / 4 * 4 != vws.back()) vws.push_back((tw + 3) / 4 * 4);
+                        const int tw2 = c.tw;
+                        vws.push_back(tw2);
+                        if (!pool2) {       // (the pooled form writes its tile to LDS pixel by pixel: no padded rows)
+                            if (tw2 % 16 && (tw2 + 15) / 16 * 16 - tw2 <= 4) vws.push_back((tw2 + 15) / 16 * 16);
+                            // rows of a multiple of 4 pixels let the epilogue move 4 pixels per access
+                            if (tw2 % 4 && (tw2 + 3) / 4 * 4 != vws.back()) vws.push_back((tw2 + 3) / 4 * 4);
+                        }
 #ifdef XL_DEV_HOOKS
-                        if (const char *f = std::getenv("XL_FORCE_VW2")) vws.assign(1, std::max(tw, std::atoi(f)));
+                        if (const char *f = std::getenv("XL_FORCE_VW2")) vws.assign(1, std::max(tw2, std::atoi(f)));
 #endif
                     } else {
                         splits.push_back(b.kind == KIND_SINGLE ? ceil_div(nrt1, wg_rt) : 1);
                         wr2s.push_back(1);
-                        vws.push_back(tw);
+                        vws.push_back(c.tw);
                     }
                     for (int cs : splits)
                         for (int w2 : wr2s)
@@ -333,6 +350,12 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                                     for (int i = 0; i < b.n2; ++i)
                                         max_per = std::max(max_per, ceil_div(ceil_div(b.c2[i].cout, v.mf2), cs));
                                     if (w2 > 1 && (w2 / 2) * NRT2 >= max_per) continue;     // idle row waves
+                                    if (pool2) {
+                                        // one pass must cover every pixel of the stage-2 tile, and its result
+                                        // (row tiles of the pass x tile pixels) is pooled from the staging area
+                                        if (ceil_div(c.th * vw, v.mf2) > (nw / w2) * NPT2) continue;
+                                        single = std::max(single, w2 * NRT2 * v.mf2 * c.th * c.tw);
+                                    }
                                     for (int i = 0; i < b.n2; ++i) {
                                         const int nkg2 = ceil_div(b.c2[i].cin, kc_of(v.mf2, v.pr));
                                         const int w2_per_kg = b.c2[i].k * b.c2[i].k * w2 * NRT2 * 64 * frows;
@@ -666,7 +689,7 @@ struct Builder {
             st.packed[3] = packed_index(b.c1b.layer, ch.v.mf1);
         }
         p.coff1 = ys.coff + coff1;
-        const bool two = b.kind == KIND_FUSED2 || b.kind == KIND_DW;
+        const bool two = b.kind == KIND_FUSED2 || b.kind == KIND_DW || b.kind == KIND_FUSED2P;
         p.n2 = two ? b.n2 : 0;
         int P2 = 0;
         for (int i = 0; i < p.n2; ++i) {
@@ -679,6 +702,11 @@ struct Builder {
         p.s2 = two ? b.c2[0].stride : (b.kind == KIND_POOL ? b.pool_s : 1);
         p.P2 = two ? P2 : (b.kind == KIND_POOL ? b.pool_p : 0);
         p.pool_k = b.pool_k;
+        p.ps2 = b.kind == KIND_FUSED2P ? b.pool_s : 1;
+        p.pth = ch.pth;
+        p.ptw = ch.ptw;
+        p.H2 = b.H2;
+        p.W2 = b.W2;
         p.relu_out = b.relu_out;
         p.th = ch.th;
         p.tw = ch.tw;
@@ -707,8 +735,8 @@ struct Builder {
 
     void fill_info(xl_group_info &gi, const BlockSpec &b, const Choice &ch) const
     {
-        gi.tile_h = ch.th;
-        gi.tile_w = ch.tw;
+        gi.tile_h = b.kind == KIND_FUSED2P ? ch.pth : ch.th;
+        gi.tile_w = b.kind == KIND_FUSED2P ? ch.ptw : ch.tw;
         gi.mid_h = b.kind == KIND_SINGLE ? 0 : ch.mh;
         gi.mid_w = b.kind == KIND_SINGLE ? 0 : ch.mw;
         gi.in_h = ch.ih;
@@ -842,7 +870,8 @@ struct Builder {
                 return fail(XL_E_UNSUPPORTED, at + "straight mode: second layer must be a convolution, max pooling or global average pooling");
             }
         } else if (mode == XL_SPLIT) {
-            if (ids.size() != 3 && ids.size() != 4) return fail(XL_E_UNSUPPORTED, at + "split mode is conv -> {conv, conv} [-> concat]");
+            if (ids.size() < 3 || ids.size() > 5)
+                return fail(XL_E_UNSUPPORTED, at + "split mode is conv -> {conv, conv} [-> concat [-> max pooling]]");
             const xl_layer &A = pl.layers[ids[1]], &B = pl.layers[ids[2]];
             if (A.op != XL_CONV || B.op != XL_CONV || A.in[0] != t_mid || B.in[0] != t_mid)
                 return fail(XL_E_GRAPH, at + "split mode: both siblings must be convolutions reading the first layer's output");
@@ -852,12 +881,29 @@ struct Builder {
                 return fail(XL_E_UNSUPPORTED, at + "split siblings must produce the same extent");
             const Storage &sa = pl.storage[A.out], &sb = pl.storage[B.out];
             if (sa.root != sb.root || sa.root == A.out) return fail(XL_E_UNSUPPORTED, at + "split siblings must feed one concat");
-            if (ids.size() == 4) {
+            if (ids.size() >= 4) {
                 const xl_layer &C = pl.layers[ids[3]];
                 if (C.op != XL_CONCAT || C.out != sa.root) return fail(XL_E_GRAPH, at + "fourth layer must be the siblings' concat");
             }
             b.kind = KIND_FUSED2;
             b.n2 = 2;
+            int pooled = -1;
+            if (ids.size() == 5) {
+                // straight after split: the concatenated result is max-pooled before it leaves the chip
+                const xl_layer &Q = pl.layers[ids[4]];
+                if (Q.op != XL_MAXPOOL || Q.in[0] != sa.root) return fail(XL_E_GRAPH, at + "fifth layer must be a max pooling of the concat");
+                if (!only_consumers(sa.root, {ids[4]})) return fail(XL_E_UNSUPPORTED, at + "the concat has a consumer outside the block");
+                if (pl.storage[sa.root].root != sa.root) return fail(XL_E_UNSUPPORTED, at + "the concat is itself a concat operand");
+                const xl_shape &cs = pl.shapes[sa.root], &qs = pl.shapes[Q.out];
+                if (Q.pad != 0 || (qs.h - 1) * Q.stride + Q.k > cs.h || (qs.w - 1) * Q.stride + Q.k > cs.w)
+                    return fail(XL_E_UNSUPPORTED, at + "the fused max pooling must keep every window inside the image (no padding)");
+                b.kind = KIND_FUSED2P;
+                b.pool_k = Q.k;
+                b.pool_s = Q.stride;
+                b.H2 = cs.h;
+                b.W2 = cs.w;
+                pooled = Q.out;
+            }
             // the sibling with the larger filter first (the kernel variants are compiled for that order)
             const bool a_first = A.k > B.k || (A.k == B.k && A.cout >= B.cout);
             const int first = a_first ? ids[1] : ids[2], second = a_first ? ids[2] : ids[1];
@@ -865,7 +911,7 @@ struct Builder {
             conv_spec(second, b.c2[1]);
             b.coff2[0] = pl.storage[pl.layers[first].out].coff - pl.storage[sa.root].coff;
             b.coff2[1] = pl.storage[pl.layers[second].out].coff - pl.storage[sa.root].coff;
-            y_id = sa.root;
+            y_id = pooled >= 0 ? pooled : sa.root;
         } else if (mode == XL_MERGE && ids.size() == 4) {
             // two producers: {conv A, conv B}(x) -> add -> conv C   (paper Fig. 4c / Table 1 c.1)
             const xl_layer &B = pl.layers[ids[1]], &S = pl.layers[ids[2]], &C = pl.layers[ids[3]];
@@ -905,7 +951,7 @@ struct Builder {
         } else {
             return fail(XL_E_UNSUPPORTED, at + "unknown fusion mode");
         }
-        if (b.kind == KIND_FUSED2 || b.kind == KIND_DW) {
+        if (b.kind == KIND_FUSED2 || b.kind == KIND_DW || b.kind == KIND_FUSED2P) {
             for (int i = 0; i < b.n2; ++i)
                 if (b.c2[i].cin != b.c1.cout) return fail(XL_E_SHAPE, at + "channel mismatch inside the block");
         }

@@ -34,7 +34,7 @@ struct ConvW {
     int nrt;                // row tiles = ceil(cout / MF)
 };
 
-enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3, KIND_POOLS = 4 };
+enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3, KIND_POOLS = 4, KIND_FUSED2P = 5 };
 
 // Kernel argument of every convolution-stage kernel.
 //   KIND_SINGLE: stage 1 writes its result to global memory (one layer, the
@@ -43,6 +43,9 @@ enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3, KIND_P
 //                LDS; stage 2 runs one or two sibling convolutions from that
 //                tile (straight / split), optionally adding a shortcut tensor
 //                in the epilogue (merge).
+//   KIND_FUSED2P: KIND_FUSED2 (without shortcut) followed by a max pooling of the block's output: every
+//                stage-2 pass leaves its result in an LDS tile, which is pooled before it goes to memory.
+//                th x tw is then the stage-2 tile a pth x ptw tile of the pooled output depends on.
 //   KIND_POOL:   stage 1 as above; stage 2 is a max pooling from the LDS tile.
 //   KIND_POOLS:  KIND_POOL for a first layer whose reduction fits one chunk, as a stream: resident
 //                workgroups walk the tiles and request the next tile's input ahead (pool_stream_kernel).
@@ -67,7 +70,10 @@ struct BlockParams {
     int coff2[2];
     int s2;                 // stride shared by the stage-2 windows
     int P2;                 // halo of the LDS tile on the top/left = largest stage-2 pad
-    int pool_k;             // KIND_POOL: window size (stride s2, pad P2)
+    int pool_k;             // KIND_POOL: window size (stride s2, pad P2); KIND_FUSED2P: window size (stride ps2, no padding)
+    int ps2;                // KIND_FUSED2P: stride of the pooling after stage 2
+    int pth, ptw;           // KIND_FUSED2P: tile of the pooled output
+    int H2, W2;             // KIND_FUSED2P: extent of the stage-2 output (before pooling)
     int relu_out;           // applied after the shortcut add (merge)
     int gap;                // KIND_SINGLE: the tile is the whole image and y receives the mean over its pixels
     int th, tw;             // output tile of the block
@@ -153,6 +159,15 @@ struct Variant {
     X(16, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 0)          \
     X(17, KIND_FUSED2, 16, 1, 1, 1, 16, 1, 2, 3, 1, 0, 0)          \
     X(18, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0, 0)          \
+    /* split -> max pooling of the concatenated result */  \
+    X(110, KIND_FUSED2P, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)        \
+    X(111, KIND_FUSED2P, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 0)        \
+    X(112, KIND_FUSED2P, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 0)        \
+    X(113, KIND_FUSED2P, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 0)        \
+    X(114, KIND_FUSED2P, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0, 0)        \
+    X(115, KIND_FUSED2P, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 4)        \
+    X(116, KIND_FUSED2P, 16, 1, 1, 3, 16, 1, 7, 3, 1, 0, 4)        \
+    X(117, KIND_FUSED2P, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)        \
     /* straight conv -> conv, and merge (with shortcut) */ \
     X(19, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0, 0)          \
     X(20, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1, 0)          \

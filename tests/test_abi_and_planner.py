@@ -218,3 +218,17 @@ def test_split_bf16_error_model():
     y3 = xh.astype(np.float64) @ wh + xh.astype(np.float64) @ wl + xl.astype(np.float64) @ wh
     y = x.astype(np.float64) @ w
     assert np.abs(y3 - y).max() < 2e-5      # a fifth of the absolute part of the tolerance
+
+
+def test_split_block_followed_by_max_pooling_is_one_launch():
+    wl = W.split_fire_pool(n=2, cin=32, hw=27, s=16, e=32)
+    p = B.Plan(wl)
+    assert p.num_groups == 1 and p.num_launches(True) == 1 and p.num_launches(False) == 4
+    q = p.query(0)
+    assert q["nlayers"] == 5
+    assert q["stores_fused"] == 2 * 64 * 13 * 13                 # only the pooled tensor is written
+    assert q["stores_unfused"] == 2 * (16 + 64) * 27 * 27 + 2 * 64 * 13 * 13
+    assert q["mid_h"] == 2 * (q["tile_h"] - 1) + 3 + 2           # pooled tile -> 3x3/2 windows -> 3x3 conv halo
+    # a padded pooling would need -inf padding inside the block: not fused
+    with pytest.raises(B.XlError):
+        B.Plan(W.split_fire_pool(n=1, hw=27, pp=1))

@@ -219,6 +219,18 @@ def test_conv_then_max_pooling_shapes(wl):
             check(s.output(fused), ref, f"{wl.name} tune={tune} fused={fused}")
 
 
+@pytest.mark.parametrize("wl", [
+    W.split_fire_pool(),                                        # 27 -> 13, the shape between fire modules
+    W.split_fire_pool(n=1, cin=40, hw=15, s=16, e=64),          # 15 -> 7
+    W.split_fire_pool(n=2, cin=24, hw=14, s=8, e=16),           # last row and column feed no window
+    W.split_fire_pool(n=1, cin=72, hw=12, s=48, e=96, pk=2, ps=2),
+    W.split_fire_pool(n=3, cin=64, hw=55, s=16, e=64),          # config 5's fire3 + pool
+])
+def test_split_block_with_max_pooling(wl):
+    run_both(wl)
+    run_both(wl, tune=True)
+
+
 def test_degenerate_shapes():
     """1x1 images, single channels, tiles larger than the image, odd sizes under stride 2."""
     for wl in (W.single_conv(1, 1, 1, 1, 1, 1),

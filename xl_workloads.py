@@ -132,13 +132,16 @@ class _Builder:
         """Close a fusion block made of layers[first_layer:]."""
         self.groups.append(Group(mode, tuple(range(first_layer, len(self.layers)))))
 
-    def fire(self, x: int, s: int, e: int, name: str) -> int:
-        """SqueezeNet fire module = one split-mode block (paper section 4.2: 8 mode-b blocks)."""
+    def fire(self, x: int, s: int, e: int, name: str, pool=None) -> int:
+        """SqueezeNet fire module = one split-mode block (paper section 4.2: 8 mode-b blocks).
+        pool = (k, stride, name): a max pooling of the module's output joins the block."""
         first = len(self.layers)
         sq = self.conv(x, s, 1, bias=True, relu=True, name=name + ".squeeze")
         e1 = self.conv(sq, e, 1, bias=True, relu=True, name=name + ".expand1x1")
         e3 = self.conv(sq, e, 3, pad=1, bias=True, relu=True, name=name + ".expand3x3")
         y = self.concat(e1, e3, name=name + ".concat")
+        if pool is not None:
+            y = self.maxpool(y, pool[0], pool[1], pool[3] if len(pool) > 3 else 0, name=pool[2])
         self.group("split", first)
         return y
 
@@ -176,6 +179,14 @@ def split_fire(n: int = 16, cin: int = 96, hw: int = 55, s: int = 16, e: int = 6
     return b.done(t, "relu_normal", 1003)
 
 
+def split_fire_pool(n: int = 2, cin: int = 32, hw: int = 27, s: int = 16, e: int = 32, pk: int = 3, ps: int = 2,
+                    seed: int = 12, pp: int = 0) -> Workload:
+    """A fire module whose concatenated output is max-pooled inside the block (straight after split)."""
+    b = _Builder(f"firepool_{cin}x{hw}_{s}_{e}_p{pk}s{ps}", n, cin, hw, hw)
+    t = b.fire(0, s, e, "fire", pool=(pk, ps, "pool", pp))
+    return b.done(t, "relu_normal", seed)
+
+
 def merge_residual(n: int = 32, c: int = 64, hw: int = 56) -> Workload:
     """Config 4: residual basic block, identity shortcut (merge mode)."""
     b = _Builder("cfg4_merge_residual", n, c, hw, hw)
@@ -187,8 +198,9 @@ def merge_residual(n: int = 32, c: int = 64, hw: int = 56) -> Workload:
 
 
 def squeezenet11(n: int = 64, hw: int = 224, classes: int = 1000, fuse_stem: bool = True,
-                 fuse_head: bool = True) -> Workload:
-    """Config 5: SqueezeNet-v1.1-shaped network; 8 split-mode fire blocks (paper section 4.2)."""
+                 fuse_head: bool = True, fuse_pools: bool = True) -> Workload:
+    """Config 5: SqueezeNet-v1.1-shaped network; 8 split-mode fire blocks (paper section 4.2).
+    fuse_pools: the two max poolings between fire modules join the fire block before them."""
     b = _Builder("cfg5_squeezenet11", n, 3, hw, hw)
     first = len(b.layers)
     t = b.conv(0, 64, 3, stride=2, pad=0, bias=True, relu=True, name="conv1")
@@ -196,11 +208,17 @@ def squeezenet11(n: int = 64, hw: int = 224, classes: int = 1000, fuse_stem: boo
     if fuse_stem:
         b.group("straight", first)
     t = b.fire(t, 16, 64, "fire2")
-    t = b.fire(t, 16, 64, "fire3")
-    t = b.maxpool(t, 3, 2, 0, name="pool2")
+    if fuse_pools:
+        t = b.fire(t, 16, 64, "fire3", pool=(3, 2, "pool2"))
+    else:
+        t = b.fire(t, 16, 64, "fire3")
+        t = b.maxpool(t, 3, 2, 0, name="pool2")
     t = b.fire(t, 32, 128, "fire4")
-    t = b.fire(t, 32, 128, "fire5")
-    t = b.maxpool(t, 3, 2, 0, name="pool3")
+    if fuse_pools:
+        t = b.fire(t, 32, 128, "fire5", pool=(3, 2, "pool3"))
+    else:
+        t = b.fire(t, 32, 128, "fire5")
+        t = b.maxpool(t, 3, 2, 0, name="pool3")
     t = b.fire(t, 48, 192, "fire6")
     t = b.fire(t, 48, 192, "fire7")
     t = b.fire(t, 64, 256, "fire8")
