@@ -168,6 +168,9 @@ struct Variant {
     X(115, KIND_FUSED2P, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 4)        \
     X(116, KIND_FUSED2P, 16, 1, 1, 3, 16, 1, 7, 3, 1, 0, 4)        \
     X(117, KIND_FUSED2P, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)        \
+    X(118, KIND_FUSED2P, 16, 1, 2, 3, 32, 2, 1, 3, 1, 0, 0)        \
+    X(119, KIND_FUSED2P, 32, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)        \
+    X(120, KIND_FUSED2P, 16, 1, 1, 4, 32, 2, 1, 3, 1, 0, 0)        \
     /* straight conv -> conv, and merge (with shortcut) */ \
     X(19, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0, 0)          \
     X(20, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1, 0)          \
@@ -244,6 +247,11 @@ struct Variant {
     X(212, KIND_FUSED2, 16, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)         \
     X(233, KIND_FUSED2, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 0)         \
     X(235, KIND_FUSED2, 16, 1, 3, 2, 32, 2, 1, 3, 1, 0, 0)         \
+    /* split -> max pooling */                                     \
+    X(250, KIND_FUSED2P, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)        \
+    X(251, KIND_FUSED2P, 16, 1, 1, 3, 32, 2, 1, 3, 1, 0, 0)        \
+    X(252, KIND_FUSED2P, 16, 1, 2, 3, 32, 2, 1, 3, 1, 0, 0)        \
+    X(253, KIND_FUSED2P, 32, 1, 1, 2, 32, 2, 1, 3, 1, 0, 0)        \
     /* straight and merge */                                       \
     X(220, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 0, 0)         \
     X(221, KIND_FUSED2, 32, 3, 2, 1, 32, 2, 1, 3, 0, 1, 0)         \
