@@ -269,7 +269,10 @@ struct Variant {
 
 const std::vector<Variant> &variants();
 
-constexpr int STAGE_UNITS = 1;      // input units (4 channels x 4 pixels) each thread stages per chunk
+#ifndef XL_STAGE_UNITS
+#define XL_STAGE_UNITS 1
+#endif
+constexpr int STAGE_UNITS = XL_STAGE_UNITS;      // input units (4 channels x 4 pixels) each thread stages per chunk
 constexpr int MAX_W_CHUNK_BYTES = 52 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
 constexpr int PLANAR_SLOTS = 8;     // LDS-direct loads per wave and chunk of a planar input chunk
 constexpr int MAX_THREADS = 512;
