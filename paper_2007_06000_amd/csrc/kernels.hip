@@ -30,7 +30,13 @@ namespace xl {
 
 // Development aid: per-workgroup phase timestamps (only in builds with -DXL_PHASE_TIMING).
 #ifdef XL_PHASE_TIMING
+#ifdef XL_TU_B3     // the reader below sees the fp32 translation unit's copy only
+static
+#endif
 __device__ unsigned long long g_phase[16 * 8192];
+#ifdef XL_TU_B3
+static
+#endif
 __device__ unsigned long long g_wtrace[8 * 8 * 16 * 4];     // [block][wave][chunk][stamp], stage-1 pass
 #define XL_PHASE(L, i)                                                        \
     do {                                                                      \
