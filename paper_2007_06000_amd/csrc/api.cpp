@@ -307,7 +307,7 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
                 if (rc != XL_OK) break;
                 continue;
             }
-            // first a quick look at every candidate, then the few fastest again with more repetitions
+            // first a quick look at every candidate (best of 3), then the 6 fastest again with more repetitions
             auto time_alt = [&](size_t a, int n, float &t_min) {
                 t_min = 1e30f;
                 for (int r = 0; r < n && rc == XL_OK; ++r) {
@@ -329,7 +329,7 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
                 rc = launch_step(plan, st.alts[a], tensors, ws, s);         // warm-up (code, filters in L2)
                 if (rc != XL_OK) break;
                 float t;
-                time_alt(a, 2, t);
+                time_alt(a, 3, t);
                 quick.push_back({t, (int)a});
 #ifdef XL_DEV_HOOKS     // development builds only: one line per candidate
                 if (std::getenv("XL_TUNE_LOG")) {
@@ -344,7 +344,7 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
             float best_ms = 1e30f;
             if (rc == XL_OK) {
                 std::sort(quick.begin(), quick.end());
-                for (size_t i = 0; i < quick.size() && i < 4 && rc == XL_OK; ++i) {
+                for (size_t i = 0; i < quick.size() && i < 6 && rc == XL_OK; ++i) {
                     float t;
                     time_alt((size_t)quick[i].second, reps, t);
                     if (t < best_ms) {
