@@ -132,6 +132,8 @@ struct Variant {
     X(72, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 4)         \
     X(73, KIND_FUSED2, 32, 1, 1, 1, 16, 1, 2, 3, 1, 0, 2)         \
     X(74, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0, 4)         \
+    X(84, KIND_FUSED2, 16, 1, 1, 2, 32, 1, 1, 5, 0, 0, 4)         \
+    X(85, KIND_FUSED2, 16, 1, 1, 2, 16, 1, 2, 5, 0, 0, 4)         \
     X(75, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 1, 0, 0, 2)           \
     /* split blocks with 16-pixel stage-2 tiles, 7 per wave (finer padding of 14-wide tiles) */ \
     X(76, KIND_FUSED2, 16, 1, 1, 2, 16, 1, 7, 3, 1, 0, 4)         \
