@@ -175,6 +175,7 @@ def test_pointwise_first_layers_with_whole_k_steps_of_channels(wl):
 ], ids=lambda w: w.name)
 def test_five_by_five_filters(wl):
     run_both(wl)
+    run_both(wl, tune=True)     # the tuner also tries the variants that stage a pointwise first layer's input as planes
 
 
 @pytest.mark.parametrize("wl", [
