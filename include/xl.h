@@ -121,8 +121,8 @@ typedef struct xl_options {
                                is hi*hi + hi*lo + lo*hi on the bf16 matrix cores, accumulated in
                                fp32 (error at most 3 * 2^-16 of |a||b| per product, about 4e-6 rms; operands must be
                                finite and below 2^127 in magnitude).  Tensors in memory stay fp32.
-                               Blocks no split-bf16 kernel covers (depthwise first layers, the
-                               two-producer merge form) run the fp32 kernels. */
+                               A depthwise first layer stays on the vector ALU in fp32; xl_tune may
+                               keep an fp32 kernel for a block where it measures faster. */
 } xl_options;
 #define XL_PRECISION_FP32   0
 #define XL_PRECISION_BF16X3 1

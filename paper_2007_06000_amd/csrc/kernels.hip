@@ -844,7 +844,7 @@ __device__ __forceinline__ void store_gap(const typename MM<MF>::Acc (&acc)[NRT]
 // must see outside the image: 0 for a convolution, -FLT_MAX for max pooling.
 // With `add` the result is added to what the tile already holds (the first of two producer layers
 // of a merge block, written by this same lane) and `relu_sum` is applied to the sum.
-// PR = 1: the tile is written as split-bf16 planes (see conv_accum_b3); no accumulation into it.
+// PR = 1: the tile is written as split-bf16 planes (see conv_accum_b3); `add` reads hi + lo back (exact in fp32).
 template <int MF, int NRT, int NPT, int PR = 0>
 __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
                                           const ConvW &c, float *mid, int my0, int mx0, int rt0, int rt_end, int pt0,
@@ -876,7 +876,18 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
                 float *dst = PR ? mid + (gr & ~1) * P.mid_gstride + pidx * 4 + (gr & 1) * 2
                                 : mid + gr * P.mid_gstride + pidx * 4;
                 f32x4 old = {0.f, 0.f, 0.f, 0.f};
-                if (!PR && add && pidx < npx) old = *(const f32x4 *)dst;
+                if (add && pidx < npx) {
+                    if constexpr (PR) {
+                        const uint2 oh = *(const uint2 *)dst, ol = *(const uint2 *)(dst + P.mid_gstride);
+                        auto up = [](unsigned bits) { return __builtin_bit_cast(float, bits); };
+                        old[0] = up(oh.x << 16) + up(ol.x << 16);
+                        old[1] = up(oh.x & 0xffff0000u) + up(ol.x & 0xffff0000u);
+                        old[2] = up(oh.y << 16) + up(ol.y << 16);
+                        old[3] = up(oh.y & 0xffff0000u) + up(ol.y & 0xffff0000u);
+                    } else {
+                        old = *(const f32x4 *)dst;
+                    }
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
@@ -957,6 +968,7 @@ __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT
 // the LDS tile the pointwise stage reads -- zero where the intermediate lies outside the image.
 // Filter: [channel group][tap] float4, scale / shift: [channel group][2] float4 (re-laid out once).
 // ----------------------------------------------------------------------------
+template <int PR>
 __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mid, float *xs, const float *ximg,
                                                  unsigned long long x_bytes, int my0, int mx0, int iy0, int ix0)
 {
@@ -1011,7 +1023,16 @@ __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mi
                 o[j] = (inside && g * 4 + j < P.Cin) ? t : 0.f;
             }
         }
-        *(f32x4 *)(mid + g * P.mid_gstride + pidx * 4) = o;
+        if constexpr (PR) {     // split-bf16 planes for the pointwise stage (see conv_accum_b3)
+            uint2 hi, lo;
+            split_bf16(o[0], o[1], hi.x, lo.x);
+            split_bf16(o[2], o[3], hi.y, lo.y);
+            float *dst = mid + (g & ~1) * P.mid_gstride + pidx * 4 + (g & 1) * 2;
+            *(uint2 *)dst = hi;
+            *(uint2 *)(dst + P.mid_gstride) = lo;
+        } else {
+            *(f32x4 *)(mid + g * P.mid_gstride + pidx * 4) = o;
+        }
     }
 }
 
@@ -1021,7 +1042,7 @@ __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mi
 template <int KIND, int MF1, int K1, int NRT1, int NPT1, int MF2, int NRT2, int NPT2, int K2A, int K2B, bool SC, int PX1, int PR = 0>
 __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_WAVES)) block_kernel(const BlockParams P)
 {
-    static_assert(PR == 0 || (KIND != KIND_DW && PX1 == 0), "split-bf16 operands: matrix-core first layers staged through registers");
+    static_assert(PR == 0 || PX1 == 0, "split-bf16 operands are staged through registers");
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int L = logical_block();
     if (L >= P.nblocks) return;
@@ -1051,7 +1072,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
 
     if constexpr (KIND == KIND_DW) {
         // ---- S1/S2 for a depthwise first layer: vector ALU from a staged input tile into the LDS tile
-        depthwise_stage1(P, mid, buf, ximg, (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, my0, mx0, iy0, ix0);
+        depthwise_stage1<PR>(P, mid, buf, ximg, (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, my0, mx0, iy0, ix0);
     } else {
     // ---- S1: layer 1 over the (halo-extended) tile
     const int npx1 = P.mh * P.mw;
@@ -1102,7 +1123,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
         // ---- S2: epilogue of layer 1 into the LDS tile
         store_mid<MF1, NRT1, NPT1, (KIND == KIND_POOL ? 0 : PR)>(acc, P, P.c1, mid, my0, mx0, rt0, rt_end1, pt0, npx1,
                                                                  KIND == KIND_POOL ? -FLT_MAX : 0.f);
-        if constexpr (KIND == KIND_FUSED2 && K1 == 1 && K2A == 1 && K2B == 0 && !SC && !PR) {
+        if constexpr (KIND == KIND_FUSED2 && K1 == 1 && K2A == 1 && K2B == 0 && !SC) {
             if (P.n1 == 2) {
                 // second producer of a merge block (paper Fig. 4c): same input, same geometry, its own
                 // filter; its result is added to the first one's in the LDS tile
@@ -1110,10 +1131,10 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                 for (int p = 0; p < NPT1; ++p)
 #pragma unroll
                     for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
-                conv_pass<MF1, K1, NRT1, NPT1, true, PX1>(acc, P, P.c1b, g1, nullptr, off1, buf, ximg,
-                                                     (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
-                store_mid<MF1, NRT1, NPT1>(acc, P, P.c1b, mid, my0, mx0, rt0, rt_end1, pt0, npx1, 0.f, true,
-                                           P.relu_mid != 0);
+                conv_pass<MF1, K1, NRT1, NPT1, true, PX1, PR>(acc, P, P.c1b, g1, nullptr, off1, buf, ximg,
+                                                         (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
+                store_mid<MF1, NRT1, NPT1, PR>(acc, P, P.c1b, mid, my0, mx0, rt0, rt_end1, pt0, npx1, 0.f, true,
+                                               P.relu_mid != 0);
             }
         }
     }

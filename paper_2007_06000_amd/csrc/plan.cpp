@@ -231,7 +231,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
         if (two) {
             if (v.k2a != b.c2[0].k || v.k2b != (b.n2 > 1 ? b.c2[1].k : 0) || v.sc != (b.shortcut ? 1 : 0)) continue;
         }
-        if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0 && v.pr == 0)) continue;
+        if (b.n1 == 2 && !(v.kind == KIND_FUSED2 && v.k1 == 1 && v.k2a == 1 && v.k2b == 0 && v.sc == 0)) continue;
         // variants whose stage 1 reads planar input chunks: a 1x1 filter, stride 1, no padding, whole
         // K steps of channels; the tile's ih rows of iws floats must fit px * 64 floats per channel
         // px1 < 0: the first layer's channels are packed two per channel slot (-px1 slots used): 32-wide
@@ -573,6 +573,7 @@ struct Builder {
 
     int packed_index(int layer, int mf, bool pairs = false, int pr = 0)
     {
+        if (mf == 0) pr = 0;        // depthwise tables have one form
         for (size_t i = 0; i < pl.packed.size(); ++i)
             if (pl.packed[i].layer == layer && pl.packed[i].mf == mf && pl.packed[i].pairs == pairs && pl.packed[i].pr == pr)
                 return (int)i;
@@ -686,7 +687,7 @@ struct Builder {
         if (b.n1 == 2) {
             fill(p.c1b, b.c1b, ch.v.mf1);
             st.conv_layer[3] = b.c1b.layer;
-            st.packed[3] = packed_index(b.c1b.layer, ch.v.mf1);
+            st.packed[3] = packed_index(b.c1b.layer, ch.v.mf1, false, ch.v.pr);
         }
         p.coff1 = ys.coff + coff1;
         const bool two = b.kind == KIND_FUSED2 || b.kind == KIND_DW || b.kind == KIND_FUSED2P;

@@ -265,6 +265,12 @@ struct Variant {
     X(229, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 1, 0, 1, 0)         \
     X(230, KIND_FUSED2, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0, 0)         \
     X(231, KIND_FUSED2, 16, 1, 1, 1, 32, 1, 1, 5, 0, 0, 0)         \
+    /* two producers -> add -> consumer, all 1x1 */                \
+    X(254, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 1, 0, 0, 0)         \
+    /* depthwise (vector ALU, fp32) -> convolution on split-bf16 operands */ \
+    X(255, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 1, 0, 0, 0)             \
+    X(256, KIND_DW, 32, 3, 1, 1, 32, 1, 1, 1, 0, 0, 0)             \
+    X(257, KIND_DW, 32, 3, 1, 1, 32, 2, 1, 3, 0, 0, 0)             \
     /* conv -> maxpool (the LDS tile stays fp32) */                \
     X(240, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
     X(241, KIND_POOL, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)

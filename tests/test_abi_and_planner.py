@@ -180,9 +180,9 @@ def test_precision_option_selects_split_bf16_kernels_where_they_exist():
     assert q["precision"] == 0
     q = B.Plan(W.config(4), precision=1).query(0)
     assert q["precision"] == 1 and q["chunk_channels"] % 16 == 0     # a K step covers 16 or 32 channels
-    # no split-bf16 kernel for a depthwise first layer or the two-producer merge form: fp32 kernels
-    assert B.Plan(W.depthwise_pointwise(1, 16, 80, 80, 16), precision=1).query(0)["precision"] == 0
-    assert B.Plan(W.merge_two_producers(1), precision=1).query(0)["precision"] == 0
+    # every block kind has split-bf16 variants (a depthwise first layer itself stays on the vector ALU in fp32)
+    for wl in (W.depthwise_pointwise(1, 16, 80, 80, 16), W.merge_two_producers(1), W.split_fire_pool(), W.config(2), W.config(3)):
+        assert B.Plan(wl, precision=1).query(0)["precision"] == 1
     with pytest.raises(B.XlError):
         B.Plan(W.config(4), precision=2)
 
