@@ -33,6 +33,11 @@ def test_config5_full_size():
     run_split(W.config(5))
 
 
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_full_size_configs_with_tuned_plans(cfg):
+    run_split(W.config(cfg), expect_split=False, tune=True)
+
+
 @pytest.mark.parametrize("cfg,kw", [(3, {}), (4, {"n": 2, "hw": 28}), (5, {"n": 2, "hw": 63, "classes": 40})])
 def test_tuned_plans(cfg, kw):
     run_split(W.config(cfg, **kw), expect_split=False, tune=True)
