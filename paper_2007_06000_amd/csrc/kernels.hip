@@ -1327,18 +1327,32 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
     int xdst = 0, xgrp = 0, xs = 0;
     f32x4 xst[4];
     __amdgpu_buffer_rsrc_t xr;
+    // Which unit a lane owns depends on the tile only through xs (columns of padding left of the image:
+    // tiles of the first column); the two decompositions are made once, not per tile.
+    struct UnitPos { int gr, r, q, x_units; };
+    auto unit_pos = [&](int xs_) {
+        const int qpr = (P.iw - xs_ + 3) >> 2;
+        const int upg = P.ih * qpr;
+        UnitPos up;
+        up.x_units = P.chunk_kg * M1::GPS * upg;             // the one chunk: every K step of the layer
+        up.gr = tid / upg;
+        const int rem = tid - up.gr * upg;
+        up.r = rem / qpr;
+        up.q = rem - up.r * qpr;
+        return up;
+    };
+    const int xs_edge = max(0, (P.P2 * P.c1.stride) + P.c1.pad);       // xs of the tiles with tx = 0
+    const UnitPos up_in = unit_pos(0), up_edge = unit_pos(xs_edge);
     auto request = [&](int L) {         // descriptor, per-lane unit and loads for tile L
         const int tile = L % tiles, n = L / tiles;
         const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
         const int iy0 = (ty * P.th * P.s2 - P.P2) * P.c1.stride - P.c1.pad;
         const int ix0 = (tx * P.tw * P.s2 - P.P2) * P.c1.stride - P.c1.pad;
         xs = max(0, -ix0);
-        const int qpr = (P.iw - xs + 3) >> 2;
-        const int upg = P.ih * qpr;
-        const int x_units = P.chunk_kg * M1::GPS * upg;      // the one chunk: every K step of the layer
+        const UnitPos up = xs == 0 ? up_in : (xs == xs_edge ? up_edge : unit_pos(xs));
+        const int x_units = up.x_units;
         const int u = tid;
-        const int gr = u / upg, rem = u - gr * upg;
-        const int r = rem / qpr, q = rem - r * qpr;
+        const int gr = up.gr, r = up.r, q = up.q;
         const int cc = xs + 4 * q;
         const int gy = iy0 + r, gx = ix0 + cc;
         const bool rowok = gy >= 0 && gy < P.H;
@@ -1379,6 +1393,32 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
         }
     };
 
+    // ---- what the epilogue and the pooling need that does not change from tile to tile
+    const int sub1 = lane / MF1, col1 = lane % MF1;
+    // scale / shift stay in registers across tiles when that fits the 128 registers of this kernel
+    constexpr bool KEEP_AFFINE = NRT1 == 1 && (JN < 4 || MF1 == 16);
+    f32x4 fa[NRT1][M1::NQ], fb[NRT1][M1::NQ];
+    if constexpr (KEEP_AFFINE) {
+#pragma unroll
+        for (int r = 0; r < NRT1; ++r)
+#pragma unroll
+            for (int q = 0; q < M1::NQ; ++q) load_affine<MF1>(P.c1, min(rt0 + r, P.c1.nrt - 1), q, fa[r][q], fb[r][q]);
+    }
+    int e_my[NPT1], e_mx[NPT1], e_pidx[NPT1];
+#pragma unroll
+    for (int p = 0; p < NPT1; ++p) {
+        e_pidx[p] = (pt0 + p) * MF1 + col1;
+        e_my[p] = e_pidx[p] / P.mw;
+        e_mx[p] = e_pidx[p] - e_my[p] * P.mw;
+    }
+    const int ngroups = (P.c1.cout + 3) >> 2;
+    const int npo = P.th * P.tw;
+    const size_t oplane = (size_t)P.Ho * P.Wo;
+    // first pooling item of this thread (the usual case: no more items than threads)
+    const int i_gq = tid / npo, i_pidx = tid - i_gq * npo;
+    const int i_oy = i_pidx / P.tw, i_ox = i_pidx - i_oy * P.tw;
+    const float *i_sp = mid + i_gq * P.mid_gstride + ((i_oy * P.s2) * P.mw + i_ox * P.s2) * 4;
+
     const int first = logical_block();
     if (first >= P.nblocks) return;     // uniform per workgroup
     request(first);
@@ -1398,18 +1438,51 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
             for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
         if (active)
             conv_accum<MF1, K1, NRT1, NPT1, 0, JN>(acc, xbuf, off1, P.iws, P.in_gstride, wbuf, rloc, wg_rt, P.c1.nkg);
-        store_mid<MF1, NRT1, NPT1>(acc, P, P.c1, mid, my0, mx0, rt0, rt_end1, pt0, npx1, -FLT_MAX);
+        // epilogue into the LDS tile (store_mid with the tile-independent parts taken from above)
+        if constexpr (!KEEP_AFFINE) {
+            asm volatile("" ::: "memory");      // not before the K loop
+#pragma unroll
+            for (int r = 0; r < NRT1; ++r)
+#pragma unroll
+                for (int q = 0; q < M1::NQ; ++q) load_affine<MF1>(P.c1, min(rt0 + r, P.c1.nrt - 1), q, fa[r][q], fb[r][q]);
+        }
+#pragma unroll
+        for (int p = 0; p < NPT1; ++p) {
+            const int gy = my0 + e_my[p], gx = mx0 + e_mx[p];
+            const bool inside = gy >= 0 && gy < P.H1 && gx >= 0 && gx < P.W1;
+#pragma unroll
+            for (int r = 0; r < NRT1; ++r) {
+                if (rt0 + r >= rt_end1) continue;
+#pragma unroll
+                for (int q = 0; q < M1::NQ; ++q) {
+                    const int cb = (rt0 + r) * MF1 + M1::quad_row(q, sub1);
+                    f32x4 v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
+                        if (P.c1.relu) z = fmaxf(z, 0.f);
+                        if (!inside) z = -FLT_MAX;
+                        if (cb + i >= P.c1.cout) z = 0.f;
+                        v[i] = z;
+                    }
+                    if (e_pidx[p] < npx1) *(f32x4 *)(mid + (cb >> 2) * P.mid_gstride + e_pidx[p] * 4) = v;
+                }
+            }
+        }
         __syncthreads();
         // pooling from the LDS tile; one float4 (4 channels of one pixel) per item
-        const int ngroups = (P.c1.cout + 3) >> 2;
-        const int npo = P.th * P.tw;
-        const size_t oplane = (size_t)P.Ho * P.Wo;
         for (int it = tid; it < ngroups * npo; it += nthreads) {
-            const int gq = it / npo, pidx = it - gq * npo;
-            const int oy = pidx / P.tw, ox = pidx - oy * P.tw;
+            int gq = i_gq, oy = i_oy, ox = i_ox;
+            const float *sp = i_sp;
+            if (it != tid) {
+                gq = it / npo;
+                const int pidx = it - gq * npo;
+                oy = pidx / P.tw;
+                ox = pidx - oy * P.tw;
+                sp = mid + gq * P.mid_gstride + ((oy * P.s2) * P.mw + ox * P.s2) * 4;
+            }
             const int gy = oy0 + oy, gx = ox0 + ox;
             if (gy >= P.Ho || gx >= P.Wo) continue;
-            const float *sp = mid + gq * P.mid_gstride + ((oy * P.s2) * P.mw + ox * P.s2) * 4;
             f32x4 m = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
             for (int u = 0; u < P.pool_k; ++u)
                 for (int v = 0; v < P.pool_k; ++v) {
