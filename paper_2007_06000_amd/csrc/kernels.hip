@@ -1471,6 +1471,7 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
         }
         __syncthreads();
         // pooling from the LDS tile; one float4 (4 channels of one pixel) per item
+        const __amdgpu_buffer_rsrc_t yr = make_rsrc(P.y + (size_t)n * P.Cy * oplane, (unsigned long long)(P.N - n) * P.Cy * oplane * 4ull);
         for (int it = tid; it < ngroups * npo; it += nthreads) {
             int gq = i_gq, oy = i_oy, ox = i_ox;
             const float *sp = i_sp;
@@ -1490,10 +1491,13 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
 #pragma unroll
                     for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
                 }
+            // 32-bit offsets from the image's first element (per-image element counts fit 30 bits: planner)
+            const unsigned vo = (unsigned)(((P.coff1 + gq * 4) * (int)oplane + gy * P.Wo + gx) * 4);
+            const float mv[4] = {m[0], m[1], m[2], m[3]};     // (a bit cast of a vector element picks element 0)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int co = gq * 4 + j;
-                if (co < P.c1.cout) P.y[((size_t)n * P.Cy + P.coff1 + co) * oplane + (size_t)gy * P.Wo + gx] = m[j];
+                if (gq * 4 + j < P.c1.cout)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, mv[j]), yr, vo, j * (int)oplane * 4, 0);
             }
         }
     }
