@@ -122,6 +122,14 @@ __device__ __forceinline__ int logical_block()
     return (blockIdx.x & 7) * per + (blockIdx.x >> 3);
 }
 
+// x / d for 0 <= x < 65536 by the multiplier the planner made for d (2^32 / d + 1; 0 stands for d = 1):
+// a division by a run-time value costs some 30 vector instructions, and the epilogues need one per
+// pixel tile.
+__device__ __forceinline__ int fdiv(int x, unsigned magic)
+{
+    return magic ? (int)__umulhi((unsigned)x, magic) : x;
+}
+
 // Buffer descriptor over [p, p + bytes) (clamped to 4 GB), raw dword addressing.  Address and size
 // are wave-uniform by construction; reading them through the first lane tells the compiler so --
 // otherwise every buffer access gets a loop over the distinct descriptor values of the wave.
@@ -638,7 +646,7 @@ __device__ __forceinline__ void quad_transpose(float (&v)[4])
 template <int MF, int NRT, int NPT, bool HAS_SC>
 __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
                                              const ConvW &c, int coff, int n, int oy0, int ox0, int th, int tw, int vw,
-                                             int rt0, int rt_end, int pt0, int relu_out)
+                                             int rt0, int rt_end, int pt0, int relu_out, unsigned rcp_vw)
 {
     typedef MM<MF> M;
     typedef unsigned u32x4 __attribute__((vector_size(16)));
@@ -675,7 +683,7 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
 #pragma unroll
         for (int p = 0; p < NPT; ++p) {
             const int pidx = (pt0 + p) * MF + (col & ~3);        // first pixel of this lane's group of 4
-            const int oy = pidx / vw, ox = pidx - oy * vw;
+            const int oy = fdiv(pidx, rcp_vw), ox = pidx - oy * vw;
             const int gy = oy0 + oy, gx = ox0 + ox;
             nvs[p] = (oy < th && gy < P.Ho) ? min(min(tw - ox, P.Wo - gx), 4) : 0;           // pixels to store
             const int pix = nvs[p] > 0 ? gy * P.Wo + gx : 0;
@@ -730,7 +738,7 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
-        const int oy = pidx / vw, ox = pidx - oy * vw;
+        const int oy = fdiv(pidx, rcp_vw), ox = pidx - oy * vw;
         const int gy = oy0 + oy, gx = ox0 + ox;
         const bool pv = oy < th && ox < tw && gy < P.Ho && gx < P.Wo;
         const int pix = pv ? gy * P.Wo + gx : 0;
@@ -862,7 +870,7 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
-        const int my = pidx / P.mw, mx = pidx - my * P.mw;
+        const int my = fdiv(pidx, P.rcp_mw), mx = pidx - my * P.mw;
         const int gy = my0 + my, gx = mx0 + mx;
         const bool inside = gy >= 0 && gy < P.H1 && gx >= 0 && gx < P.W1;
 #pragma unroll
@@ -938,7 +946,7 @@ __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
-        const int oy = pidx / P.vw2, ox = pidx - oy * P.vw2;
+        const int oy = fdiv(pidx, P.rcp_vw2), ox = pidx - oy * P.vw2;
         const bool valid = oy < P.th && ox < P.tw;
         const bool inside = oy0 + oy < P.H2 && ox0 + ox < P.W2;
 #pragma unroll
@@ -1002,7 +1010,7 @@ __device__ __forceinline__ void depthwise_stage1(const BlockParams &P, float *mi
         const int g = it / mid_px, pidx = it - g * mid_px;
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
         if (g < ncg) {
-            const int my = pidx / P.mw, mx = pidx - my * P.mw;
+            const int my = fdiv(pidx, P.rcp_mw), mx = pidx - my * P.mw;
             const float *s = xs + (g * P.ih * P.iws + (my * c.stride) * P.iws + mx * c.stride) * 4;
             const f32x4 *w = c.wp + g * T;
             f32x4 a = {0.f, 0.f, 0.f, 0.f};
@@ -1099,7 +1107,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
             for (int r = 1; r < NRT1; ++r) acc[r][p] = acc[0][p];
             int pidx = (pt0 + p) * MF1 + col;
             pidx = pidx < npx1 ? pidx : 0;
-            const int my = pidx / P.mw, mx = pidx - my * P.mw;
+            const int my = fdiv(pidx, P.rcp_mw), mx = pidx - my * P.mw;
             off1[p] = PX1 > 0 ? my * P.iws + max(mx - max(0, -ix0), 0) + sub * (4 * PX1 * 64)
                               : ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * SUBP * P.in_gstride;
         }
@@ -1117,7 +1125,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
         }
         if (g1.active)
             store_global<MF1, NRT1, NPT1, false>(acc, P, P.c1, P.coff1, n, oy0, ox0, P.mh, P.mw, P.mw, rt0, rt_end1, pt0,
-                                                 P.relu_out);
+                                                 P.relu_out, P.rcp_mw);
         return;
     } else {
         // ---- S2: epilogue of layer 1 into the LDS tile
@@ -1202,7 +1210,8 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
 #pragma unroll
                             for (int r = 1; r < NRT2; ++r) acc2[r][p] = acc2[0][p];
                             const int pidx = (p0 + p) * MF2 + col;
-                            const int oy = min(pidx / P.vw2, P.th - 1), ox = min(pidx % P.vw2, P.tw - 1);
+                            const int oyu = fdiv(pidx, P.rcp_vw2);
+                            const int oy = min(oyu, P.th - 1), ox = min(pidx - oyu * P.vw2, P.tw - 1);
                             off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * SUBP * P.mid_gstride;
                         }
 #ifdef XL_PHASE_TIMING
@@ -1243,7 +1252,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                             __syncthreads();
                         } else if (g2.active)
                             store_global<MF2, NRT2, NPT2, SC>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
-                                                              p0, P.relu_out);
+                                                              p0, P.relu_out, P.rcp_vw2);
 #ifdef XL_PHASE_TIMING
                         if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 2] = clock64();
 #endif
@@ -1316,7 +1325,7 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
         for (int p = 0; p < NPT1; ++p) {
             int pidx = (pt0 + p) * MF1 + col;
             pidx = pidx < npx1 ? pidx : 0;
-            const int my = pidx / P.mw, mx = pidx - my * P.mw;
+            const int my = fdiv(pidx, P.rcp_mw), mx = pidx - my * P.mw;
             off1[p] = ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * P.in_gstride;
         }
     }
@@ -1408,7 +1417,7 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
 #pragma unroll
     for (int p = 0; p < NPT1; ++p) {
         e_pidx[p] = (pt0 + p) * MF1 + col1;
-        e_my[p] = e_pidx[p] / P.mw;
+        e_my[p] = fdiv(e_pidx[p], P.rcp_mw);
         e_mx[p] = e_pidx[p] - e_my[p] * P.mw;
     }
     const int ngroups = (P.c1.cout + 3) >> 2;

@@ -726,6 +726,9 @@ struct Builder {
         p.waves_r1 = ch.waves_r1;
         p.waves_r2 = ch.waves_r2;
         p.vw2 = ch.vw2;
+        auto rcp = [](int d) { return d <= 1 ? 0u : (unsigned)((1ull << 32) / (unsigned)d + 1); };
+        p.rcp_mw = rcp(ch.mw);
+        p.rcp_vw2 = rcp(ch.vw2);
         p.mid_gstride = ch.mh * ch.mw * 4;
         p.in_gstride = ch.ih * p.iws * 4;
         p.lds_buf_off = ch.mid_floats;
