@@ -380,7 +380,8 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         for (int i = 0; i < PLANAR_SLOTS; ++i) {
             const int Q = (i * nwaves_wg + wave_id) * 64 + lane_id;
             const int ch = Q / QPR, rq = Q - ch * QPR;
-            const int r = min(rq / qrow, P.ih - 1), q = rq - (rq / qrow) * qrow;
+            const int rr = fdiv(rq, P.rcp_qrow);
+            const int r = min(rr, P.ih - 1), q = rq - rr * qrow;
             const int gy = min(max(iy0 + r, 0), P.H - 1);
             xvo[i] = (unsigned)((ch * HWp + gy * P.W + ix0 + xs + 4 * q) * 4);
         }

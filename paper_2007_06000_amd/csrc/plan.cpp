@@ -729,6 +729,7 @@ struct Builder {
         auto rcp = [](int d) { return d <= 1 ? 0u : (unsigned)((1ull << 32) / (unsigned)d + 1); };
         p.rcp_mw = rcp(ch.mw);
         p.rcp_vw2 = rcp(ch.vw2);
+        p.rcp_qrow = rcp(p.iws / 4);
         p.mid_gstride = ch.mh * ch.mw * 4;
         p.in_gstride = ch.ih * p.iws * 4;
         p.lds_buf_off = ch.mid_floats;

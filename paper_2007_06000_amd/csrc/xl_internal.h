@@ -87,7 +87,7 @@ struct BlockParams {
     int waves_r1;           // stage-1 waves along the row-tile (Cout) direction
     int waves_r2;           // stage-2 waves along the row-tile direction
     int vw2;                // stage 2 lays output pixels out in virtual rows of vw2 >= tw columns
-    unsigned rcp_mw, rcp_vw2;   // 2^32 / mw + 1 and 2^32 / vw2 + 1 (0 when the divisor is 1): x / d = mulhi(x, rcp) for x < 65536
+    unsigned rcp_mw, rcp_vw2, rcp_qrow;   // 2^32 / d + 1 for d = mw, vw2, iws / 4 (0 when d is 1): x / d = mulhi(x, rcp) for x < 65536
     int mid_gstride;        // floats between consecutive 4-channel groups of the LDS tile
     int in_gstride;         // same for the staged input
     int lds_buf_off;        // float offset of the two staging buffers in LDS (after the tile)
