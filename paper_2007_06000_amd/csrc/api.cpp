@@ -181,12 +181,12 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, vo
             }
             continue;
         }
-        e = xl::launch_pack_filter(static_cast<const float *>(weights[L.w_slot]),
+        e = xl::launch_pack_filter(static_cast<const float *>(weights[L.w_slot]), plan->scale_ptr[p.layer],
                                    reinterpret_cast<xl::f32x4 *>(ws + p.offset), L.cout, L.cin, L.k, p.mf,
                                    p.nkg, p.nrt, s, p.pairs ? 1 : 0, p.pr);
         if (e == hipSuccess)
-            e = xl::launch_pack_affine(plan->scale_ptr[p.layer], plan->shift_ptr[p.layer],
-                                       reinterpret_cast<xl::f32x4 *>(ws + p.aff_offset), L.cout, p.mf, p.nrt, s);
+            e = xl::launch_pack_affine(plan->shift_ptr[p.layer], reinterpret_cast<xl::f32x4 *>(ws + p.aff_offset), L.cout,
+                                       p.mf, p.nrt, s);
         if (e != hipSuccess) {
             plan->error = std::string("filter re-layout launch failed: ") + hipGetErrorString(e);
             return XL_E_LAUNCH;

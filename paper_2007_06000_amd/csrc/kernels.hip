@@ -598,15 +598,16 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #endif
 }
 
-// Per-channel scale / shift of the 4 consecutive output channels a lane holds in accumulator
-// quad q of row tile rt, from the table xl_prepare lays out in accumulator order:
-// [row tile][quad][scale, shift][lane] float4 (0 for channels past Cout).
+// Per-channel shift of the 4 consecutive output channels a lane holds in accumulator quad q of row
+// tile rt, from the table xl_prepare lays out in accumulator order: [row tile][quad][lane] float4
+// (0 for channels past Cout).  The per-channel scale is not applied here: xl_prepare multiplies it into
+// the re-laid-out filter (scale * sum(w x) = sum((scale w) x)), so an epilogue loads half as much and
+// the multiply folds away (sc is the constant 1).
 template <int MF>
 __device__ __forceinline__ void load_affine(const ConvW &c, int rt, int q, f32x4 &sc, f32x4 &sh)
 {
-    const f32x4 *t = c.aff + ((rt * MM<MF>::NQ + q) * 2) * 64 + (threadIdx.x & 63);
-    sc = t[0];
-    sh = t[64];
+    sc = f32x4{1.f, 1.f, 1.f, 1.f};
+    sh = c.aff[(rt * MM<MF>::NQ + q) * 64 + (threadIdx.x & 63)];
 }
 
 // Epilogue of a tile to global memory (S5), also used by the single-layer kernel.
@@ -1600,8 +1601,8 @@ hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t l
 // zero where cout or cin run past the real extent.
 // ----------------------------------------------------------------------------
 // pairs != 0 (mf = 32, one K step): channel c goes to lane half c % 2, slot c / 2.
-__global__ void pack_filter_kernel(const float *__restrict__ w, f32x4 *__restrict__ wp, int cout, int cin, int k,
-                                   int mf, int nkg, int nrt, int pairs)
+__global__ void pack_filter_kernel(const float *__restrict__ w, const float *__restrict__ scale, f32x4 *__restrict__ wp,
+                                   int cout, int cin, int k, int mf, int nkg, int nrt, int pairs)
 {
     const int taps = k * k;
     const long long total = (long long)nkg * taps * nrt * 64;
@@ -1620,7 +1621,7 @@ __global__ void pack_filter_kernel(const float *__restrict__ w, f32x4 *__restric
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int ci = pairs ? 2 * j + sub : kg * kc + sub * 4 + j;
-        v[j] = (o < cout && ci < cin) ? w[((size_t)o * cin + ci) * taps + t] : 0.f;
+        v[j] = (o < cout && ci < cin) ? w[((size_t)o * cin + ci) * taps + t] * (scale ? scale[o] : 1.f) : 0.f;
     }
     wp[idx] = v;
 }
@@ -1628,8 +1629,8 @@ __global__ void pack_filter_kernel(const float *__restrict__ w, f32x4 *__restric
 // split-bf16 form: [K step][tap][row tile][hi, lo][lane] of 8 bf16;
 //   lane l holds cout = rt*mf + l%mf, cin = kg*kc + (l/mf)*8 + e, kc = 16 (mf = 32) or 32 (mf = 16);
 //   hi = bf16(w), lo = bf16(w - hi), round to nearest.
-__global__ void pack_filter_b3_kernel(const float *__restrict__ w, uint4 *__restrict__ wp, int cout, int cin, int k,
-                                      int mf, int nkg, int nrt)
+__global__ void pack_filter_b3_kernel(const float *__restrict__ w, const float *__restrict__ scale, uint4 *__restrict__ wp,
+                                      int cout, int cin, int k, int mf, int nkg, int nrt)
 {
     const int taps = k * k;
     const long long total = (long long)nkg * taps * nrt * 128;
@@ -1652,7 +1653,7 @@ __global__ void pack_filter_b3_kernel(const float *__restrict__ w, uint4 *__rest
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int ci = kg * kc + sub * 8 + 2 * e + h;
-            v[h] = (o < cout && ci < cin) ? w[((size_t)o * cin + ci) * taps + t] : 0.f;
+            v[h] = (o < cout && ci < cin) ? w[((size_t)o * cin + ci) * taps + t] * (scale ? scale[o] : 1.f) : 0.f;
         }
         unsigned hi, lo;
         split_bf16(v[0], v[1], hi, lo);
@@ -1661,22 +1662,21 @@ __global__ void pack_filter_b3_kernel(const float *__restrict__ w, uint4 *__rest
     wp[idx] = uint4{out[0], out[1], out[2], out[3]};
 }
 
-hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf, int nkg, int nrt,
-                              hipStream_t s, int pairs, int pr)
+hipError_t launch_pack_filter(const float *w, const float *scale, f32x4 *wp, int cout, int cin, int k, int mf, int nkg,
+                              int nrt, hipStream_t s, int pairs, int pr)
 {
     const long long total = (long long)nkg * k * k * nrt * (pr ? 128 : 64);
     const int threads = 256;
     const int grid = (int)((total + threads - 1) / threads);
     if (pr)
-        hipLaunchKernelGGL(pack_filter_b3_kernel, dim3(grid), dim3(threads), 0, s, w, (uint4 *)wp, cout, cin, k, mf, nkg, nrt);
+        hipLaunchKernelGGL(pack_filter_b3_kernel, dim3(grid), dim3(threads), 0, s, w, scale, (uint4 *)wp, cout, cin, k, mf, nkg, nrt);
     else
-        hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, wp, cout, cin, k, mf, nkg, nrt, pairs);
+        hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, scale, wp, cout, cin, k, mf, nkg, nrt, pairs);
     return hipGetLastError();
 }
 
-// scale / shift in accumulator order: [row tile][quad][scale, shift][lane] float4
-__global__ void pack_affine_kernel(const float *__restrict__ scale, const float *__restrict__ shift,
-                                   f32x4 *__restrict__ out, int cout, int mf, int nrt)
+// shift in accumulator order: [row tile][quad][lane] float4 (the scale goes into the filter)
+__global__ void pack_affine_kernel(const float *__restrict__ shift, f32x4 *__restrict__ out, int cout, int mf, int nrt)
 {
     const int nq = mf == 32 ? 4 : 1;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // over nrt * nq * 64
@@ -1684,23 +1684,19 @@ __global__ void pack_affine_kernel(const float *__restrict__ scale, const float 
     const int lane = idx & 63, q = (idx >> 6) % nq, rt = (idx >> 6) / nq;
     const int sub = lane / mf;
     const int cb = rt * mf + (mf == 32 ? q * 8 + sub * 4 : sub * 4);
-    f32x4 a, b;
+    f32x4 b;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int co = cb + i;
-        a[i] = co < cout ? (scale ? scale[co] : 1.f) : 0.f;
-        b[i] = co < cout ? (shift ? shift[co] : 0.f) : 0.f;
+        b[i] = (co < cout && shift) ? shift[co] : 0.f;
     }
-    out[((rt * nq + q) * 2) * 64 + lane] = a;
-    out[((rt * nq + q) * 2 + 1) * 64 + lane] = b;
+    out[idx] = b;
 }
 
-hipError_t launch_pack_affine(const float *scale, const float *shift, f32x4 *out, int cout, int mf, int nrt,
-                              hipStream_t s)
+hipError_t launch_pack_affine(const float *shift, f32x4 *out, int cout, int mf, int nrt, hipStream_t s)
 {
     const int total = nrt * (mf == 32 ? 4 : 1) * 64;
-    hipLaunchKernelGGL(pack_affine_kernel, dim3((total + 255) / 256), dim3(256), 0, s, scale, shift, out, cout, mf,
-                       nrt);
+    hipLaunchKernelGGL(pack_affine_kernel, dim3((total + 255) / 256), dim3(256), 0, s, shift, out, cout, mf, nrt);
     return hipGetLastError();
 }
 

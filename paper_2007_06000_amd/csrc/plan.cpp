@@ -591,7 +591,7 @@ struct Builder {
             p.nkg = pairs ? 1 : ceil_div(L.cin, kc_of(mf, pr));
             p.nrt = ceil_div(L.cout, mf);
             p.bytes = (size_t)p.nkg * L.k * L.k * p.nrt * 64 * 16 * (pr ? 2 : 1);
-            p.aff_bytes = (size_t)p.nrt * (mf == 32 ? 4 : 1) * 2 * 64 * 16;
+            p.aff_bytes = (size_t)p.nrt * (mf == 32 ? 4 : 1) * 64 * 16;
         }
         p.offset = 0;
         p.aff_offset = 0;

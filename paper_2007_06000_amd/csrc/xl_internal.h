@@ -24,9 +24,9 @@ constexpr int gps_of(int mf, int pr = 0) { return (mf == 32 ? 2 : 4) << pr; }   
 
 // One convolution as the kernels see it.
 struct ConvW {
-    const f32x4 *wp;        // filter re-laid out as [K step][tap][row tile][lane] of float4
+    const f32x4 *wp;        // filter, times the per-channel scale, re-laid out as [K step][tap][row tile][lane] of float4
                             // (split-bf16 kernels: [K step][tap][row tile][hi, lo][lane] of 8 bf16)
-    const f32x4 *aff;       // scale / shift in accumulator order: [row tile][quad][scale, shift][lane] float4
+    const f32x4 *aff;       // shift in accumulator order: [row tile][quad][lane] float4
     int cin, cout;
     int k, stride, pad;
     int relu;
@@ -294,10 +294,9 @@ constexpr int MAX_ALTERNATIVES = 48;  // candidates per block kept for on-device
 hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t lds_bytes, hipStream_t s);
 hipError_t configure_kernels(int max_lds_bytes);      // raises the dynamic-LDS cap of every variant
 
-hipError_t launch_pack_filter(const float *w, f32x4 *wp, int cout, int cin, int k, int mf,
+hipError_t launch_pack_filter(const float *w, const float *scale, f32x4 *wp, int cout, int cin, int k, int mf,
                               int nkg, int nrt, hipStream_t s, int pairs = 0, int pr = 0);
-hipError_t launch_pack_affine(const float *scale, const float *shift, f32x4 *out, int cout, int mf, int nrt,
-                              hipStream_t s);
+hipError_t launch_pack_affine(const float *shift, f32x4 *out, int cout, int mf, int nrt, hipStream_t s);
 hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, int Ho, int Wo,
                           int k, int stride, int pad, int Cy, int coff, hipStream_t s);
 hipError_t launch_add(const float *a, const float *b, float *y, long long count, int relu, hipStream_t s);
