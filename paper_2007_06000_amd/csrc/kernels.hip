@@ -598,16 +598,37 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #endif
 }
 
-// Per-channel shift of the 4 consecutive output channels a lane holds in accumulator quad q of row
-// tile rt, from the table xl_prepare lays out in accumulator order: [row tile][quad][lane] float4
-// (0 for channels past Cout).  The per-channel scale is not applied here: xl_prepare multiplies it into
-// the re-laid-out filter (scale * sum(w x) = sum((scale w) x)), so an epilogue loads half as much and
-// the multiply folds away (sc is the constant 1).
+// The per-channel scale and shift (folded BN, bias) cost the epilogues nothing: xl_prepare multiplies
+// the scale into the re-laid-out filter (scale * sum(w x) = sum((scale w) x)), and the accumulators start
+// from the shift instead of zero (init_acc: the table read overlaps the wait for the first operands, and
+// the values live in registers the K loop holds anyway).  What the epilogues still call load_affine
+// for folds away: scale 1, shift 0.
 template <int MF>
-__device__ __forceinline__ void load_affine(const ConvW &c, int rt, int q, f32x4 &sc, f32x4 &sh)
+__device__ __forceinline__ void load_affine(const ConvW &, int, int, f32x4 &sc, f32x4 &sh)
 {
     sc = f32x4{1.f, 1.f, 1.f, 1.f};
-    sh = c.aff[(rt * MM<MF>::NQ + q) * 64 + (threadIdx.x & 63)];
+    sh = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+// Accumulators of row tiles rt0 .. rt0 + NRT - 1 start from the per-channel shift: the table xl_prepare
+// lays out in accumulator order, [row tile][quad][lane] float4, holds for every lane the 4 consecutive
+// output channels of accumulator quad q (0 for channels past Cout).
+template <int MF, int NRT, int NPT>
+__device__ __forceinline__ void init_acc(typename MM<MF>::Acc (&acc)[NRT][NPT], const ConvW &c, int rt0)
+{
+    typedef MM<MF> M;
+#pragma unroll
+    for (int r = 0; r < NRT; ++r) {
+        typename M::Acc a;
+#pragma unroll
+        for (int q = 0; q < M::NQ; ++q) {
+            const f32x4 sh = c.aff[(min(rt0 + r, c.nrt - 1) * M::NQ + q) * 64 + (threadIdx.x & 63)];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[q * 4 + i] = sh[i];
+        }
+#pragma unroll
+        for (int p = 0; p < NPT; ++p) acc[r][p] = a;
+    }
 }
 
 // Epilogue of a tile to global memory (S5), also used by the single-layer kernel.
@@ -1104,9 +1125,6 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
         const int sub = lane / MF1, col = lane % MF1;
 #pragma unroll
         for (int p = 0; p < NPT1; ++p) {
-            zero_acc(acc[0][p]);
-#pragma unroll
-            for (int r = 1; r < NRT1; ++r) acc[r][p] = acc[0][p];
             int pidx = (pt0 + p) * MF1 + col;
             pidx = pidx < npx1 ? pidx : 0;
             const int my = fdiv(pidx, P.rcp_mw), mx = pidx - my * P.mw;
@@ -1114,6 +1132,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                               : ((my * P.c1.stride) * P.iws + mx * P.c1.stride) * 4 + sub * SUBP * P.in_gstride;
         }
     }
+    init_acc<MF1, NRT1, NPT1>(acc, P.c1, rt0);
     XL_PHASE(L, 0);
     conv_pass<MF1, K1, NRT1, NPT1, true, PX1, PR>(acc, P, P.c1, g1, nullptr, off1, buf, ximg,
                                                   (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
@@ -1137,10 +1156,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
             if (P.n1 == 2) {
                 // second producer of a merge block (paper Fig. 4c): same input, same geometry, its own
                 // filter; its result is added to the first one's in the LDS tile
-#pragma unroll
-                for (int p = 0; p < NPT1; ++p)
-#pragma unroll
-                    for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
+                init_acc<MF1, NRT1, NPT1>(acc, P.c1b, rt0);
                 conv_pass<MF1, K1, NRT1, NPT1, true, PX1, PR>(acc, P, P.c1b, g1, nullptr, off1, buf, ximg,
                                                          (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
                 store_mid<MF1, NRT1, NPT1, PR>(acc, P, P.c1b, mid, my0, mx0, rt0, rt_end1, pt0, npx1, 0.f, true,
@@ -1206,11 +1222,9 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                         g2.active = r0 < rte && p0 < npt2;
                         typename MM<MF2>::Acc acc2[NRT2][NPT2];
                         int off2[NPT2];
+                        init_acc<MF2, NRT2, NPT2>(acc2, c, r0);
 #pragma unroll
                         for (int p = 0; p < NPT2; ++p) {
-                            zero_acc(acc2[0][p]);
-#pragma unroll
-                            for (int r = 1; r < NRT2; ++r) acc2[r][p] = acc2[0][p];
                             const int pidx = (p0 + p) * MF2 + col;
                             const int oyu = fdiv(pidx, P.rcp_vw2);
                             const int oy = min(oyu, P.th - 1), ox = min(pidx - oyu * P.vw2, P.tw - 1);
@@ -1406,15 +1420,11 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
 
     // ---- what the epilogue and the pooling need that does not change from tile to tile
     const int sub1 = lane / MF1, col1 = lane % MF1;
-    // scale / shift stay in registers across tiles when that fits the 128 registers of this kernel
+    // the shift the accumulators start from stays in registers across tiles when that fits the 128
+    // registers of this kernel
     constexpr bool KEEP_AFFINE = NRT1 == 1 && (JN < 4 || MF1 == 16);
-    f32x4 fa[NRT1][M1::NQ], fb[NRT1][M1::NQ];
-    if constexpr (KEEP_AFFINE) {
-#pragma unroll
-        for (int r = 0; r < NRT1; ++r)
-#pragma unroll
-            for (int q = 0; q < M1::NQ; ++q) load_affine<MF1>(P.c1, min(rt0 + r, P.c1.nrt - 1), q, fa[r][q], fb[r][q]);
-    }
+    typename M1::Acc acc_init[NRT1][1];
+    if constexpr (KEEP_AFFINE) init_acc<MF1, NRT1, 1>(acc_init, P.c1, rt0);
     int e_my[NPT1], e_mx[NPT1], e_pidx[NPT1];
 #pragma unroll
     for (int p = 0; p < NPT1; ++p) {
@@ -1443,20 +1453,17 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
         __syncthreads();
         if (L + (int)gridDim.x < P.nblocks) request(L + gridDim.x);
         typename M1::Acc acc[NRT1][NPT1];
+        if constexpr (KEEP_AFFINE) {
 #pragma unroll
-        for (int p = 0; p < NPT1; ++p)
+            for (int p = 0; p < NPT1; ++p)
 #pragma unroll
-            for (int r = 0; r < NRT1; ++r) zero_acc(acc[r][p]);
+                for (int r = 0; r < NRT1; ++r) acc[r][p] = acc_init[r][0];
+        } else {
+            init_acc<MF1, NRT1, NPT1>(acc, P.c1, rt0);
+        }
         if (active)
             conv_accum<MF1, K1, NRT1, NPT1, 0, JN>(acc, xbuf, off1, P.iws, P.in_gstride, wbuf, rloc, wg_rt, P.c1.nkg);
         // epilogue into the LDS tile (store_mid with the tile-independent parts taken from above)
-        if constexpr (!KEEP_AFFINE) {
-            asm volatile("" ::: "memory");      // not before the K loop
-#pragma unroll
-            for (int r = 0; r < NRT1; ++r)
-#pragma unroll
-                for (int q = 0; q < M1::NQ; ++q) load_affine<MF1>(P.c1, min(rt0 + r, P.c1.nrt - 1), q, fa[r][q], fb[r][q]);
-        }
 #pragma unroll
         for (int p = 0; p < NPT1; ++p) {
             const int gy = my0 + e_my[p], gx = mx0 + e_mx[p];
@@ -1470,7 +1477,7 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
                     f32x4 v;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
+                        float z = acc[r][p][q * 4 + i];
                         if (P.c1.relu) z = fmaxf(z, 0.f);
                         if (!inside) z = -FLT_MAX;
                         if (cb + i >= P.c1.cout) z = 0.f;
