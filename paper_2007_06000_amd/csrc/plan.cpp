@@ -399,7 +399,17 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     std::vector<Choice> ranked;
     for (auto &kv : per_key) ranked.push_back(kv.second);
     std::sort(ranked.begin(), ranked.end(), [](const Choice &a, const Choice &b) { return a.cost < b.cost; });
-    if (ranked.size() > (size_t)MAX_ALTERNATIVES) ranked.resize(MAX_ALTERNATIVES);
+    if (ranked.size() > (size_t)MAX_ALTERNATIVES) {
+        // The model assumes at most two waves per SIMD; kernels that need fewer registers run three
+        // 256-thread workgroups per CU when their LDS share allows it, which the model cannot rank.  Keep
+        // the best of those among the candidates, for xl_tune to time.
+        const size_t reserve = MAX_ALTERNATIVES / 5;
+        std::vector<Choice> small;
+        for (size_t i = MAX_ALTERNATIVES - reserve; i < ranked.size() && small.size() < reserve; ++i)
+            if (ranked[i].threads == 256 && ranked[i].lds_bytes * 3 <= pl.lds_per_cu) small.push_back(ranked[i]);
+        ranked.resize(MAX_ALTERNATIVES - small.size());
+        ranked.insert(ranked.end(), small.begin(), small.end());
+    }
     return ranked;
 }
 

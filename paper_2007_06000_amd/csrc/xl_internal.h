@@ -285,7 +285,7 @@ constexpr int STAGE_UNITS = XL_STAGE_UNITS;      // input units (4 channels x 4 
 constexpr int MAX_W_CHUNK_BYTES = 52 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
 constexpr int PLANAR_SLOTS = 8;     // LDS-direct loads per wave and chunk of a planar input chunk
 constexpr int MAX_THREADS = 512;
-constexpr int MAX_ALTERNATIVES = 48;  // candidates per block kept for on-device tuning
+constexpr int MAX_ALTERNATIVES = 64;  // candidates per block kept for on-device tuning
 #ifndef XL_MIN_WAVES
 #define XL_MIN_WAVES 2
 #endif
