@@ -601,14 +601,7 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 // The per-channel scale and shift (folded BN, bias) cost the epilogues nothing: xl_prepare multiplies
 // the scale into the re-laid-out filter (scale * sum(w x) = sum((scale w) x)), and the accumulators start
 // from the shift instead of zero (init_acc: the table read overlaps the wait for the first operands, and
-// the values live in registers the K loop holds anyway).  What the epilogues still call load_affine
-// for folds away: scale 1, shift 0.
-template <int MF>
-__device__ __forceinline__ void load_affine(const ConvW &, int, int, f32x4 &sc, f32x4 &sh)
-{
-    sc = f32x4{1.f, 1.f, 1.f, 1.f};
-    sh = f32x4{0.f, 0.f, 0.f, 0.f};
-}
+// the values live in registers the K loop holds anyway).  An epilogue is activation, masks and stores.
 
 // Accumulators of row tiles rt0 .. rt0 + NRT - 1 start from the per-channel shift: the table xl_prepare
 // lays out in accumulator order, [row tile][quad][lane] float4, holds for every lane the 4 consecutive
@@ -679,14 +672,7 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     const int plane = P.Ho * P.Wo;
     float *__restrict__ yn = P.y + ((size_t)n * P.Cy + coff) * plane;
     const float *__restrict__ scn = HAS_SC ? P.sc + (size_t)n * P.Csc * plane : nullptr;
-    // scale / shift of every channel this lane holds: all loads go out before the first use, but not
-    // before the K loop (the clobber keeps the compiler from hoisting 64 live registers over it)
-    asm volatile("" ::: "memory");
-    f32x4 fa[NRT][M::NQ], fb[NRT][M::NQ];
-#pragma unroll
-    for (int r = 0; r < NRT; ++r)
-#pragma unroll
-        for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[r][q], fb[r][q]);
+    asm volatile("" ::: "memory");      // keeps the epilogue's address arithmetic out of the K loop's schedule
 
     const bool wide = (vw & 3) == 0 || th == 1;
     if (wide) {
@@ -733,7 +719,7 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
                     float v[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        v[e] = acc[r][p][q * 4 + e] * fa[r][q][e] + fb[r][q][e];
+                        v[e] = acc[r][p][q * 4 + e];
                         if (c.relu) v[e] = fmaxf(v[e], 0.f);
                     }
                     quad_transpose(v);
@@ -779,7 +765,7 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
             float res[M::NQ * 4];
 #pragma unroll
             for (int e = 0; e < M::NQ * 4; ++e) {
-                float v = acc[r][p][e] * fa[r][e >> 2][e & 3] + fb[r][e >> 2][e & 3];
+                float v = acc[r][p][e];
                 if (c.relu) v = fmaxf(v, 0.f);
                 if constexpr (HAS_SC) v += sv[e];
                 if (relu_out) v = fmaxf(v, 0.f);
@@ -819,21 +805,17 @@ __device__ __forceinline__ void store_gap(const typename MM<MF>::Acc (&acc)[NRT]
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
     const int rows_wg = wg_rt * MF;
-    const int rt0 = rt_base + wr * NRT;
     if (active) {
         asm volatile("" ::: "memory");
         float s[NRT][M::NQ * 4];
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
-            f32x4 fa[M::NQ], fb[M::NQ];
-#pragma unroll
-            for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[q], fb[q]);
 #pragma unroll
             for (int e = 0; e < M::NQ * 4; ++e) {
                 float t = 0.f;
 #pragma unroll
                 for (int p = 0; p < NPT; ++p) {
-                    float v = acc[r][p][e] * fa[e >> 2][e & 3] + fb[e >> 2][e & 3];
+                    float v = acc[r][p][e];
                     if (c.relu) v = fmaxf(v, 0.f);
                     if (P.relu_out) v = fmaxf(v, 0.f);
                     t += ((pt0 + p) * MF + col < npx) ? v : 0.f;
@@ -884,12 +866,7 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
     typedef MM<MF> M;
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
-    asm volatile("" ::: "memory");      // keep the loads below from being hoisted over the K loop
-    f32x4 fa[NRT][M::NQ], fb[NRT][M::NQ];
-#pragma unroll
-    for (int r = 0; r < NRT; ++r)
-#pragma unroll
-        for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[r][q], fb[r][q]);
+    asm volatile("" ::: "memory");      // keeps the epilogue's address arithmetic out of the K loop's schedule
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -921,7 +898,7 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
                 }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
+                    float z = acc[r][p][q * 4 + i];
                     if (c.relu) z = fmaxf(z, 0.f);
                     if (add) {
                         z += old[i];
@@ -961,11 +938,6 @@ __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT
     const int sub = lane / MF, col = lane % MF;
     const int npx = P.th * P.tw;
     asm volatile("" ::: "memory");
-    f32x4 fa[NRT][M::NQ], fb[NRT][M::NQ];
-#pragma unroll
-    for (int r = 0; r < NRT; ++r)
-#pragma unroll
-        for (int q = 0; q < M::NQ; ++q) load_affine<MF>(c, min(rt0 + r, c.nrt - 1), q, fa[r][q], fb[r][q]);
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -981,7 +953,7 @@ __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT
                 f32x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float z = acc[r][p][q * 4 + i] * fa[r][q][i] + fb[r][q][i];
+                    float z = acc[r][p][q * 4 + i];
                     if (c.relu) z = fmaxf(z, 0.f);
                     v[i] = inside ? z : -FLT_MAX;
                 }
