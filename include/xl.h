@@ -17,7 +17,9 @@
  * LD.G, CONV1, ST.S, barrier, LD.S, CONV2, ST.G) or, for comparison, one
  * kernel per layer with every intermediate written to and re-read from HBM
  * (Fig. 3a).  Both paths use the same tiled implicit-GEMM convolution
- * (section 3.2) on the fp32 matrix cores.
+ * (section 3.2) on the fp32 matrix cores, or, when xl_options.precision asks
+ * for it, on the bf16 matrix cores with every operand split into two bf16
+ * numbers.
  *
  * Data.  All tensors are dense fp32 NCHW in DEVICE memory owned by the caller
  * (e.g. allocated by PyTorch).  Filters are [Cout, Cin, K, K] fp32 (section 4.1
@@ -176,8 +178,9 @@ xl_status xl_plan_query(const xl_plan *plan, int group, xl_group_info *out);
 size_t xl_plan_workspace_bytes(const xl_plan *plan);
 
 /*
- * Re-lay the filters into `workspace` (device) for the matrix-core kernels and
- * record the scale/shift pointers.  `weights[slot]` are DEVICE pointers indexed
+ * Re-lay the filters into `workspace` (device) for the matrix-core kernels: the
+ * per-channel scale is multiplied into the re-laid-out filter (one more fp32
+ * rounding per weight), the shift is re-laid out in accumulator order.  `weights[slot]` are DEVICE pointers indexed
  * by the slots named in xl_layer; they must stay valid and unchanged until the
  * last xl_run that uses this workspace has finished.  Call once per workspace,
  * and again whenever filter values change.  Enqueues on `stream`; returns
