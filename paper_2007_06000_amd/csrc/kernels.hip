@@ -264,6 +264,31 @@ __device__ __forceinline__ void conv_accum_b3(typename MM<MF, 1>::Acc (&acc)[NRT
             for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(ah[cur][r], bh[cur][p], acc[r][p]);
         __builtin_amdgcn_sched_barrier(0);
     };
+    // Four or more tile pairs per wave: one operand set only (two would not fit 256 registers); the
+    // reads of a step are covered by the other wave of the SIMD and by the step's own 12+ operations.
+    if constexpr (NRT * NPT >= 4) {
+        for (int kg = 0; kg < nkg; ++kg) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                fetch(0, kg, t);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < NRT; ++r)
+#pragma unroll
+                    for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(al[0][r], bh[0][p], acc[r][p]);
+#pragma unroll
+                for (int r = 0; r < NRT; ++r)
+#pragma unroll
+                    for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(ah[0][r], bl[0][p], acc[r][p]);
+#pragma unroll
+                for (int r = 0; r < NRT; ++r)
+#pragma unroll
+                    for (int p = 0; p < NPT; ++p) acc[r][p] = M::mma(ah[0][r], bh[0][p], acc[r][p]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        return;
+    }
     fetch(0, 0, 0);
     if constexpr (T == 1) {
         for (int kg = 0; kg < nkg; kg += 2) {

@@ -244,6 +244,9 @@ struct Variant {
     X(216, KIND_SINGLE, 32, 3, 4, 1, 0, 0, 0, 0, 0, 0, 0)          \
     X(217, KIND_SINGLE, 32, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)          \
     X(218, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)          \
+    X(203, KIND_SINGLE, 32, 1, 2, 4, 0, 0, 0, 0, 0, 0, 0)          \
+    X(222, KIND_FUSED2, 32, 3, 2, 2, 32, 2, 2, 3, 0, 0, 0)         \
+    X(213, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 2, 3, 1, 0, 0)         \
     /* split */                                                    \
     X(210, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)         \
     X(211, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 0)         \
