@@ -146,7 +146,7 @@ def test_tuned_plans_match_the_oracle(cfg, kw):
 
 @pytest.mark.parametrize("cfg", [4, 5])
 def test_full_size_configs_with_the_plans_the_benchmark_times(cfg):
-    """bench.py times tuned plans at the full BASELINE sizes: the same launch configuration, every element."""
+    """bench.py times tuned plans at the full benchmark sizes: the same launch configuration, every element."""
     run_both(W.config(cfg), tune=True)
 
 
