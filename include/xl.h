@@ -197,6 +197,8 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights,
  * fused = 0: one kernel per layer (concat still free).  Stream-ordered,
  * asynchronous; results are complete when the stream reaches this point.
  * Two xl_run calls that share a workspace must be ordered on one stream.
+ * The call enqueues kernel launches only (no allocation, no copy, no memset, no
+ * synchronisation), so it may be recorded into a HIP graph by a capturing stream.
  */
 xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
                  void *workspace, void *stream, int fused);
