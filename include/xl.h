@@ -122,7 +122,13 @@ typedef struct xl_options {
                                two bf16 numbers, hi = bf16(x) and lo = bf16(x - hi), and a product
                                is hi*hi + hi*lo + lo*hi on the bf16 matrix cores, accumulated in
                                fp32 (error at most 3 * 2^-16 of |a||b| per product, about 4e-6 rms; operands must be
-                               finite and below 2^127 in magnitude).  Tensors in memory stay fp32.
+                               finite and below 2^127 in magnitude).  The error of an output is therefore
+                               relative to sum(|a||b|) over its reduction, not to the output itself: the
+                               library's bar |err| <= 1e-4 + 1e-4 |out| holds for data of the benchmark's
+                               scale (activations and filter sums of order 1, where 3 * 2^-16 * sum|a||b|
+                               stays under 1e-4); on inputs scaled by s the absolute part of the bar has to
+                               scale with s as well, i.e. the guarantee is |err| <= 1e-4 * max|out| there.
+                               Tensors in memory stay fp32.
                                A depthwise first layer stays on the vector ALU in fp32; xl_tune may
                                keep an fp32 kernel for a block where it measures faster. */
 } xl_options;
@@ -167,24 +173,39 @@ xl_status xl_plan_create(const xl_layer *layers, int nlayers,
                          const xl_group *groups, int ngroups,
                          int device, const xl_options *opts, xl_plan **out);
 
+/* Frees the host metadata of a plan (NULL is allowed).  No device memory is touched. */
 void xl_plan_destroy(xl_plan *plan);
 
+/* Number of fusion blocks of the plan in graph order (paper section 3.1, Fig. 5: the dotted
+ * boxes of the compute graph); layers outside every listed block count as XL_SINGLE blocks. */
 int xl_plan_num_groups(const xl_plan *plan);
 
+/* What was decided for block `group` (0 .. xl_plan_num_groups - 1): the output tile and grid
+ * (paper section 3.2: "tiling size" and "grid size"), the halo-extended intermediate and input
+ * tiles (section 3.2: redundant data), the LDS share of one workgroup (section 3.2: shared memory
+ * is the bottleneck resource) and the block's algorithmic traffic, fused and unfused (section 2.2
+ * Fig. 3; stored elements as counted in Table 2).  XL_E_GRAPH for a group out of range. */
 xl_status xl_plan_query(const xl_plan *plan, int group, xl_group_info *out);
 
-/* Bytes of caller-provided device workspace (filters re-laid out for the matrix
- * cores + every intermediate tensor of the unfused path). */
+/* Bytes of caller-provided device workspace: the filters re-laid out for the matrix cores (the
+ * counterpart of the paper's filters and bias placed in constant memory, section 3.3) plus every
+ * tensor that one kernel writes and a later one reads -- in the unfused path each layer's output
+ * (section 2.2 Fig. 3a), in the fused path only tensors between blocks. */
 size_t xl_plan_workspace_bytes(const xl_plan *plan);
 
 /*
+ * Upload step before the first launch (paper section 2.1: read-only data is copied to the device
+ * and placed where the kernels read it fastest before a kernel runs; section 3.3: filters and bias
+ * are read-only and get a placement of their own).
  * Re-lay the filters into `workspace` (device) for the matrix-core kernels: the
  * per-channel scale is multiplied into the re-laid-out filter (one more fp32
  * rounding per weight), the shift is re-laid out in accumulator order.  `weights[slot]` are DEVICE pointers indexed
  * by the slots named in xl_layer; they must stay valid and unchanged until the
  * last xl_run that uses this workspace has finished.  Call once per workspace,
- * and again whenever filter values change.  Enqueues on `stream`; returns
- * without synchronising.
+ * and again whenever filter values change; a plan remembers every workspace it
+ * has prepared.  The plan's device must be the current HIP device (XL_E_DEVICE
+ * otherwise).  Enqueues on `stream`; returns without synchronising.  Not
+ * thread-safe against other calls on the same plan.
  */
 xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights,
                      void *workspace, void *stream);
@@ -199,6 +220,10 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights,
  * Two xl_run calls that share a workspace must be ordered on one stream.
  * The call enqueues kernel launches only (no allocation, no copy, no memset, no
  * synchronisation), so it may be recorded into a HIP graph by a capturing stream.
+ * Every tensor pointer read from `tensors` must be 16-byte aligned (XL_E_ALIGN); the plan's device
+ * must be the current HIP device (XL_E_DEVICE).  The plan is not modified: several threads may run
+ * one plan at the same time (on workspaces of their own); the message of a failure is kept per
+ * thread and returned by xl_plan_last_error on that thread.
  */
 xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
                  void *workspace, void *stream, int fused);
@@ -211,13 +236,55 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
  * xl_plan_query reports the adopted tiles.  Needs xl_prepare on this workspace first.  Contents of
  * the tensors do not matter but every graph input/output pointer must be valid; outputs and the
  * workspace intermediates are overwritten.  Unlike xl_run this call SYNCHRONISES the stream
- * repeatedly; call it once, outside any timed region.  reps < 1 means 3 timed launches per candidate.
+ * repeatedly; call it once, outside any timed region.  Every candidate is timed three times (fastest
+ * kept) and the six fastest again `reps` times each (reps < 5 means 5), ranked by their MEDIAN
+ * time; ties go to the lower candidate index.  xl_plan_candidate_info(.., -1, ..) names the winner.
  */
 xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors,
                   void *workspace, void *stream, int reps);
 
-/* Number of kernel launches one xl_run issues in the given mode. */
+/* Number of kernel launches one xl_run issues in the given mode (paper section 2.2, Fig. 3: one
+ * kernel per layer unfused, one per fusion block fused). */
 int xl_plan_num_launches(const xl_plan *plan, int fused);
+
+/*
+ * The tuner's search space made visible (paper section 3.2: the tuning tool searches (tile, grid)
+ * candidates and must not change results).  Every launch of a plan (index 0 ..
+ * xl_plan_num_launches(plan, fused) - 1, in launch order) has a ranked list of candidate launch
+ * configurations: kernel variant, output tile, workgroup size, wave layout, chunk length and
+ * output-channel split.  Candidate 0 is the cost model's choice; xl_tune adopts the one it measures
+ * fastest; xl_plan_select_candidate adopts one by index, so that a caller can time or check each.
+ * Element-wise launches (pooling, add, depthwise, global pooling of the unfused path) have exactly
+ * one candidate.
+ */
+typedef struct xl_launch_info {
+    int group;              /* fusion block the launch belongs to (fused mode), -1 in unfused mode  */
+    int first_layer;        /* first layer the launch executes                                     */
+    int nlayers;            /* layers the launch executes (1 in unfused mode)                      */
+    int is_block_kernel;    /* 1: a convolution block kernel; 0: an element-wise kernel            */
+    int candidate;          /* index of this configuration in the launch's candidate list          */
+    int variant;            /* id of the compiled kernel variant (block kernels)                   */
+    int tile_h, tile_w;     /* output tile                                                         */
+    int threads;            /* workgroup size                                                      */
+    int cout_split;         /* workgroups sharing a tile, each a slice of the output channels      */
+    int waves_cout_1, waves_cout_2;   /* waves along the output-channel direction, stage 1 / 2    */
+    int chunk_channels;     /* input channels staged per pipeline step of stage 1                  */
+    int lds_bytes;          /* LDS per workgroup                                                   */
+    int workgroups;         /* workgroups launched (logical: tiles * cout_split * N)               */
+    int precision;          /* XL_PRECISION_*                                                      */
+    double model_cost_us;   /* the cost model's estimate for this candidate                        */
+} xl_launch_info;
+
+/* Number of candidates of a launch; 0 when plan is NULL or the launch index is out of range. */
+int xl_plan_num_candidates(const xl_plan *plan, int fused, int launch);
+
+/* Describes candidate `candidate` of a launch; candidate = -1 describes the adopted one.
+ * XL_E_GRAPH for an index out of range. */
+xl_status xl_plan_candidate_info(const xl_plan *plan, int fused, int launch, int candidate, xl_launch_info *out);
+
+/* Adopts candidate `candidate` for a launch: later xl_run calls use it, and xl_plan_query reports
+ * its tiles for the launch's block.  Host only; must not race with xl_run on the same plan. */
+xl_status xl_plan_select_candidate(xl_plan *plan, int fused, int launch, int candidate);
 
 /*
  * The paper's tuner search space (section 3.2): square tiles whose size and

@@ -28,6 +28,7 @@ EXPORTS = [
     "xl_plan_create", "xl_plan_destroy", "xl_plan_num_groups", "xl_plan_query", "xl_plan_workspace_bytes",
     "xl_prepare", "xl_run", "xl_tune", "xl_plan_num_launches", "xl_tuner_candidates", "xl_required_extent",
     "xl_strerror", "xl_plan_last_error", "xl_version",
+    "xl_plan_num_candidates", "xl_plan_candidate_info", "xl_plan_select_candidate",
 ]
 
 
@@ -66,6 +67,18 @@ class xl_group_info(ctypes.Structure):
                 ("stores_fused", ctypes.c_longlong), ("stores_unfused", ctypes.c_longlong),
                 ("flops", ctypes.c_longlong), ("flops_executed", ctypes.c_longlong),
                 ("redundancy", ctypes.c_double), ("precision", ctypes.c_int)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+class xl_launch_info(ctypes.Structure):
+    _fields_ = [("group", ctypes.c_int), ("first_layer", ctypes.c_int), ("nlayers", ctypes.c_int),
+                ("is_block_kernel", ctypes.c_int), ("candidate", ctypes.c_int), ("variant", ctypes.c_int),
+                ("tile_h", ctypes.c_int), ("tile_w", ctypes.c_int), ("threads", ctypes.c_int),
+                ("cout_split", ctypes.c_int), ("waves_cout_1", ctypes.c_int), ("waves_cout_2", ctypes.c_int),
+                ("chunk_channels", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("workgroups", ctypes.c_int),
+                ("precision", ctypes.c_int), ("model_cost_us", ctypes.c_double)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -116,6 +129,12 @@ def lib() -> ctypes.CDLL:
         L.xl_strerror.restype = ctypes.c_char_p
         L.xl_plan_last_error.argtypes = [vp]
         L.xl_plan_last_error.restype = ctypes.c_char_p
+        L.xl_plan_num_candidates.argtypes = [vp, i, i]
+        L.xl_plan_num_candidates.restype = i
+        L.xl_plan_candidate_info.argtypes = [vp, i, i, i, ctypes.POINTER(xl_launch_info)]
+        L.xl_plan_candidate_info.restype = i
+        L.xl_plan_select_candidate.argtypes = [vp, i, i, i]
+        L.xl_plan_select_candidate.restype = i
         L.xl_version.argtypes = []
         L.xl_version.restype = ctypes.c_char_p
         _lib = L
@@ -212,6 +231,17 @@ class Plan:
 
     def num_launches(self, fused: bool) -> int:
         return lib().xl_plan_num_launches(self.handle, int(fused))
+
+    def num_candidates(self, fused: bool, launch: int) -> int:
+        return lib().xl_plan_num_candidates(self.handle, int(fused), launch)
+
+    def candidate_info(self, fused: bool, launch: int, candidate: int = -1) -> dict:
+        info = xl_launch_info()
+        self._check(lib().xl_plan_candidate_info(self.handle, int(fused), launch, candidate, ctypes.byref(info)))
+        return info.as_dict()
+
+    def select_candidate(self, fused: bool, launch: int, candidate: int):
+        self._check(lib().xl_plan_select_candidate(self.handle, int(fused), launch, candidate))
 
     def prepare(self, weight_ptrs: Sequence[Optional[int]], workspace_ptr: int, stream: int = 0):
         arr = (ctypes.c_void_p * self.nweights)(*[ctypes.c_void_p(p) if p else None for p in weight_ptrs])

@@ -16,6 +16,16 @@ int required_extent(int t, int k, int s);
 }  // namespace xl
 
 static thread_local std::string g_create_error;
+// xl_run leaves the plan untouched: the message of a failed run lives with the calling thread
+static thread_local std::string g_run_error;
+static thread_local const xl_plan *g_run_error_plan = nullptr;
+
+static xl_status run_fail(const xl_plan *plan, xl_status st, const std::string &msg)
+{
+    g_run_error = msg;
+    g_run_error_plan = plan;
+    return st;
+}
 
 static constexpr int GFX950_LDS_BYTES = 160 * 1024;
 static constexpr int GFX950_CUS = 256;
@@ -41,7 +51,12 @@ const char *xl_strerror(xl_status st)
     return "unknown status";
 }
 
-const char *xl_plan_last_error(const xl_plan *plan) { return plan ? plan->error.c_str() : g_create_error.c_str(); }
+const char *xl_plan_last_error(const xl_plan *plan)
+{
+    if (!plan) return g_create_error.c_str();
+    if (g_run_error_plan == plan && !g_run_error.empty()) return g_run_error.c_str();
+    return plan->error.c_str();
+}
 
 int xl_tuner_candidates(int out_size, int *tile, int *grid, int cap) { return xl::tuner_candidates(out_size, tile, grid, cap); }
 
@@ -115,6 +130,14 @@ int xl_plan_num_launches(const xl_plan *plan, int fused)
     return (int)(fused ? plan->fused_steps.size() : plan->unfused_steps.size());
 }
 
+// The plan was sized for one device (compute units, LDS): that device must be the current one.
+static bool on_plan_device(const xl_plan *plan)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    return plan->device < 0 || dev == plan->device;
+}
+
 static xl_status configure_once(xl_plan *plan)
 {
     static std::mutex mu;
@@ -122,6 +145,10 @@ static xl_status configure_once(xl_plan *plan)
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
         plan->error = "no current HIP device";
+        return XL_E_DEVICE;
+    }
+    if (!on_plan_device(plan)) {
+        plan->error = "the plan was made for device " + std::to_string(plan->device) + ", which is not the current device";
         return XL_E_DEVICE;
     }
     std::lock_guard<std::mutex> lock(mu);
@@ -192,15 +219,15 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, vo
             return XL_E_LAUNCH;
         }
     }
-    plan->prepared_ws = workspace;
+    plan->prepared.insert(workspace);
+    plan->error.clear();
     return XL_OK;
 }
 
-// Enqueue one step.  Shared by xl_run and xl_tune.
+// Enqueue one step.  Shared by xl_run and xl_tune.  Failures are reported through run_fail.
 static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void *const *tensors, char *ws,
                              hipStream_t s)
 {
-    xl_plan *mp = const_cast<xl_plan *>(plan);       // only the error string is written
     if (plan->shapes[st.x_id].n == 0) return XL_OK;  // empty batch: nothing to do, pointers may be NULL
     auto base = [&](int t) -> char * {
         const xl::Storage &sg = plan->storage[t];
@@ -208,24 +235,19 @@ static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void
         return ws + sg.offset;
     };
     char *x = base(st.x_id), *y = base(st.y_id);
-    if (!x || !y) {
-        mp->error = "a graph input or output pointer is NULL";
-        return XL_E_NULL;
-    }
-    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) % 16) {
-        mp->error = "tensor pointers must be 16-byte aligned";
-        return XL_E_ALIGN;
-    }
+    char *sc = st.type == xl::STEP_BLOCK && st.sc_id >= 0 ? base(st.sc_id) : x;
+    char *b = st.type == xl::STEP_ADD ? base(st.b_id) : x;
+    if (!x || !y || !sc || !b) return run_fail(plan, XL_E_NULL, "a graph input or output pointer is NULL");
+    // every tensor is read and written with 16-byte accesses
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(sc) |
+         reinterpret_cast<uintptr_t>(b)) % 16)
+        return run_fail(plan, XL_E_ALIGN, "tensor pointers must be 16-byte aligned");
     hipError_t e = hipSuccess;
     if (st.type == xl::STEP_BLOCK) {
         xl::BlockParams p = st.bp;
         p.x = reinterpret_cast<const float *>(x);
         p.y = reinterpret_cast<float *>(y);
-        p.sc = nullptr;
-        if (st.sc_id >= 0) {
-            p.sc = reinterpret_cast<const float *>(base(st.sc_id));
-            if (!p.sc) return XL_E_NULL;
-        }
+        p.sc = st.sc_id >= 0 ? reinterpret_cast<const float *>(sc) : nullptr;
         xl::ConvW *cw[4] = {&p.c1, &p.c2[0], &p.c2[1], &p.c1b};
         for (int i = 0; i < 4; ++i) {
             if (st.conv_layer[i] < 0) continue;
@@ -238,12 +260,8 @@ static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void
         e = xl::launch_maxpool(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N, st.C, st.H,
                                st.W, st.Ho, st.Wo, st.k, st.stride, st.pad, ys.ctot, ys.coff, s);
     } else if (st.type == xl::STEP_ADD) {
-        char *b = base(st.b_id);
-        if (!b) return XL_E_NULL;
-        if (plan->storage[st.y_id].root != st.y_id) {
-            mp->error = "add writing into a concat slice is not supported";
-            return XL_E_UNSUPPORTED;
-        }
+        if (plan->storage[st.y_id].root != st.y_id)
+            return run_fail(plan, XL_E_UNSUPPORTED, "add writing into a concat slice is not supported");
         e = xl::launch_add(reinterpret_cast<const float *>(x), reinterpret_cast<const float *>(b),
                            reinterpret_cast<float *>(y), st.count, st.relu, s);
     } else if (st.type == xl::STEP_DEPTHWISE) {
@@ -254,50 +272,152 @@ static xl_status launch_step(const xl_plan *plan, const xl::Step &st, const void
                                  reinterpret_cast<const xl::f32x4 *>(ws + pf.aff_offset), st.N, st.C, st.H, st.W, st.Ho,
                                  st.Wo, st.k, st.stride, st.pad, st.relu, ys.ctot, ys.coff, s);
     } else if (st.type == xl::STEP_GAP) {
-        if (plan->storage[st.y_id].root != st.y_id) {
-            mp->error = "global pooling writing into a concat slice is not supported";
-            return XL_E_UNSUPPORTED;
-        }
+        if (plan->storage[st.y_id].root != st.y_id)
+            return run_fail(plan, XL_E_UNSUPPORTED, "global pooling writing into a concat slice is not supported");
         e = xl::launch_gap(reinterpret_cast<const float *>(x), reinterpret_cast<float *>(y), st.N * st.C,
                            st.H * st.W, s);
     }
-    if (e != hipSuccess) {
-        mp->error = std::string("kernel launch failed: ") + hipGetErrorString(e);
-        return XL_E_LAUNCH;
-    }
+    if (e != hipSuccess) return run_fail(plan, XL_E_LAUNCH, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return XL_OK;
+}
+
+static xl_status check_run_args(const xl_plan *plan, const void *const *tensors, int ntensors, const void *workspace)
+{
+    if (!plan || !tensors || !workspace) return XL_E_NULL;
+    if (!plan->prepared.count(workspace)) return run_fail(plan, XL_E_STATE, "xl_prepare has not been called for this workspace");
+    if (ntensors < (int)plan->shapes.size()) return run_fail(plan, XL_E_GRAPH, "the tensors array is shorter than the plan's tensor list");
+    if (!on_plan_device(plan)) return run_fail(plan, XL_E_DEVICE, "the plan's device is not the current device");
     return XL_OK;
 }
 
 xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors, void *workspace, void *stream,
                  int fused)
 {
-    if (!plan || !tensors || !workspace) return XL_E_NULL;
-    if (plan->prepared_ws != workspace) return XL_E_STATE;
-    if (ntensors < (int)plan->shapes.size()) return XL_E_GRAPH;
+    xl_status rc = check_run_args(plan, tensors, ntensors, workspace);
+    if (rc != XL_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
     for (const xl::Step &st : steps) {
-        xl_status rc = launch_step(plan, st, tensors, ws, s);
+        rc = launch_step(plan, st, tensors, ws, s);
         if (rc != XL_OK) return rc;
     }
     return XL_OK;
 }
 
+// Make candidate `idx` the configuration of step `st`; in the fused path the block's reported tiles follow.
+static void adopt(xl_plan *plan, xl::Step &st, int idx, bool fused)
+{
+    std::vector<xl::Step> alts;
+    std::vector<xl_group_info> infos;
+    alts.swap(st.alts);
+    infos.swap(st.alt_info);
+    const int group = st.group, first_layer = st.first_layer, nlayers = st.nlayers;
+    st = alts[idx];
+    st.group = group;
+    st.first_layer = first_layer;
+    st.nlayers = nlayers;
+    st.adopted = idx;
+    st.alts.swap(alts);
+    st.alt_info.swap(infos);
+    if (fused && group >= 0 && group < (int)plan->groups.size()) {
+        xl_group_info &gi = plan->groups[group].info;
+        const xl_group_info &src = st.alt_info[idx];
+        gi.tile_h = src.tile_h; gi.tile_w = src.tile_w;
+        gi.mid_h = src.mid_h; gi.mid_w = src.mid_w;
+        gi.in_h = src.in_h; gi.in_w = src.in_w;
+        gi.tiles_y = src.tiles_y; gi.tiles_x = src.tiles_x;
+        gi.cout_split = src.cout_split; gi.workgroups = src.workgroups;
+        gi.threads = src.threads; gi.lds_bytes = src.lds_bytes;
+        gi.workgroups_per_cu = src.workgroups_per_cu; gi.chunk_channels = src.chunk_channels;
+        gi.flops_executed = src.flops_executed; gi.redundancy = src.redundancy;
+        gi.precision = src.precision;
+    }
+}
+
+static const xl::Step *find_launch(const xl_plan *plan, int fused, int launch)
+{
+    if (!plan) return nullptr;
+    const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
+    if (launch < 0 || launch >= (int)steps.size()) return nullptr;
+    return &steps[launch];
+}
+
+int xl_plan_num_candidates(const xl_plan *plan, int fused, int launch)
+{
+    const xl::Step *st = find_launch(plan, fused, launch);
+    if (!st) return 0;
+    return st->alts.empty() ? 1 : (int)st->alts.size();
+}
+
+xl_status xl_plan_candidate_info(const xl_plan *plan, int fused, int launch, int candidate, xl_launch_info *out)
+{
+    if (!plan || !out) return XL_E_NULL;
+    const xl::Step *st = find_launch(plan, fused, launch);
+    if (!st) return XL_E_GRAPH;
+    const int n = st->alts.empty() ? 1 : (int)st->alts.size();
+    if (candidate < -1 || candidate >= n) return XL_E_GRAPH;
+    if (candidate < 0) candidate = st->adopted;
+    const xl::Step &c = st->alts.empty() ? *st : st->alts[candidate];
+    memset(out, 0, sizeof *out);
+    out->group = fused ? st->group : -1;
+    out->first_layer = st->first_layer;
+    out->nlayers = st->nlayers;
+    out->candidate = candidate;
+    out->is_block_kernel = c.type == xl::STEP_BLOCK ? 1 : 0;
+    if (c.type == xl::STEP_BLOCK) {
+        const xl::BlockParams &p = c.bp;
+        const bool pooled = p.pth > 0;
+        out->variant = c.variant;
+        out->tile_h = pooled ? p.pth : p.th;
+        out->tile_w = pooled ? p.ptw : p.tw;
+        out->threads = c.threads;
+        out->cout_split = p.csplit;
+        out->waves_cout_1 = p.waves_r1;
+        out->waves_cout_2 = p.waves_r2;
+        out->lds_bytes = c.lds_bytes;
+        out->workgroups = p.nblocks;
+        out->model_cost_us = c.cost_us;
+        if (!st->alt_info.empty()) {
+            out->chunk_channels = st->alt_info[candidate].chunk_channels;
+            out->precision = st->alt_info[candidate].precision;
+        }
+    }
+    return XL_OK;
+}
+
+xl_status xl_plan_select_candidate(xl_plan *plan, int fused, int launch, int candidate)
+{
+    if (!plan) return XL_E_NULL;
+    std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
+    if (launch < 0 || launch >= (int)steps.size()) return XL_E_GRAPH;
+    xl::Step &st = steps[launch];
+    const int n = st.alts.empty() ? 1 : (int)st.alts.size();
+    if (candidate < 0 || candidate >= n) return XL_E_GRAPH;
+    if (!st.alts.empty()) adopt(plan, st, candidate, fused != 0);
+    return XL_OK;
+}
+
 xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void *workspace, void *stream, int reps)
 {
-    if (!plan || !tensors || !workspace) return XL_E_NULL;
-    if (plan->prepared_ws != workspace) return XL_E_STATE;
-    if (ntensors < (int)plan->shapes.size()) return XL_E_GRAPH;
-    if (reps < 1) reps = 3;
+    xl_status rc = check_run_args(plan, tensors, ntensors, workspace);
+    if (rc != XL_OK) {
+        if (plan) plan->error = g_run_error;
+        return rc;
+    }
+    if (reps < 5) reps = 5;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+    if (hipEventCreate(&e0) != hipSuccess) {
         plan->error = "cannot create timing events";
         return XL_E_DEVICE;
     }
-    xl_status rc = XL_OK;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        plan->error = "cannot create timing events";
+        return XL_E_DEVICE;
+    }
     for (int pass = 0; pass < 2 && rc == XL_OK; ++pass) {
         std::vector<xl::Step> &steps = pass == 0 ? plan->fused_steps : plan->unfused_steps;
         for (xl::Step &st : steps) {
@@ -307,80 +427,54 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
                 if (rc != XL_OK) break;
                 continue;
             }
-            // first a quick look at every candidate (best of 3), then the 6 fastest again with more repetitions
-            auto time_alt = [&](size_t a, int n, float &t_min) {
-                t_min = 1e30f;
+            // n timed launches of one candidate, sorted
+            auto time_alt = [&](size_t a, int n, std::vector<float> &t) {
+                t.clear();
                 for (int r = 0; r < n && rc == XL_OK; ++r) {
                     (void)hipEventRecord(e0, s);
                     rc = launch_step(plan, st.alts[a], tensors, ws, s);
                     (void)hipEventRecord(e1, s);
                     if (hipEventSynchronize(e1) != hipSuccess) {
-                        plan->error = "a candidate kernel failed while tuning";
-                        rc = XL_E_LAUNCH;
+                        if (rc == XL_OK) rc = run_fail(plan, XL_E_LAUNCH, "a candidate kernel failed while tuning");
                         break;
                     }
                     float ms = 0.f;
                     (void)hipEventElapsedTime(&ms, e0, e1);
-                    t_min = ms < t_min ? ms : t_min;
+                    t.push_back(ms);
                 }
+                std::sort(t.begin(), t.end());
             };
+            // a quick look at every candidate (fastest of 3 after a warm-up launch) ...
             std::vector<std::pair<float, int>> quick;
+            std::vector<float> t;
             for (size_t a = 0; a < st.alts.size() && rc == XL_OK; ++a) {
                 rc = launch_step(plan, st.alts[a], tensors, ws, s);         // warm-up (code, filters in L2)
                 if (rc != XL_OK) break;
-                float t;
                 time_alt(a, 3, t);
-                quick.push_back({t, (int)a});
-#ifdef XL_DEV_HOOKS     // development builds only: one line per candidate
-                if (std::getenv("XL_TUNE_LOG")) {
-                    const xl::Step &c = st.alts[a];
-                    fprintf(stderr, "[tune] pass %d group %d alt %zu variant %d thr %d tile %dx%d lds %d chunk %d/%d/%d wr %d/%d cs %d vw %d: %.1f us\n",
-                            pass, st.group, a, c.variant, c.threads, c.bp.th, c.bp.tw, c.lds_bytes, c.bp.chunk_kg,
-                            c.bp.chunk_kg2[0], c.bp.chunk_kg2[1], c.bp.waves_r1, c.bp.waves_r2, c.bp.csplit, c.bp.vw2, t * 1e3f);
-                }
-#endif
+                if (rc == XL_OK) quick.push_back({t.front(), (int)a});
             }
+            // ... then the six fastest again, ranked by the median of `reps` launches (ties: lower index)
             int best = 0;
             float best_ms = 1e30f;
             if (rc == XL_OK) {
                 std::sort(quick.begin(), quick.end());
                 for (size_t i = 0; i < quick.size() && i < 6 && rc == XL_OK; ++i) {
-                    float t;
                     time_alt((size_t)quick[i].second, reps, t);
-                    if (t < best_ms) {
-                        best_ms = t;
+                    if (rc != XL_OK) break;
+                    const float med = t[t.size() / 2];
+                    if (med < best_ms || (med == best_ms && quick[i].second < best)) {
+                        best_ms = med;
                         best = quick[i].second;
                     }
                 }
             }
             if (rc != XL_OK) break;
-            // adopt the winner (keep the candidate list for a later re-tune)
-            std::vector<xl::Step> alts;
-            std::vector<xl_group_info> infos;
-            alts.swap(st.alts);
-            infos.swap(st.alt_info);
-            const int group = st.group;
-            st = alts[best];
-            st.group = group;
-            st.alts.swap(alts);
-            st.alt_info.swap(infos);
-            if (pass == 0 && group >= 0 && group < (int)plan->groups.size()) {
-                xl_group_info &gi = plan->groups[group].info;
-                const xl_group_info &src = st.alt_info[best];
-                gi.tile_h = src.tile_h; gi.tile_w = src.tile_w;
-                gi.mid_h = src.mid_h; gi.mid_w = src.mid_w;
-                gi.in_h = src.in_h; gi.in_w = src.in_w;
-                gi.tiles_y = src.tiles_y; gi.tiles_x = src.tiles_x;
-                gi.cout_split = src.cout_split; gi.workgroups = src.workgroups;
-                gi.threads = src.threads; gi.lds_bytes = src.lds_bytes;
-                gi.workgroups_per_cu = src.workgroups_per_cu; gi.chunk_channels = src.chunk_channels;
-                gi.flops_executed = src.flops_executed; gi.redundancy = src.redundancy;
-                gi.precision = src.precision;
-            }
+            adopt(plan, st, best, pass == 0);
         }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
+    if (rc != XL_OK) plan->error = g_run_error;
     return rc;
 }
 

@@ -22,32 +22,13 @@
 // is exactly one float4 of the LDS tile layout.
 #include <float.h>
 
+#include <tuple>
 #include <type_traits>
 
 #include "xl_internal.h"
 
 namespace xl {
 
-// Development aid: per-workgroup phase timestamps (only in builds with -DXL_PHASE_TIMING).
-#ifdef XL_PHASE_TIMING
-#ifdef XL_TU_B3     // the reader below sees the fp32 translation unit's copy only
-static
-#endif
-__device__ unsigned long long g_phase[16 * 8192];
-#ifdef XL_TU_B3
-static
-#endif
-__device__ unsigned long long g_wtrace[8 * 8 * 16 * 4];     // [block][wave][chunk][stamp], stage-1 pass
-#define XL_PHASE(L, i)                                                        \
-    do {                                                                      \
-        if (threadIdx.x == 0 && (L) < 8192) {                                 \
-            g_phase[(L) * 16 + (i)] = clock64();                              \
-            g_phase[(L) * 16 + 8 + (i)] = wall_clock64();                     \
-        }                                                                     \
-    } while (0)
-#else
-#define XL_PHASE(L, i) do { } while (0)
-#endif
 
 // ----------------------------------------------------------------------------
 // matrix-core wrappers
@@ -551,9 +532,6 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     };
 
     const int nchunks = (c.nkg + g.chunk_kg - 1) / g.chunk_kg;
-#ifdef XL_PHASE_TIMING
-    long long t_ld = 0, t_mm = 0, t_st = 0, t_pro = clock64();
-#endif
     // The input runs two chunks ahead in registers: the units of chunk i + 1 are written to LDS at the
     // start of chunk i, by the few waves that own units, while the other wave of their SIMD already
     // streams matrix operations (vector ALU work squeezed in after a wave's own matrix operations would
@@ -569,23 +547,12 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
         float *nxt = buf + ((ch + 1) & 1) * g.buf_stride;
         const bool more = ch + 1 < nchunks;
         const int kg0 = ch * g.chunk_kg;
-#ifdef XL_PHASE_TIMING
-        if (ch == 0) t_pro = clock64() - t_pro;
-        long long t0 = clock64();
-        const int wt_b = logical_block();
-        const bool wt_on = STAGE_X && wt_b < 8 && ch < 16 && (threadIdx.x & 63) == 0;
-        unsigned long long *wt = g_wtrace + ((wt_b * 8 + (threadIdx.x >> 6)) * 16 + ch) * 4;
-        if (wt_on) wt[0] = t0;
-#endif
         const int c_next = (kg0 + g.chunk_kg) * M::KC;
         if (more) {
             store_x(nxt, c_next);
             load_w(nxt + g.w_off, kg0 + g.chunk_kg);
             if (ch + 2 < nchunks) load_x(c_next + g.chunk_kg * M::KC);
         }
-#ifdef XL_PHASE_TIMING
-        long long t1 = clock64();
-#endif
         const int nkg = min(g.chunk_kg, c.nkg - kg0);
         if (g.active) {
             const float *bs = STAGE_X ? cur : bsrc + kg0 * (M::GPS * g.gstride);
@@ -594,33 +561,9 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
             else
                 conv_accum<MF, KS, NRT, NPT>(acc, bs, off, g.src_w, g.gstride, cur + g.w_off, rloc, g.wg_rt, nkg);
         }
-#ifdef XL_PHASE_TIMING
-        long long t2 = clock64();
-        if (wt_on) wt[1] = t2;
-#endif
-#ifdef XL_PHASE_TIMING
-        if (wt_on) wt[2] = clock64();
-#endif
         __builtin_amdgcn_s_waitcnt(0);
-#ifdef XL_PHASE_TIMING
-        if (wt_on) wt[3] = clock64();
-#endif
         __syncthreads();
-#ifdef XL_PHASE_TIMING
-        long long t3 = clock64();
-        t_ld += t1 - t0; t_mm += t2 - t1; t_st += t3 - t2;
-#endif
     }
-#ifdef XL_PHASE_TIMING
-    if (threadIdx.x == 0 && STAGE_X) {
-        const int Lb = logical_block();
-        if (Lb < 8192) { g_phase[Lb * 16 + 4] = t_pro; g_phase[Lb * 16 + 5] = t_ld; g_phase[Lb * 16 + 6] = t_mm; g_phase[Lb * 16 + 7] = t_st; }
-    }
-    if (threadIdx.x == 0 && !STAGE_X && KS == 3) {
-        const int Lb = logical_block();
-        if (Lb < 8192) { g_phase[Lb * 16 + 12] = t_pro; g_phase[Lb * 16 + 13] = t_ld; g_phase[Lb * 16 + 14] = t_mm; g_phase[Lb * 16 + 15] = t_st; }
-    }
-#endif
 }
 
 // The per-channel scale and shift (folded BN, bias) cost the epilogues nothing: xl_prepare multiplies
@@ -1130,10 +1073,8 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
         }
     }
     init_acc<MF1, NRT1, NPT1>(acc, P.c1, rt0);
-    XL_PHASE(L, 0);
     conv_pass<MF1, K1, NRT1, NPT1, true, PX1, PR>(acc, P, P.c1, g1, nullptr, off1, buf, ximg,
                                                   (unsigned long long)(P.N - n) * P.Cin * P.H * P.W * 4ull, iy0, ix0);
-    XL_PHASE(L, 1);
 
     if constexpr (KIND == KIND_SINGLE) {
         if (P.gap) {
@@ -1165,7 +1106,6 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
     if constexpr (KIND != KIND_SINGLE) {
         // ---- S3: barrier between producing and consuming the LDS tile
         __syncthreads();
-        XL_PHASE(L, 2);
 
         if constexpr (KIND == KIND_POOL) {
             // ---- S4/S5: max pooling from the LDS tile; one float4 (4 channels of one pixel) per item
@@ -1227,13 +1167,7 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                             const int oy = min(oyu, P.th - 1), ox = min(pidx - oyu * P.vw2, P.tw - 1);
                             off2[p] = ((oy * P.s2 + d) * P.mw + ox * P.s2 + d) * 4 + sub * SUBP * P.mid_gstride;
                         }
-#ifdef XL_PHASE_TIMING
-                        if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 0] = clock64();
-#endif
                         conv_pass<MF2, KS2, NRT2, NPT2, false, 0, PR>(acc2, P, c, g2, mid, off2, buf, nullptr, 0ull, 0, 0);
-#ifdef XL_PHASE_TIMING
-                        if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 1] = clock64();
-#endif
                         if constexpr (KIND == KIND_FUSED2P) {
                             // the pass covers every pixel of the tile (planner): its result goes to an LDS tile
                             // over the staging buffers, which no wave reads any more, and is pooled from there
@@ -1266,16 +1200,12 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                         } else if (g2.active)
                             store_global<MF2, NRT2, NPT2, SC>(acc2, P, c, coff, n, oy0, ox0, P.th, P.tw, P.vw2, r0, rte,
                                                               p0, P.relu_out, P.rcp_vw2);
-#ifdef XL_PHASE_TIMING
-                        if (L < 8 && (threadIdx.x & 63) == 0) g_wtrace[((L * 8 + (threadIdx.x >> 6)) * 16 + 15) * 4 + 2] = clock64();
-#endif
                     }
                 }
             };
             run_conv(std::integral_constant<int, K2A>{}, P.c2[0], P.coff2[0], P.chunk_kg2[0]);
             if constexpr (K2B != 0) run_conv(std::integral_constant<int, K2B>{}, P.c2[1], P.coff2[1], P.chunk_kg2[1]);
         }
-        XL_PHASE(L, 3);
     }
 }
 
@@ -1299,6 +1229,7 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
     typedef MM<MF1> M1;
     typedef unsigned u32x4 __attribute__((vector_size(16)));
     constexpr int T = K1 * K1;
+    static_assert(STAGE_UNITS == 1, "every thread of the stream kernel stages exactly one input unit per tile");
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *mid = lds;
     float *xbuf = lds + P.lds_buf_off;
@@ -1521,6 +1452,18 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
 // ----------------------------------------------------------------------------
 // launch table
 // ----------------------------------------------------------------------------
+// Launches through hipLaunchKernel, whose return value is the status of this launch alone (the
+// "last error" of the runtime may hold a failure of the caller's own earlier calls).
+template <typename... Params, typename... Args>
+static hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds, hipStream_t s, Args... args)
+{
+    std::tuple<Params...> values{static_cast<Params>(args)...};
+    void *argv[sizeof...(Params)];
+    int i = 0;
+    std::apply([&](auto &...v) { ((argv[i++] = (void *)&v), ...); }, values);
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, lds, s);
+}
+
 // This file is compiled twice: once for the fp32 variants and everything else, and once with
 // XL_TU_B3 defined for the split-bf16 variants alone (the two halves build in parallel).
 typedef void (*BlockKernel)(const BlockParams);
@@ -1562,21 +1505,6 @@ static BlockKernel kernel_of(int variant)
     return kernel_of_b3(variant);
 }
 
-const std::vector<Variant> &variants()
-{
-    static const std::vector<Variant> v = {
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1) \
-    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1, 0},
-        XL_VARIANT_LIST(X)
-#undef X
-#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1) \
-    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1, 1},
-        XL_VARIANT_LIST_B3(X)
-#undef X
-    };
-    return v;
-}
-
 hipError_t configure_kernels(int max_lds_bytes)
 {
     for (const Variant &v : variants()) {
@@ -1594,8 +1522,7 @@ hipError_t launch_block(int variant, const BlockParams &p, int threads, size_t l
     if (p.nblocks <= 0) return hipSuccess;
     int grid = (p.nblocks + 7) / 8 * 8;
     if (p.stream_wgs > 0) grid = std::min(grid, (p.stream_wgs + 7) / 8 * 8);     // resident workgroups walking the tiles
-    hipLaunchKernelGGL(k, dim3(grid), dim3(threads), lds_bytes, s, p);
-    return hipGetLastError();
+    return launch(k, dim3(grid), dim3(threads), lds_bytes, s, p);
 }
 
 // ----------------------------------------------------------------------------
@@ -1673,10 +1600,8 @@ hipError_t launch_pack_filter(const float *w, const float *scale, f32x4 *wp, int
     const int threads = 256;
     const int grid = (int)((total + threads - 1) / threads);
     if (pr)
-        hipLaunchKernelGGL(pack_filter_b3_kernel, dim3(grid), dim3(threads), 0, s, w, scale, (uint4 *)wp, cout, cin, k, mf, nkg, nrt);
-    else
-        hipLaunchKernelGGL(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, scale, wp, cout, cin, k, mf, nkg, nrt, pairs);
-    return hipGetLastError();
+        return launch(pack_filter_b3_kernel, dim3(grid), dim3(threads), 0, s, w, scale, (uint4 *)wp, cout, cin, k, mf, nkg, nrt);
+    return launch(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, scale, wp, cout, cin, k, mf, nkg, nrt, pairs);
 }
 
 // shift in accumulator order: [row tile][quad][lane] float4 (the scale goes into the filter)
@@ -1700,8 +1625,7 @@ __global__ void pack_affine_kernel(const float *__restrict__ shift, f32x4 *__res
 hipError_t launch_pack_affine(const float *shift, f32x4 *out, int cout, int mf, int nrt, hipStream_t s)
 {
     const int total = nrt * (mf == 32 ? 4 : 1) * 64;
-    hipLaunchKernelGGL(pack_affine_kernel, dim3((total + 255) / 256), dim3(256), 0, s, shift, out, cout, mf, nrt);
-    return hipGetLastError();
+    return launch(pack_affine_kernel, dim3((total + 255) / 256), dim3(256), 0, s, shift, out, cout, mf, nrt);
 }
 
 // ----------------------------------------------------------------------------
@@ -1774,15 +1698,13 @@ hipError_t launch_maxpool(const float *x, float *y, int N, int C, int H, int W, 
     const int threads = 256;
     const size_t plane_bytes = (size_t)H * W * 4;
     if (plane_bytes <= 64 * 1024) {
-        hipLaunchKernelGGL(maxpool_plane_kernel, dim3(N * C), dim3(threads), (plane_bytes + 15) / 16 * 16, s, x, y, C, H,
+        return launch(maxpool_plane_kernel, dim3(N * C), dim3(threads), (plane_bytes + 15) / 16 * 16, s, x, y, C, H,
                            W, Ho, Wo, k, stride, pad, Cy, coff);
-        return hipGetLastError();
     }
     const int pix_blocks = (Ho * Wo + threads - 1) / threads;
     if (pix_blocks > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(maxpool_kernel, dim3(N * C, pix_blocks), dim3(threads), 0, s, x, y, C, H, W, Ho, Wo, k, stride,
+    return launch(maxpool_kernel, dim3(N * C, pix_blocks), dim3(threads), 0, s, x, y, C, H, W, Ho, Wo, k, stride,
                        pad, Cy, coff);
-    return hipGetLastError();
 }
 
 __global__ void add_kernel(const float *__restrict__ a, const float *__restrict__ b, float *__restrict__ y,
@@ -1811,9 +1733,8 @@ hipError_t launch_add(const float *a, const float *b, float *y, long long count,
     if (count == 0) return hipSuccess;
     const int threads = 256;
     const long long work = (count >> 2) + 1;
-    hipLaunchKernelGGL(add_kernel, dim3((unsigned)((work + threads - 1) / threads)), dim3(threads), 0, s, a, b, y, count,
+    return launch(add_kernel, dim3((unsigned)((work + threads - 1) / threads)), dim3(threads), 0, s, a, b, y, count,
                        relu);
-    return hipGetLastError();
 }
 
 // one wavefront per (image, channel): mean over H*W
@@ -1835,8 +1756,7 @@ hipError_t launch_gap(const float *x, float *y, int NC, int HW, hipStream_t s)
     if (NC == 0) return hipSuccess;
     const int threads = 256;
     const int wpb = threads / 64;
-    hipLaunchKernelGGL(gap_kernel, dim3((NC + wpb - 1) / wpb), dim3(threads), 0, s, x, y, NC, HW);
-    return hipGetLastError();
+    return launch(gap_kernel, dim3((NC + wpb - 1) / wpb), dim3(threads), 0, s, x, y, NC, HW);
 }
 
 // ----------------------------------------------------------------------------
@@ -1874,9 +1794,8 @@ hipError_t launch_pack_depthwise(const float *w, const float *scale, const float
                                  int k, hipStream_t s)
 {
     const int items = ((C + 3) / 4) * k * k;
-    hipLaunchKernelGGL(pack_depthwise_kernel, dim3((items + 255) / 256), dim3(256), 0, s, w, scale, shift, wp, aff, C,
+    return launch(pack_depthwise_kernel, dim3((items + 255) / 256), dim3(256), 0, s, w, scale, shift, wp, aff, C,
                        k * k);
-    return hipGetLastError();
 }
 
 // one thread per output element; consecutive threads run along W
@@ -1916,23 +1835,11 @@ hipError_t launch_depthwise(const float *x, float *y, const f32x4 *wp, const f32
     if (total == 0) return hipSuccess;
     const long long blocks = (total + 255) / 256;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(depthwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, y, wp, aff, C, H, W, Ho, Wo, k, stride,
+    return launch(depthwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, y, wp, aff, C, H, W, Ho, Wo, k, stride,
                        pad, relu, Cy, coff, total);
-    return hipGetLastError();
 }
 
 #endif  // XL_TU_B3
 
 }  // namespace xl
 
-#if defined(XL_PHASE_TIMING) && !defined(XL_TU_B3)
-extern "C" int xl_debug_read_wtrace(unsigned long long *host, int count)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(xl::g_wtrace), sizeof(unsigned long long) * count);
-}
-
-extern "C" int xl_debug_read_phases(unsigned long long *host, int count)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(xl::g_phase), sizeof(unsigned long long) * count);
-}
-#endif

@@ -13,6 +13,22 @@
 
 namespace xl {
 
+// The table of compiled kernel variants (the kernels themselves are instantiated from the same list).
+const std::vector<Variant> &variants()
+{
+    static const std::vector<Variant> v = {
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1) \
+    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1, 0},
+        XL_VARIANT_LIST(X)
+#undef X
+#define X(ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1) \
+    Variant{ID, KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1, 1},
+        XL_VARIANT_LIST_B3(X)
+#undef X
+    };
+    return v;
+}
+
 static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -221,10 +237,6 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     for (const Variant &v : variants()) {
         const bool stream = v.kind == KIND_POOLS;          // conv -> pool as a stream of tiles: same block kind
         if ((v.kind != b.kind && !(stream && b.kind == KIND_POOL)) || v.k1 != b.c1.k || v.pr != pr) continue;
-#ifdef XL_DEV_HOOKS     // development builds only: restrict the search to one kernel variant
-        if (const char *only = std::getenv("XL_ONLY_VARIANT"))
-            if (b.kind != KIND_SINGLE && std::atoi(only) != v.id) continue;
-#endif
         const bool dw = b.kind == KIND_DW;                  // depthwise stage 1: no matrix-core tiling of layer 1
         const bool pool2 = b.kind == KIND_FUSED2P;          // stage 2 is pooled before it is stored
         const bool two = b.kind == KIND_FUSED2 || dw || pool2;       // stage 2 runs convolutions from the LDS tile
@@ -325,9 +337,6 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                             // rows of a multiple of 4 pixels let the epilogue move 4 pixels per access
                             if (tw2 % 4 && (tw2 + 3) / 4 * 4 != vws.back()) vws.push_back((tw2 + 3) / 4 * 4);
                         }
-#ifdef XL_DEV_HOOKS
-                        if (const char *f = std::getenv("XL_FORCE_VW2")) vws.assign(1, std::max(tw2, std::atoi(f)));
-#endif
                     } else {
                         splits.push_back(b.kind == KIND_SINGLE ? ceil_div(nrt1, wg_rt) : 1);
                         wr2s.push_back(1);
@@ -654,6 +663,7 @@ struct Builder {
         st = Step{};
         st.type = STEP_BLOCK;
         st.variant = ch.v.id;
+        st.cost_us = ch.cost * 1e6;
         st.threads = ch.threads;
         st.lds_bytes = ch.lds_bytes;
         st.x_id = x_id;
@@ -956,6 +966,9 @@ struct Builder {
             if (!only_consumers(t_mid, {ids[1]}) || !only_consumers(L2.out, {ids[2]}))
                 return fail(XL_E_UNSUPPORTED, at + "an intermediate has a consumer outside the block");
             if (pl.storage[other].root != other) return fail(XL_E_UNSUPPORTED, at + "shortcut is a concat operand");
+            // the block runs where its first layer stands: whatever it reads from outside must exist by then
+            if (producer[other] >= ids[0])
+                return fail(XL_E_UNSUPPORTED, at + "the shortcut is produced after the block's first layer; list its producer before the block");
             b.kind = KIND_FUSED2;
             b.n2 = 1;
             conv_spec(ids[1], b.c2[0]);
@@ -1005,6 +1018,8 @@ struct Builder {
         if (s != XL_OK) return s;
         fill_info(gi, b, ch);
         st.group = (int)pl.groups.size();
+        st.first_layer = ids[0];
+        st.nlayers = (int)ids.size();
         pl.fused_steps.push_back(st);
         return XL_OK;
     }
@@ -1023,6 +1038,9 @@ struct Builder {
             Step st;
             s = single_step(li, st, nullptr);
             if (s != XL_OK) return s;
+            st.first_layer = li;
+            st.nlayers = 1;
+            for (Step &a : st.alts) a.first_layer = li;
             pl.unfused_steps.push_back(st);
         }
 
@@ -1060,6 +1078,8 @@ struct Builder {
                     s = single_step(li, st, &gp.info);
                     if (s != XL_OK) return s;
                     st.group = (int)pl.groups.size();
+                    st.first_layer = li;
+                    st.nlayers = 1;
                     pl.fused_steps.push_back(st);
                 }
             } else {

@@ -2,6 +2,7 @@
 // kernel for both execution modes.  Not part of the C ABI.
 #pragma once
 
+#include <set>
 #include <string>
 #include <vector>
 
@@ -51,6 +52,9 @@ struct Step {
     // tuning: the planner's ranked candidates for this block (alts[0] is the model's choice) with
     // the tile facts each would report, and the fusion block whose info the selection updates
     int group = -1;
+    int adopted = 0;        // index into alts of the configuration this step currently is
+    double cost_us = 0;     // the cost model's estimate
+    int first_layer = -1, nlayers = 1;
     std::vector<Step> alts;
     std::vector<xl_group_info> alt_info;
 };
@@ -76,7 +80,7 @@ struct xl_plan {
     int num_cus = 256;
     xl_options opts{};
     // bound by xl_prepare
-    const void *prepared_ws = nullptr;
+    std::set<const void *> prepared;                   // workspaces that hold this plan's re-laid-out filters
     std::vector<const float *> scale_ptr, shift_ptr;   // per layer
     std::string error;
 };

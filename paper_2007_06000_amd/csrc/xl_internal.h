@@ -93,7 +93,8 @@ struct BlockParams {
     int lds_buf_off;        // float offset of the two staging buffers in LDS (after the tile)
     int buf_stride;         // floats per staging buffer
     int w_off1;             // stage 1: float offset of the filter chunk inside a buffer (after the input chunk)
-    int stream_wgs;         // KIND_POOLS: workgroups to launch (each walks tiles L, L + stream_wgs, ...)
+    int stream_wgs;         // KIND_POOLS: resident workgroups wanted; the launch rounds it up to a multiple of 8 and
+                            // each workgroup walks tiles L, L + gridDim.x, ...
 };
 
 // A compiled kernel variant.

@@ -232,3 +232,72 @@ def test_split_block_followed_by_max_pooling_is_one_launch():
     # a padded pooling would need -inf padding inside the block: not fused
     with pytest.raises(B.XlError):
         B.Plan(W.split_fire_pool(n=1, hw=27, pp=1))
+
+
+def test_candidates_of_a_launch_can_be_listed_and_selected():
+    """Paper section 3.2: the tuner searches (tile, grid) candidates; the library shows and lets a caller
+    force each of them."""
+    p = B.Plan(W.config(3))
+    assert p.num_launches(True) == 1 and p.num_launches(False) == 3
+    n = p.num_candidates(True, 0)
+    assert 2 <= n <= 64
+    adopted = p.candidate_info(True, 0)
+    assert adopted["candidate"] == 0 and adopted["group"] == 0 and adopted["nlayers"] == 4 and adopted["is_block_kernel"] == 1
+    seen = set()
+    for c in range(n):
+        info = p.candidate_info(True, 0, c)
+        assert info["candidate"] == c and info["threads"] in (256, 512) and 0 < info["lds_bytes"] <= 160 * 1024
+        assert info["workgroups"] > 0 and info["tile_h"] >= 1 and info["tile_w"] >= 1
+        seen.add((info["variant"], info["threads"], info["tile_h"], info["tile_w"]))
+    assert len(seen) == n          # one candidate per (kernel variant, workgroup size, tile)
+    costs = [p.candidate_info(True, 0, c)["model_cost_us"] for c in range(n)]
+    assert costs[0] == min(costs)
+    last = p.candidate_info(True, 0, n - 1)
+    p.select_candidate(True, 0, n - 1)
+    now = p.candidate_info(True, 0)
+    assert now["candidate"] == n - 1 and now == last
+    q = p.query(0)
+    assert (q["tile_h"], q["tile_w"], q["threads"], q["lds_bytes"]) == (last["tile_h"], last["tile_w"], last["threads"], last["lds_bytes"])
+    # unfused launches are layers; their candidates do not touch the block's reported tiles
+    u = p.candidate_info(False, 1, 0)
+    assert u["group"] == -1 and u["first_layer"] == 1 and u["nlayers"] == 1
+    p.select_candidate(False, 1, p.num_candidates(False, 1) - 1)
+    assert p.query(0)["tile_h"] == last["tile_h"]
+    for bad in ((True, 1, 0), (True, 0, n), (False, 3, 0), (True, -1, 0)):
+        assert p.num_candidates(bad[0], bad[1]) == 0 or bad[2] >= p.num_candidates(bad[0], bad[1])
+        with pytest.raises(B.XlError) as e:
+            p.select_candidate(*bad)
+        assert e.value.status == B.XL_E_GRAPH
+
+
+def test_element_wise_launches_have_one_candidate():
+    p = B.Plan(W.config(4))
+    assert [p.num_candidates(False, l) for l in range(3)][2] == 1
+    info = p.candidate_info(False, 2)
+    assert info["is_block_kernel"] == 0 and info["first_layer"] == 2
+
+
+def test_blocks_cut_out_of_config5_plan_like_the_network_itself():
+    """The per-block GPU checks run every candidate on blocks cut out of config 5: their candidate lists must be
+    the ones the whole network's plan holds."""
+    full = W.config(5)
+    pf = B.Plan(full)
+    keys = ("variant", "tile_h", "tile_w", "threads", "cout_split", "waves_cout_1", "waves_cout_2", "chunk_channels",
+            "lds_bytes", "workgroups")
+    for launch in range(pf.num_launches(True)):
+        gi = pf.candidate_info(True, launch)["group"]
+        ps = B.Plan(W.subgraph(full, gi))
+        assert ps.num_candidates(True, 0) == pf.num_candidates(True, launch)
+        for c in range(ps.num_candidates(True, 0)):
+            a, b = ps.candidate_info(True, 0, c), pf.candidate_info(True, launch, c)
+            assert [a[k] for k in keys] == [b[k] for k in keys]
+
+
+def test_shortcut_produced_after_the_first_layer_of_a_merge_block_is_rejected():
+    """A fused block runs where its first layer stands; a shortcut computed by a layer listed later would be
+    read before it exists."""
+    with pytest.raises(B.XlError) as e:
+        B.Plan(W.merge_residual_projection(shortcut_first=False))
+    assert e.value.status == B.XL_E_UNSUPPORTED
+    p = B.Plan(W.merge_residual_projection(shortcut_first=True))
+    assert p.num_launches(True) == 2 and p.num_launches(False) == 4

@@ -197,6 +197,27 @@ def merge_residual(n: int = 32, c: int = 64, hw: int = 56) -> Workload:
     return b.done(t, "relu_normal", 1004)
 
 
+def merge_residual_projection(n: int = 2, cin: int = 32, c: int = 64, hw: int = 28, shortcut_first: bool = True) -> Workload:
+    """Residual block whose shortcut is a 1x1 projection of the block input (channel counts differ).
+    The projection is a layer outside the merge block; listed before the block (shortcut_first) the
+    block can read it, listed between the block's layers it is produced too late for a fused block."""
+    b = _Builder(f"merge_proj_{cin}_{c}x{hw}", n, cin, hw, hw)
+    if shortcut_first:
+        sc = b.conv(0, c, 1, bn=True, relu=False, name="projection")
+        first = len(b.layers)
+        t = b.conv(0, c, 3, pad=1, bn=True, relu=True, name="conv1")
+        t = b.conv(t, c, 3, pad=1, bn=True, relu=False, name="conv2")
+        t = b.add(t, sc, relu=True, name="add")
+        b.group("merge", first)
+    else:
+        t = b.conv(0, c, 3, pad=1, bn=True, relu=True, name="conv1")
+        t = b.conv(t, c, 3, pad=1, bn=True, relu=False, name="conv2")
+        sc = b.conv(0, c, 1, bn=True, relu=False, name="projection")
+        t = b.add(t, sc, relu=True, name="add")
+        b.groups.append(Group("merge", (0, 1, 3)))
+    return b.done(t, "relu_normal", 1014)
+
+
 def squeezenet11(n: int = 64, hw: int = 224, classes: int = 1000, fuse_stem: bool = True,
                  fuse_head: bool = True, fuse_pools: bool = True) -> Workload:
     """Config 5: SqueezeNet-v1.1-shaped network; 8 split-mode fire blocks (paper section 4.2).
