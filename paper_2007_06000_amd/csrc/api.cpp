@@ -198,6 +198,16 @@ xl_status xl_prepare(xl_plan *plan, const void *const *weights, int nweights, vo
     for (const xl::PackedFilter &p : plan->packed) {
         const xl_layer &L = plan->layers[p.layer];
         hipError_t e;
+        if (p.mf < 0) {
+            e = xl::launch_pack_thin(static_cast<const float *>(weights[L.w_slot]), plan->scale_ptr[p.layer],
+                                     plan->shift_ptr[p.layer], reinterpret_cast<float *>(ws + p.offset),
+                                     reinterpret_cast<float *>(ws + p.aff_offset), L.cout, L.cin * L.k * L.k, s);
+            if (e != hipSuccess) {
+                plan->error = std::string("filter re-layout launch failed: ") + hipGetErrorString(e);
+                return XL_E_LAUNCH;
+            }
+            continue;
+        }
         if (p.mf == 0) {
             e = xl::launch_pack_depthwise(static_cast<const float *>(weights[L.w_slot]), plan->scale_ptr[p.layer],
                                           plan->shift_ptr[p.layer], reinterpret_cast<xl::f32x4 *>(ws + p.offset),

@@ -1449,6 +1449,12 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
     }
 }
 
+}  // namespace xl
+#ifndef XL_TU_B3
+#include "thin_conv.h"
+#endif
+namespace xl {
+
 // ----------------------------------------------------------------------------
 // launch table
 // ----------------------------------------------------------------------------
@@ -1488,6 +1494,8 @@ static BlockKernel select_kernel()
 {
     if constexpr (KIND == KIND_POOLS)
         return pool_stream_kernel<MF1, K1, NRT1, NPT1, (PX1 < 0 ? -PX1 : 4)>;
+    else if constexpr (KIND == KIND_THIN)
+        return thin_conv_kernel<NRT1, K1, NPT1, K2A, K2B>;      // Cin, K, conv stride, pool window, pool stride
     else
         return block_kernel<KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1>;
 }
@@ -1602,6 +1610,13 @@ hipError_t launch_pack_filter(const float *w, const float *scale, f32x4 *wp, int
     if (pr)
         return launch(pack_filter_b3_kernel, dim3(grid), dim3(threads), 0, s, w, scale, (uint4 *)wp, cout, cin, k, mf, nkg, nrt);
     return launch(pack_filter_kernel, dim3(grid), dim3(threads), 0, s, w, scale, wp, cout, cin, k, mf, nkg, nrt, pairs);
+}
+
+hipError_t launch_pack_thin(const float *w, const float *scale, const float *shift, float *wp, float *aff, int cout,
+                            int taps, hipStream_t s)
+{
+    const int total = (cout + 63) / 64 * taps * 64;
+    return launch(pack_thin_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w, scale, shift, wp, aff, cout, taps);
 }
 
 // shift in accumulator order: [row tile][quad][lane] float4 (the scale goes into the filter)

@@ -235,6 +235,52 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     }
     bool any_lds_reject = false;
     for (const Variant &v : variants()) {
+        if (v.kind == KIND_THIN) {
+            // a first layer with a handful of input channels on the vector ALU, alone or with its max pooling
+            // (columns of the variant: nrt1 = Cin, npt1 = convolution stride, k2a / k2b = pooling window / stride)
+            const bool pooled = b.kind == KIND_POOL;
+            if (pr != 0 || !(pooled || (b.kind == KIND_SINGLE && !b.gap))) continue;
+            if (v.k1 != b.c1.k || v.nrt1 != b.c1.cin || v.npt1 != b.c1.stride) continue;
+            if (pooled ? (v.k2a != b.pool_k || v.k2b != b.pool_s) : (v.k2a != 1 || v.k2b != 1)) continue;
+            if (pl.opts.force_threads > 0 && pl.opts.force_threads != 256) continue;
+            std::vector<int> rows;
+            if (pl.opts.force_tile_h > 0) rows.push_back(std::min(pl.opts.force_tile_h, b.Ho));
+            else
+                for (int th : ths)
+                    if (th <= 32 || th == b.Ho) rows.push_back(th);
+            for (int th : rows) {
+                Choice c;
+                c.v = v;
+                c.threads = 256;
+                c.waves_r1 = c.waves_r2 = 1;
+                c.th = th;
+                c.tw = THIN_TILE_W;
+                c.vw2 = c.tw;
+                c.mh = (th - 1) * v.k2b + v.k2a;               // convolution outputs under the item's windows
+                c.mw = (c.tw - 1) * v.k2b + v.k2a;
+                c.ih = required_extent(c.mh, b.c1.k, b.c1.stride);
+                c.iw = required_extent(c.mw, b.c1.k, b.c1.stride);
+                c.tiles_y = ceil_div(b.Ho, th);
+                c.tiles_x = ceil_div(b.Wo, c.tw);
+                c.csplit = ceil_div(b.c1.cout, 64);             // groups of 64 output channels, one per wavefront item
+                c.chunk_kg = 1;
+                c.lds_bytes = 0;
+                c.occ = 4;
+                // one multiply-add instruction (4 cycles per wavefront) per filter value and convolution output;
+                // four wavefronts share a SIMD, 16 a compute unit
+                const double items = (double)c.tiles_x * c.tiles_y * c.csplit * b.N;
+                const double taps = (double)b.c1.cin * b.c1.k * b.c1.k;
+                const double item_clk = (double)c.mh * c.mw * (taps + 2.0) * 4.0 + 600.0;
+                const double t_alu = std::ceil(items / (pl.num_cus * 16.0)) * item_clk * 4.0 / 2.4e9;
+                const double t_mem = (double)b.alg_bytes / 8.0e12;
+                c.cost = std::max(t_alu, t_mem) + 0.15 * std::min(t_alu, t_mem);
+                c.flops_exec = (long long)(items * c.mh * c.mw * taps * 64.0 * 2.0);
+                c.ok = true;
+                if (!best.ok || c.cost < best.cost) best = c;
+                per_key[std::make_tuple(v.id, 256, th, c.tw)] = c;
+            }
+            continue;
+        }
         const bool stream = v.kind == KIND_POOLS;          // conv -> pool as a stream of tiles: same block kind
         if ((v.kind != b.kind && !(stream && b.kind == KIND_POOL)) || v.k1 != b.c1.k || v.pr != pr) continue;
         const bool dw = b.kind == KIND_DW;                  // depthwise stage 1: no matrix-core tiling of layer 1
@@ -592,7 +638,7 @@ struct Builder {
 
     int packed_index(int layer, int mf, bool pairs = false, int pr = 0)
     {
-        if (mf == 0) pr = 0;        // depthwise tables have one form
+        if (mf <= 0) pr = 0;        // depthwise and thin-layer tables have one form
         for (size_t i = 0; i < pl.packed.size(); ++i)
             if (pl.packed[i].layer == layer && pl.packed[i].mf == mf && pl.packed[i].pairs == pairs && pl.packed[i].pr == pr)
                 return (int)i;
@@ -602,7 +648,11 @@ struct Builder {
         p.mf = mf;
         p.pairs = pairs;
         p.pr = pr;
-        if (mf == 0) {      // depthwise: [channel group][tap] float4 and [channel group][scale, shift] float4
+        if (mf < 0) {       // thin first layer: [group of 64 channels][Cin*K*K][lane] floats and [group][lane] shifts
+            p.nkg = p.nrt = 0;
+            p.bytes = (size_t)ceil_div(L.cout, 64) * L.cin * L.k * L.k * 64 * 4;
+            p.aff_bytes = (size_t)ceil_div(L.cout, 64) * 64 * 4;
+        } else if (mf == 0) {      // depthwise: [channel group][tap] float4 and [channel group][scale, shift] float4
             p.nkg = p.nrt = 0;
             p.bytes = (size_t)ceil_div(L.cout, 4) * L.k * L.k * 16;
             p.aff_bytes = (size_t)ceil_div(L.cout, 4) * 2 * 16;
@@ -671,7 +721,7 @@ struct Builder {
         st.sc_id = sc_id;
         st.conv_layer[0] = b.c1.layer;
         st.conv_layer[1] = st.conv_layer[2] = -1;
-        st.packed[0] = packed_index(b.c1.layer, b.kind == KIND_DW ? 0 : ch.v.mf1, ch.v.px1 < 0, ch.v.pr);
+        st.packed[0] = packed_index(b.c1.layer, b.kind == KIND_DW ? 0 : (ch.v.kind == KIND_THIN ? -1 : ch.v.mf1), ch.v.px1 < 0, ch.v.pr);
         st.packed[1] = st.packed[2] = -1;
         BlockParams &p = st.bp;
         memset(&p, 0, sizeof p);
@@ -756,6 +806,7 @@ struct Builder {
         p.buf_stride = ch.buf_floats;
         p.w_off1 = ch.w_off1;
         p.stream_wgs = ch.v.kind == KIND_POOLS ? std::min(p.nblocks, pl.num_cus * std::max(ch.occ, 1)) : 0;
+        if (ch.v.kind == KIND_THIN) p.stream_wgs = ceil_div(p.nblocks, ch.threads / 64);     // one item per wavefront
     }
 
     void fill_info(xl_group_info &gi, const BlockSpec &b, const Choice &ch) const
@@ -773,7 +824,7 @@ struct Builder {
         gi.threads = ch.threads;
         gi.lds_bytes = ch.lds_bytes;
         gi.workgroups_per_cu = ch.occ;
-        gi.chunk_channels = ch.chunk_kg * kc_of(ch.v.mf1, ch.v.pr);
+        gi.chunk_channels = ch.v.kind == KIND_THIN ? b.c1.cin : ch.chunk_kg * kc_of(ch.v.mf1, ch.v.pr);
         gi.flops_executed = ch.flops_exec;
         gi.precision = ch.v.pr ? XL_PRECISION_BF16X3 : XL_PRECISION_FP32;
         if (b.kind == KIND_SINGLE) {

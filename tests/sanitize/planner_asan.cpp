@@ -21,6 +21,7 @@ namespace xl {
 hipError_t launch_block(int, const BlockParams &, int, size_t, hipStream_t) { return hipSuccess; }
 hipError_t configure_kernels(int) { return hipSuccess; }
 hipError_t launch_pack_filter(const float *, const float *, f32x4 *, int, int, int, int, int, int, hipStream_t, int, int) { return hipSuccess; }
+hipError_t launch_pack_thin(const float *, const float *, const float *, float *, float *, int, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_pack_affine(const float *, f32x4 *, int, int, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_maxpool(const float *, float *, int, int, int, int, int, int, int, int, int, int, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_add(const float *, const float *, float *, long long, int, hipStream_t) { return hipSuccess; }
