@@ -55,6 +55,7 @@ typedef int xl_status;
 #define XL_E_LAUNCH      (-7)   /* a kernel launch was rejected by the runtime          */
 #define XL_E_GRAPH       (-8)   /* graph wiring invalid (ids, order, group membership)  */
 #define XL_E_STATE       (-9)   /* xl_run before xl_prepare on this workspace           */
+#define XL_E_SCRATCH     (-10)  /* plan needs more workspace than xl_run_static holds   */
 
 /* Layer kinds (paper section 2.2: convolution, pooling, activation, element-wise
  * addition and concatenation are the basic operations; activation rides in the
@@ -242,6 +243,28 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
  */
 xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors,
                   void *workspace, void *stream, int reps);
+
+/*
+ * xl_prepare + xl_run for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The workspace is not the caller's but a
+ * static device array inside the library, XL_STATIC_SCRATCH_BYTES long, which every GPU the library
+ * runs on holds from the first call on that GPU until the process ends.  The call allocates no
+ * device memory and frees none; it enqueues kernels on `stream` and returns without synchronising.
+ *   - XL_E_SCRATCH when xl_plan_workspace_bytes(plan) exceeds XL_STATIC_SCRATCH_BYTES (configs 1-4 at
+ *     their full sizes fit; config 5 up to batch 4).
+ *   - relayout != 0: the filters are re-laid out into the array first (as xl_prepare does), from
+ *     `weights` / `nweights`; needed on the first call and whenever filter values change.
+ *     relayout == 0: the filters are re-laid out only if the array's last user on this GPU was another
+ *     plan (then `weights` must be given: XL_E_STATE if it is NULL); otherwise `weights` may be NULL.
+ *   - `tensors`, `fused`: as xl_run.  Graph inputs and outputs stay the caller's buffers.
+ * All calls on one GPU share that GPU's array, and the array keeps what the last call left: nothing in
+ * it has to start at zero (filters are rewritten, every intermediate is written before it is read), but
+ * two calls that overlap in time on one GPU -- different streams, different threads -- race on it.
+ * Order them on one stream.  The current device must be the plan's.
+ */
+#define XL_STATIC_SCRATCH_BYTES (64u << 20)
+xl_status xl_run_static(xl_plan *plan, const void *const *weights, int nweights, const void *const *tensors,
+                        int ntensors, void *stream, int fused, int relayout);
 
 /* Number of kernel launches one xl_run issues in the given mode (paper section 2.2, Fig. 3: one
  * kernel per layer unfused, one per fusion block fused). */

@@ -15,7 +15,8 @@ LIB_PATH = os.environ.get("XL_LIBRARY_PATH") or os.path.join(_HERE, "libxl.so")
 
 XL_OK = 0
 XL_E_NULL, XL_E_SHAPE, XL_E_UNSUPPORTED, XL_E_LDS_BUDGET = -1, -2, -3, -4
-XL_E_DEVICE, XL_E_ALIGN, XL_E_LAUNCH, XL_E_GRAPH, XL_E_STATE = -5, -6, -7, -8, -9
+XL_E_DEVICE, XL_E_ALIGN, XL_E_LAUNCH, XL_E_GRAPH, XL_E_STATE, XL_E_SCRATCH = -5, -6, -7, -8, -9, -10
+XL_STATIC_SCRATCH_BYTES = 64 << 20
 
 XL_CONV, XL_MAXPOOL, XL_GLOBAL_AVGPOOL, XL_ADD, XL_CONCAT = 0, 1, 2, 3, 4
 XL_SINGLE, XL_STRAIGHT, XL_SPLIT, XL_MERGE = 0, 1, 2, 3
@@ -28,7 +29,7 @@ EXPORTS = [
     "xl_plan_create", "xl_plan_destroy", "xl_plan_num_groups", "xl_plan_query", "xl_plan_workspace_bytes",
     "xl_prepare", "xl_run", "xl_tune", "xl_plan_num_launches", "xl_tuner_candidates", "xl_required_extent",
     "xl_strerror", "xl_plan_last_error", "xl_version",
-    "xl_plan_num_candidates", "xl_plan_candidate_info", "xl_plan_select_candidate",
+    "xl_plan_num_candidates", "xl_plan_candidate_info", "xl_plan_select_candidate", "xl_run_static",
 ]
 
 
@@ -135,6 +136,8 @@ def lib() -> ctypes.CDLL:
         L.xl_plan_candidate_info.restype = i
         L.xl_plan_select_candidate.argtypes = [vp, i, i, i]
         L.xl_plan_select_candidate.restype = i
+        L.xl_run_static.argtypes = [vp, ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, vp, i, i]
+        L.xl_run_static.restype = i
         L.xl_version.argtypes = []
         L.xl_version.restype = ctypes.c_char_p
         _lib = L
@@ -254,6 +257,17 @@ class Plan:
             arr[t] = p
         self._check(lib().xl_run(self.handle, arr, self.ntensors, ctypes.c_void_p(workspace_ptr),
                                  ctypes.c_void_p(stream), int(fused)))
+
+    def run_static(self, weight_ptrs: Optional[Sequence[Optional[int]]], tensor_ptrs: Dict[int, int], stream: int = 0,
+                   fused: bool = True, relayout: bool = True):
+        warr = None
+        if weight_ptrs is not None:
+            warr = (ctypes.c_void_p * self.nweights)(*[ctypes.c_void_p(p) if p else None for p in weight_ptrs])
+        arr = (ctypes.c_void_p * self.ntensors)()
+        for t, p in tensor_ptrs.items():
+            arr[t] = p
+        self._check(lib().xl_run_static(self.handle, warr, self.nweights, arr, self.ntensors, ctypes.c_void_p(stream),
+                                        int(fused), int(relayout)))
 
     def tune(self, tensor_ptrs: Dict[int, int], workspace_ptr: int, stream: int = 0, reps: int = 5):
         arr = (ctypes.c_void_p * self.ntensors)()

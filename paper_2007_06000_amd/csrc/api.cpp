@@ -1,6 +1,7 @@
 // C ABI of libxl (see include/xl.h).
 #include <cstdint>
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -47,6 +48,7 @@ const char *xl_strerror(xl_status st)
     case XL_E_LAUNCH: return "kernel launch failed";
     case XL_E_GRAPH: return "invalid graph wiring";
     case XL_E_STATE: return "xl_prepare has not been called for this workspace";
+    case XL_E_SCRATCH: return "the plan needs more workspace than the static scratch array holds";
     }
     return "unknown status";
 }
@@ -85,6 +87,8 @@ xl_status xl_plan_create(const xl_layer *layers, int nlayers, const xl_shape *sh
         delete pl;
         return XL_E_UNSUPPORTED;
     }
+    static std::atomic<unsigned long long> next_serial{1};
+    pl->serial = next_serial.fetch_add(1);
     pl->device = device;
     pl->lds_per_cu = GFX950_LDS_BYTES;
     pl->num_cus = GFX950_CUS;

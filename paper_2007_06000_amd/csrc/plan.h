@@ -80,6 +80,7 @@ struct xl_plan {
     int lds_per_cu = 160 * 1024;
     int num_cus = 256;
     xl_options opts{};
+    unsigned long long serial = 0;                     // unique per created plan (never reused), from 1
     // bound by xl_prepare
     std::set<const void *> prepared;                   // workspaces that hold this plan's re-laid-out filters
     std::vector<const float *> scale_ptr, shift_ptr;   // per layer

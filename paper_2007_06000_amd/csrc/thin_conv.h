@@ -27,14 +27,13 @@ namespace xl {
 
 constexpr int THIN_PW = THIN_TILE_W;      // pooled (without pooling: convolution) columns per item
 
-template <int CIN, int K, int S, int PK, int PS>
+template <int CIN, int K, int S, int PK, int PS, int G = 4>
 __global__ void __launch_bounds__(256) thin_conv_kernel(const BlockParams P)
 {
     constexpr int PW = THIN_PW;
     constexpr int CC = PS * (PW - 1) + PK;          // convolution columns under one row of pooled pixels
     constexpr int T = CIN * K * K;
     constexpr int KEEP = PK > PS ? PK - PS : 0;     // convolution rows two consecutive pooled rows share
-    constexpr int G = 4;                            // convolution pixels that share one run of input columns
     constexpr int NX = S * (G - 1) + K;             // input columns under G convolution pixels
     typedef const float __attribute__((address_space(4))) cfloat;    // read-only, wave-uniform: scalar loads
 
@@ -108,6 +107,7 @@ __global__ void __launch_bounds__(256) thin_conv_kernel(const BlockParams P)
 #pragma unroll
                         for (int v = 0; v < NX; ++v)
                             if (v < run) xr[ci][u][v] = first[((size_t)ci * H + u) * W + v];
+                __builtin_amdgcn_sched_barrier(0);      // every load of the group in flight before the first use: one wait
 #pragma unroll
                 for (int ci = 0; ci < CIN; ++ci)
 #pragma unroll

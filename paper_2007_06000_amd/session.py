@@ -24,7 +24,7 @@ class Session:
         self.x = torch.from_numpy(np.ascontiguousarray(x)).to(self.dev)
         self.y = torch.empty(workload.shapes[workload.output_id], dtype=torch.float32, device=self.dev)
         self._weights = []
-        ptrs = [None] * self.plan.nweights
+        ptrs = self.weight_ptrs = [None] * self.plan.nweights
         for li, p in params.items():
             for j, key in enumerate(("w", "scale", "shift")):
                 if p.get(key) is not None:
