@@ -1495,7 +1495,7 @@ static BlockKernel select_kernel()
     if constexpr (KIND == KIND_POOLS)
         return pool_stream_kernel<MF1, K1, NRT1, NPT1, (PX1 < 0 ? -PX1 : 4)>;
     else if constexpr (KIND == KIND_THIN)
-        return thin_conv_kernel<NRT1, K1, NPT1, K2A, K2B>;      // Cin, K, conv stride, pool window, pool stride
+        return thin_conv_kernel<NRT1, K1, K2B>;      // Cin, K, pooling window
     else
         return block_kernel<KIND, MF1, K1, NRT1, NPT1, MF2, NRT2, NPT2, K2A, K2B, SC, PX1>;
 }
@@ -1615,7 +1615,7 @@ hipError_t launch_pack_filter(const float *w, const float *scale, f32x4 *wp, int
 hipError_t launch_pack_thin(const float *w, const float *scale, const float *shift, float *wp, float *aff, int cout,
                             int taps, hipStream_t s)
 {
-    const int total = (cout + 63) / 64 * taps * 64;
+    const int total = (cout + 15) / 16 * 16 * taps;
     return launch(pack_thin_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w, scale, shift, wp, aff, cout, taps);
 }
 

@@ -237,47 +237,53 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
     for (const Variant &v : variants()) {
         if (v.kind == KIND_THIN) {
             // a first layer with a handful of input channels on the vector ALU, alone or with its max pooling
-            // (columns of the variant: nrt1 = Cin, npt1 = convolution stride, k2a / k2b = pooling window / stride)
+            // (columns of the variant: k1 = K, nrt1 = Cin, k2b = pooling window)
             const bool pooled = b.kind == KIND_POOL;
             if (pr != 0 || !(pooled || (b.kind == KIND_SINGLE && !b.gap))) continue;
-            if (v.k1 != b.c1.k || v.nrt1 != b.c1.cin || v.npt1 != b.c1.stride) continue;
-            if (pooled ? (v.k2a != b.pool_k || v.k2b != b.pool_s) : (v.k2a != 1 || v.k2b != 1)) continue;
-            if (pl.opts.force_threads > 0 && pl.opts.force_threads != 256) continue;
-            std::vector<int> rows;
-            if (pl.opts.force_tile_h > 0) rows.push_back(std::min(pl.opts.force_tile_h, b.Ho));
-            else
-                for (int th : ths)
-                    if (th <= 32 || th == b.Ho) rows.push_back(th);
-            for (int th : rows) {
-                Choice c;
-                c.v = v;
-                c.threads = 256;
-                c.waves_r1 = c.waves_r2 = 1;
-                c.th = th;
-                c.tw = THIN_TILE_W;
-                c.vw2 = c.tw;
-                c.mh = (th - 1) * v.k2b + v.k2a;               // convolution outputs under the item's windows
-                c.mw = (c.tw - 1) * v.k2b + v.k2a;
-                c.ih = required_extent(c.mh, b.c1.k, b.c1.stride);
-                c.iw = required_extent(c.mw, b.c1.k, b.c1.stride);
-                c.tiles_y = ceil_div(b.Ho, th);
-                c.tiles_x = ceil_div(b.Wo, c.tw);
-                c.csplit = ceil_div(b.c1.cout, 64);             // groups of 64 output channels, one per wavefront item
-                c.chunk_kg = 1;
-                c.lds_bytes = 0;
-                c.occ = 4;
-                // one multiply-add instruction (4 cycles per wavefront) per filter value and convolution output;
-                // four wavefronts share a SIMD, 16 a compute unit
-                const double items = (double)c.tiles_x * c.tiles_y * c.csplit * b.N;
-                const double taps = (double)b.c1.cin * b.c1.k * b.c1.k;
-                const double item_clk = (double)c.mh * c.mw * (taps + 2.0) * 4.0 + 600.0;
-                const double t_alu = std::ceil(items / (pl.num_cus * 16.0)) * item_clk * 4.0 / 2.4e9;
-                const double t_mem = (double)b.alg_bytes / 8.0e12;
-                c.cost = std::max(t_alu, t_mem) + 0.15 * std::min(t_alu, t_mem);
-                c.flops_exec = (long long)(items * c.mh * c.mw * taps * 64.0 * 2.0);
-                c.ok = true;
-                if (!best.ok || c.cost < best.cost) best = c;
-                per_key[std::make_tuple(v.id, 256, th, c.tw)] = c;
+            if (v.k1 != b.c1.k || v.nrt1 != b.c1.cin || v.k2b != (pooled ? b.pool_k : 0)) continue;
+            const double taps = (double)b.c1.cin * b.c1.k * b.c1.k;
+            const int rows16 = ceil_div(b.c1.cout, 16) * 16;
+            for (int threads : {256, 512}) {
+                if (pl.opts.force_threads > 0 && pl.opts.force_threads != threads) continue;
+                for (auto [th, tw] : tiles) {
+                    Choice c;
+                    c.v = v;
+                    c.threads = threads;
+                    c.waves_r1 = c.waves_r2 = 1;
+                    c.th = th;
+                    c.tw = tw;
+                    c.vw2 = tw;
+                    c.mh = pooled ? required_extent(th, b.pool_k, b.pool_s) : th;      // convolution outputs under the tile
+                    c.mw = pooled ? required_extent(tw, b.pool_k, b.pool_s) : tw;
+                    const int npx = c.mh * c.mw;
+                    if (npx > threads) continue;                          // one lane per convolution output
+                    if (th * tw * 16 >= 65536) continue;                 // index range of the kernel's divisions
+                    // tiles that leave many lanes idle are not worth timing (the whole image may be smaller)
+                    if (npx * 4 < threads * 3 && !(th == b.Ho && tw == b.Wo) && !(pl.opts.force_tile_h > 0)) continue;
+                    c.ih = required_extent(c.mh, b.c1.k, b.c1.stride);
+                    c.iw = required_extent(c.mw, b.c1.k, b.c1.stride);
+                    c.tiles_y = ceil_div(b.Ho, th);
+                    c.tiles_x = ceil_div(b.Wo, tw);
+                    c.csplit = 1;
+                    c.chunk_kg = 1;
+                    c.lds_bytes = pooled ? 2 * 16 * threads * 4 + rows16 * 4 : 0;      // two tiles of 16 channels x one float per lane, the shifts
+                    if (c.lds_bytes > pl.lds_budget) {
+                        any_lds_reject = true;
+                        continue;
+                    }
+                    c.occ = std::max(1, std::min(pl.lds_per_cu / std::max(c.lds_bytes, 1), 2048 / threads));
+                    // one multiply-add instruction (4 cycles per wavefront) per filter value and output channel, every
+                    // wavefront of the workgroup; 4 SIMDs per compute unit
+                    const double nwg = (double)c.tiles_x * c.tiles_y * b.N;
+                    const double wave_clk = rows16 * (taps + (pooled ? 4.0 : 2.0)) * 4.0 + 1500.0;
+                    const double t_alu = std::ceil(nwg / pl.num_cus) * (threads / 64) / 4.0 * wave_clk / 2.4e9;
+                    const double t_mem = (double)b.alg_bytes / 8.0e12;
+                    c.cost = std::max(t_alu, t_mem) + 0.15 * std::min(t_alu, t_mem);
+                    c.flops_exec = (long long)(nwg * threads * rows16 * taps * 2.0);
+                    c.ok = true;
+                    if (!best.ok || c.cost < best.cost) best = c;
+                    per_key[std::make_tuple(v.id, threads, th, tw)] = c;
+                }
             }
             continue;
         }
@@ -648,10 +654,10 @@ struct Builder {
         p.mf = mf;
         p.pairs = pairs;
         p.pr = pr;
-        if (mf < 0) {       // thin first layer: [group of 64 channels][Cin*K*K][lane] floats and [group][lane] shifts
+        if (mf < 0) {       // thin first layer: [Cout rounded up to 16][Cin*K*K] floats and as many shifts
             p.nkg = p.nrt = 0;
-            p.bytes = (size_t)ceil_div(L.cout, 64) * L.cin * L.k * L.k * 64 * 4;
-            p.aff_bytes = (size_t)ceil_div(L.cout, 64) * 64 * 4;
+            p.bytes = (size_t)ceil_div(L.cout, 16) * 16 * L.cin * L.k * L.k * 4;
+            p.aff_bytes = (size_t)ceil_div(L.cout, 16) * 16 * 4;
         } else if (mf == 0) {      // depthwise: [channel group][tap] float4 and [channel group][scale, shift] float4
             p.nkg = p.nrt = 0;
             p.bytes = (size_t)ceil_div(L.cout, 4) * L.k * L.k * 16;
@@ -806,7 +812,7 @@ struct Builder {
         p.buf_stride = ch.buf_floats;
         p.w_off1 = ch.w_off1;
         p.stream_wgs = ch.v.kind == KIND_POOLS ? std::min(p.nblocks, pl.num_cus * std::max(ch.occ, 1)) : 0;
-        if (ch.v.kind == KIND_THIN) p.stream_wgs = ceil_div(p.nblocks, ch.threads / 64);     // one item per wavefront
+        if (ch.v.kind == KIND_THIN) p.rcp_qrow = rcp(ch.th * ch.tw);
     }
 
     void fill_info(xl_group_info &gi, const BlockSpec &b, const Choice &ch) const

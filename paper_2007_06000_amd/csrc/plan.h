@@ -16,7 +16,7 @@ enum StepType { STEP_BLOCK = 0, STEP_MAXPOOL = 1, STEP_ADD = 2, STEP_GAP = 3, ST
 struct PackedFilter {
     int layer;
     int mf;             // 32 or 16; 0 = depthwise tables ([channel group][tap], [channel group][scale, shift]);
-                        // -1 = thin first layer ([group of 64 channels][Cin*K*K][lane], [group][lane] shifts)
+                        // -1 = thin first layer ([Cout rounded up to 16][Cin*K*K] floats, as many shifts)
     int pr = 0;         // 1: split-bf16 form ([K step][tap][row tile][hi, lo][lane] of 8 bf16)
     bool pairs = false; // channels packed two per channel slot (c -> lane half c % 2, slot c / 2), one K step
     int nkg, nrt;

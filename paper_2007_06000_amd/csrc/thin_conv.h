@@ -4,223 +4,185 @@
 // matrix cores a reduction of 27 terms: most of a K step is padding, and the layer is bound by moving
 // its input and output, not by arithmetic (paper section 2.2: convolutions with few input channels are
 // memory-bound).  Here it runs as plain multiply-adds instead:
-//   - a lane owns one OUTPUT CHANNEL (64 per wavefront) and keeps that channel's whole filter,
-//     Cin * K * K values, in registers for the life of the wavefront;
-//   - the input pixels are the same for every lane, so they are not vector data at all: they are read
-//     with scalar loads straight from the input tensor (wave-uniform addresses, constant address
-//     space) and enter v_fma_f32 as its scalar operand.  No LDS, no staging, no barrier;
-//   - a following max pooling (paper Fig. 3b: Layer2 consumes Layer1's output on chip) happens in the
-//     same lane: the PK x (PS * (PW - 1) + PK) convolution outputs under one row of PW pooled pixels
-//     live in registers, rows shared by two pooled rows are kept, and only pooled values are stored.
-//     Bias and ReLU are applied after the maximum (both are monotonic, so the result is bit-identical
-//     to applying them to every convolution output first).
-// A wavefront works on one item: (image, group of 64 output channels, tile of th x PW pooled pixels).
-// Everything but the final store mask is wave-uniform control flow.
+//   - a lane owns one PIXEL of the workgroup's tile of convolution outputs and keeps that pixel's whole
+//     input window, Cin * K * K values, in registers (loaded once, every load in flight together);
+//   - the output channels are looped over; a filter value is the same for every lane, so it is not
+//     vector data at all: the filter is read with scalar loads (wave-uniform addresses, constant
+//     address space; it is a few KB and stays in the scalar cache) and enters v_fmac_f32 as its scalar
+//     operand.  No filter in LDS, no staging through registers;
+//   - a following max pooling (paper Fig. 3b: Layer2 consumes Layer1's output on chip) takes the
+//     convolution outputs of 16 channels at a time from an LDS tile (two tiles alternate, one barrier
+//     per 16 channels): the convolution output never reaches HBM.  Bias and ReLU are applied after the
+//     maximum (both are monotonic, so the result is bit-identical to applying them first).  PK is the
+//     pooling window (0: no pooling); which pooled pixels a lane takes does not depend on the channel
+//     chunk and is worked out once.
+//   - without a pooling the lanes store their outputs directly (consecutive lanes = consecutive pixels
+//     of a tile row).
 //
 // BlockParams fields used: x, y, N, Cin, H, W, H1, W1 (convolution output extent), Ho, Wo (block output
-// extent), Cy, coff1, c1 (wp: filter as [channel group][Cin*K*K][64 lanes] with the scale folded in,
-// aff: shift as [channel group][64 lanes]; stride, pad, relu, cout), P2 (padding of the pooling),
-// th (pooled rows per item), tiles_x, tiles_y, csplit (channel groups), nblocks (items).
+// extent), Cy, coff1, c1 (wp: filter as [Cout rounded up to 16][Cin*K*K] floats with the scale folded
+// in, aff: shift as [Cout rounded up to 16] floats; stride, pad, relu, cout), pool_k (0: no pooling),
+// s2 / P2 (stride / padding of the pooling), th x tw (output tile), mh x mw (tile of convolution outputs
+// under it, at most blockDim.x pixels), rcp_mw, rcp_vw2 (for tw), rcp_qrow (for th * tw), tiles_x,
+// tiles_y, nblocks.  LDS: two tiles of 16 x blockDim.x floats, then the shifts (Cout rounded up to 16).
 #pragma once
 
 namespace xl {
 
-constexpr int THIN_PW = THIN_TILE_W;      // pooled (without pooling: convolution) columns per item
+constexpr int THIN_OCB = 16;        // output channels per LDS tile (per barrier)
 
-template <int CIN, int K, int S, int PK, int PS, int G = 4>
-__global__ void __launch_bounds__(256) thin_conv_kernel(const BlockParams P)
+template <int CIN, int K, int PK>
+__global__ void __launch_bounds__(MAX_THREADS) thin_conv_kernel(const BlockParams P)
 {
-    constexpr int PW = THIN_PW;
-    constexpr int CC = PS * (PW - 1) + PK;          // convolution columns under one row of pooled pixels
     constexpr int T = CIN * K * K;
-    constexpr int KEEP = PK > PS ? PK - PS : 0;     // convolution rows two consecutive pooled rows share
-    constexpr int NX = S * (G - 1) + K;             // input columns under G convolution pixels
+    constexpr int OCB = THIN_OCB;
     typedef const float __attribute__((address_space(4))) cfloat;    // read-only, wave-uniform: scalar loads
+    extern __shared__ __attribute__((aligned(16))) float lds[];
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int item = __builtin_amdgcn_readfirstlane(logical_block() * (int)(blockDim.x >> 6) + wave);
-    if (item >= P.nblocks) return;
-    const int tx = item % P.tiles_x;
-    int r = item / P.tiles_x;
-    const int ty = r % P.tiles_y;
-    r /= P.tiles_y;
-    const int cg = r % P.csplit;
-    const int n = r / P.csplit;
+    const int L = logical_block();
+    if (L >= P.nblocks) return;
+    const int tiles = P.tiles_x * P.tiles_y;
+    const int tile = L % tiles, n = L / tiles;
+    const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const bool pooled = P.pool_k > 0;
+    const int oy0 = ty * P.th, ox0 = tx * P.tw;                         // first output pixel of the tile
+    const int my0 = pooled ? oy0 * P.s2 - P.P2 : oy0;                   // first convolution output under it
+    const int mx0 = pooled ? ox0 * P.s2 - P.P2 : ox0;
+    const int npx = P.mh * P.mw;
 
-    const int oc = cg * 64 + lane;
-    float w[T];
+    // ---- this lane's pixel and its input window
+    const int r = fdiv(tid, P.rcp_mw), c = tid - r * P.mw;
+    const int cy = my0 + r, cx = mx0 + c;
+    const bool valid = tid < npx && cy >= 0 && cy < P.H1 && cx >= 0 && cx < P.W1;
+    const int H = P.H, W = P.W, S = P.c1.stride, pad = P.c1.pad;
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(P.x + (size_t)n * CIN * H * W,
+                                                (unsigned long long)(P.N - n) * CIN * H * W * 4ull);
+    float x[T];
     {
-        const float *wp = reinterpret_cast<const float *>(P.c1.wp) + (size_t)cg * T * 64 + lane;
+        const int gy0 = cy * S - pad, gx0 = cx * S - pad;
 #pragma unroll
-        for (int t = 0; t < T; ++t) w[t] = wp[t * 64];
+        for (int ci = 0; ci < CIN; ++ci)
+#pragma unroll
+            for (int u = 0; u < K; ++u)
+#pragma unroll
+                for (int v = 0; v < K; ++v) {
+                    const int gy = gy0 + u, gx = gx0 + v;
+                    const bool in = valid && gy >= 0 && gy < H && gx >= 0 && gx < W;
+                    // a lane without an element aims past the end of the buffer: the load returns zero
+                    const unsigned off = in ? (unsigned)(((ci * H + gy) * W + gx) * 4) : 0xfffffff0u;
+                    x[(ci * K + u) * K + v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xr, off, 0, 0));
+                }
     }
-    const float shift = reinterpret_cast<const float *>(P.c1.aff)[cg * 64 + lane];
 
-    const int H = P.H, W = P.W, pad = P.c1.pad;
-    const int py0 = ty * P.th, px0 = tx * PW;                   // first pooled pixel of the item
-    const int cy0 = py0 * PS - P.P2, cx0 = px0 * PS - P.P2;     // first convolution output under its windows
-    const float *xg = P.x + (size_t)n * CIN * H * W;            // this image, for per-lane loads
-    cfloat *xn = (cfloat *)(unsigned long long)xg;              // the same, for scalar loads
+    const int cout = P.c1.cout;
+    const int nchunks = (cout + OCB - 1) / OCB;
+    cfloat *wq = (cfloat *)(unsigned long long)P.c1.wp;
+    cfloat *shift_s = (cfloat *)(unsigned long long)P.c1.aff;                  // by scalar loads (uniform channel)
     const size_t oplane = (size_t)P.Ho * P.Wo;
     const __amdgpu_buffer_rsrc_t yr = make_rsrc(P.y + ((size_t)n * P.Cy + P.coff1) * oplane,
                                                 ((unsigned long long)(P.N - n) * P.Cy - P.coff1) * oplane * 4ull);
 
-    // filter value of a run-time channel (the border path loops over channels to stay small)
-    auto wsel = [&](int ci, int t) {
-        float r = w[t];
+    if constexpr (PK == 0) {
+        const unsigned own = (unsigned)((cy * P.Wo + cx) * 4);                // this lane's output pixel
+        for (int oc = 0; oc < cout; ++oc) {
+            cfloat *wr = wq + (size_t)oc * T;
+            float acc = 0.f;
 #pragma unroll
-        for (int c = 1; c < CIN; ++c) r = ci == c ? w[c * K * K + t] : r;
-        return r;
-    };
-    float cv[PK][CC];
-    // One row of convolution outputs (without shift and activation); -FLT_MAX where the pooling must not
-    // look.  Columns are worked off in groups of G that share one run of input columns per (channel, filter
-    // row).  A run that lies inside the image row is read with scalar loads; a run that crosses the
-    // row's ends (padding, the ragged last item of a row) is fetched by the first lanes with a bounds
-    // check and handed out with v_readlane.
-    auto conv_row = [&](float (&out)[CC], int cr) {
-        if (cr < 0 || cr >= P.H1) {
-#pragma unroll
-            for (int c = 0; c < CC; ++c) out[c] = -FLT_MAX;
-            return;
+            for (int t = 0; t < T; ++t) acc = fmaf(x[t], wr[t], acc);
+            float z = acc + shift_s[oc];
+            if (P.c1.relu) z = fmaxf(z, 0.f);
+            if (valid) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, z), yr, own, oc * (int)oplane * 4, 0);
         }
-        const int gy0 = cr * S - pad;
+    } else {
+        // ---- the pooled pixels this lane takes in every chunk: item = (channel of the chunk, pooled pixel), pixels
+        // of a row on consecutive lanes.  NI items cover workgroups of stride-2 poolings; the rare rest is
+        // worked out on the fly.
+        constexpr int NI = 4;
+        const int ntile = P.th * P.tw;
+        const int nitems = OCB * ntile;
+        float *shift_l = lds + 2 * OCB * nthreads;                            // the shifts, for lanes that differ in channel
+        for (int i = tid; i < nchunks * OCB; i += nthreads) shift_l[i] = reinterpret_cast<const float *>(P.c1.aff)[i];
+        int i_src[NI], i_o[NI];
+        unsigned i_dst[NI];
+        auto item = [&](int it, int &src, int &o, unsigned &dst) {
+            o = fdiv(it, P.rcp_qrow);
+            const int q = it - o * ntile;
+            const int py = fdiv(q, P.rcp_vw2), px = q - py * P.tw;
+            const int gy = oy0 + py, gx = ox0 + px;
+            src = o * nthreads + (py * P.s2) * P.mw + px * P.s2;
+            dst = (gy < P.Ho && gx < P.Wo) ? (unsigned)((gy * P.Wo + gx) * 4) : ~0u;      // ~0: nothing to store
+        };
 #pragma unroll
-        for (int c0 = 0; c0 < CC; c0 += G) {
-            const int gcount = CC - c0 < G ? CC - c0 : G;           // compile-time after unrolling
-            const int run = S * (gcount - 1) + K;                   // input columns under the group
-            const int cc0 = cx0 + c0;                               // first convolution column of the group
-            const int gx0 = cc0 * S - pad;                          // first input column under it
-            float acc[G];
+        for (int k = 0; k < NI; ++k) item(min(tid + k * nthreads, nitems - 1), i_src[k], i_o[k], i_dst[k]);
 #pragma unroll
-            for (int g = 0; g < G; ++g) acc[g] = 0.f;
-            // every input element under the group inside the image: all its runs in one burst of scalar loads
-            const bool fast = gx0 >= 0 && gx0 + run <= W && gy0 >= 0 && gy0 + K <= H;
-            if (fast) {
-                cfloat *first = xn + (size_t)gy0 * W + gx0;
-                float xr[CIN][K][NX];
+        for (int k = 0; k < NI; ++k)
+            if (tid + k * nthreads >= nitems) i_dst[k] = ~0u;
+        auto pool_store = [&](const float *buf, int ch, int src, int o, unsigned dst) {
+            const int oc = ch * OCB + o;
+            const float *sp = buf + src;
+            float m = sp[0];
 #pragma unroll
-                for (int ci = 0; ci < CIN; ++ci)
+            for (int u = 0; u < PK; ++u)
 #pragma unroll
-                    for (int u = 0; u < K; ++u)
+                for (int v = 0; v < PK; ++v)
+                    if (u + v > 0) m = fmaxf(m, sp[u * P.mw + v]);
+            m += shift_l[oc];
+            if (P.c1.relu) m = fmaxf(m, 0.f);
+            if (oc < cout && dst != ~0u)
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, m), yr, dst, oc * (int)oplane * 4, 0);
+        };
+        for (int ch = 0; ch < nchunks; ++ch) {
+            float *buf = lds + (ch & 1) * OCB * nthreads;
+            // two channels at a time: their filter rows arrive with one wait, and the two chains of multiply-adds
+            // alternate
+            for (int o = 0; o < OCB; o += 2) {
+                cfloat *wr = wq + (size_t)(ch * OCB + o) * T;
+                float w0[T], w1[T];
 #pragma unroll
-                        for (int v = 0; v < NX; ++v)
-                            if (v < run) xr[ci][u][v] = first[((size_t)ci * H + u) * W + v];
-                __builtin_amdgcn_sched_barrier(0);      // every load of the group in flight before the first use: one wait
-#pragma unroll
-                for (int ci = 0; ci < CIN; ++ci)
-#pragma unroll
-                    for (int u = 0; u < K; ++u)
-#pragma unroll
-                        for (int g = 0; g < G; ++g) {
-                            if (g >= gcount) continue;
-#pragma unroll
-                            for (int v = 0; v < K; ++v) acc[g] = fmaf(xr[ci][u][g * S + v], w[(ci * K + u) * K + v], acc[g]);
-                        }
-            } else if (cc0 + gcount > 0 && cc0 < P.W1) {
-                for (int ci = 0; ci < CIN; ++ci) {
-#pragma unroll
-                    for (int u = 0; u < K; ++u) {
-                        const int gy = gy0 + u;
-                        if (gy < 0 || gy >= H) continue;           // a row of padding adds nothing
-                        const size_t ro = ((size_t)ci * H + gy) * W;
-                        const int gx = gx0 + lane;
-                        const bool ok = lane < run && gx >= 0 && gx < W;
-                        const float t = ok ? xg[ro + (ok ? gx : 0)] : 0.f;
-                        float xr[NX];
-#pragma unroll
-                        for (int v = 0; v < NX; ++v)
-                            if (v < run)
-                                xr[v] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t), v));
-#pragma unroll
-                        for (int g = 0; g < G; ++g) {
-                            if (g >= gcount) continue;
-#pragma unroll
-                            for (int v = 0; v < K; ++v) acc[g] = fmaf(xr[g * S + v], wsel(ci, u * K + v), acc[g]);
-                        }
-                    }
+                for (int t = 0; t < T; ++t) {
+                    w0[t] = wr[t];
+                    w1[t] = wr[T + t];
                 }
-            }
+                float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (g >= gcount) continue;
-                const int cc = cc0 + g;
-                out[c0 + g] = (cc >= 0 && cc < P.W1) ? acc[g] : -FLT_MAX;
-            }
-        }
-    };
-
-    // Pooled rows top to bottom.  Pooled row i looks at convolution rows cr0 .. cr0 + PK - 1, the first KEEP
-    // of which it shares with the row above: those are moved up, the other PS are computed.  The loop
-    // starts one row early (i = -1) to produce the rows the first pooled row would have inherited.
-    const int rows = min(P.th, P.Ho - py0);
-    const size_t oplane_oc = (size_t)oc * oplane;
-    for (int i = (KEEP > 0 ? -1 : 0); i < rows; ++i) {
-        const int cr0 = cy0 + i * PS;       // first convolution row under pooled row py0 + i
-#pragma unroll
-        for (int u = 0; u < KEEP; ++u)
-#pragma unroll
-            for (int c = 0; c < CC; ++c) cv[u][c] = cv[u + PS][c];
-#pragma unroll
-        for (int u = KEEP; u < PK; ++u) {
-            if (i < 0 && u < PS) continue;          // warm-up: only the rows pooled row 0 inherits
-            conv_row(cv[u], cr0 + u);
-        }
-        if (i < 0) continue;
-        // maximum over the window: rows first, then columns
-        float cm[CC];
-#pragma unroll
-        for (int c = 0; c < CC; ++c) {
-            float m = cv[0][c];
-#pragma unroll
-            for (int u = 1; u < PK; ++u) m = fmaxf(m, cv[u][c]);
-            cm[c] = m;
-        }
-        float o[PW];
-#pragma unroll
-        for (int j = 0; j < PW; ++j) {
-            float m = cm[PS * j];
-#pragma unroll
-            for (int v = 1; v < PK; ++v) m = fmaxf(m, cm[PS * j + v]);
-            m += shift;
-            o[j] = P.c1.relu ? fmaxf(m, 0.f) : m;
-        }
-        // a lane stores PW consecutive pixels of its own channel's row
-        const int py = py0 + i;
-        const unsigned off = (unsigned)((oplane_oc + (size_t)py * P.Wo + px0) * 4);
-        if (oc < P.c1.cout) {
-            typedef unsigned u32x4 __attribute__((vector_size(16)));
-#pragma unroll
-            for (int j = 0; j < PW; j += 4) {
-                if (px0 + j + 3 < P.Wo) {
-                    const f32x4 v4 = {o[j], o[j + 1], o[j + 2], o[j + 3]};
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v4), yr, off + 4 * j, 0, 0);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (px0 + j + e < P.Wo)
-                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, o[j + e]), yr, off + 4 * (j + e), 0, 0);
+                for (int t = 0; t < T; ++t) {
+                    acc0 = fmaf(x[t], w0[t], acc0);
+                    acc1 = fmaf(x[t], w1[t], acc1);
                 }
+                // outside the layer's extent the pooling must not look (section 3.3: the tile is written with the
+                // next layer's padding value already in place)
+                buf[o * nthreads + tid] = valid ? acc0 : -FLT_MAX;
+                buf[(o + 1) * nthreads + tid] = valid ? acc1 : -FLT_MAX;
             }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < NI; ++k)
+                if (k * nthreads < nitems) pool_store(buf, ch, i_src[k], i_o[k], i_dst[k]);
+            for (int it = tid + NI * nthreads; it < nitems; it += nthreads) {
+                int src, o;
+                unsigned dst;
+                item(it, src, o, dst);
+                pool_store(buf, ch, src, o, dst);
+            }
+            // the next chunk goes to the other tile; this one is overwritten two chunks on, after the barrier in between
         }
     }
 }
 
-// Filter of a thin layer: [Cout][Cin][K][K] -> [channel group of 64][Cin*K*K][lane], times the per-channel
-// scale; shift -> [channel group][lane].  Zero for channels past Cout.
+// Filter of a thin layer: [Cout][Cin*K*K] times the per-channel scale, rows up to the next multiple of 16 zero;
+// shift likewise.
 __global__ void pack_thin_kernel(const float *__restrict__ w, const float *__restrict__ scale,
                                  const float *__restrict__ shift, float *__restrict__ wp, float *__restrict__ aff,
                                  int cout, int taps)
 {
-    const int ncg = (cout + 63) / 64;
+    const int rows = (cout + THIN_OCB - 1) / THIN_OCB * THIN_OCB;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < ncg * taps * 64) {
-        const int lane = idx & 63, t = (idx >> 6) % taps, cg = (idx >> 6) / taps;
-        const int oc = cg * 64 + lane;
-        wp[idx] = oc < cout ? w[(size_t)oc * taps + t] * (scale ? scale[oc] : 1.f) : 0.f;
+    if (idx < rows * taps) {
+        const int oc = idx / taps;
+        wp[idx] = oc < cout ? w[idx] * (scale ? scale[oc] : 1.f) : 0.f;
     }
-    if (idx < ncg * 64) aff[idx] = (idx < cout && shift) ? shift[idx] : 0.f;
+    if (idx < rows) aff[idx] = (idx < cout && shift) ? shift[idx] : 0.f;
 }
 
 }  // namespace xl

@@ -50,9 +50,8 @@ enum Kind { KIND_SINGLE = 0, KIND_FUSED2 = 1, KIND_POOL = 2, KIND_DW = 3, KIND_P
 //   KIND_POOLS:  KIND_POOL for a first layer whose reduction fits one chunk, as a stream: resident
 //                workgroups walk the tiles and request the next tile's input ahead (pool_stream_kernel).
 //   KIND_THIN:   a first layer with at most 4 input channels on the vector ALU (thin_conv_kernel): a lane owns
-//                an output channel, input pixels are scalar operands; alone (KIND_SINGLE blocks) or followed
-//                by a max pooling done in registers (KIND_POOL blocks).  No LDS.  th x 8 pooled pixels per
-//                wavefront, csplit = groups of 64 output channels, nblocks = wavefront items.
+//                a pixel of the tile, filter values are scalar operands; alone (KIND_SINGLE blocks) or followed
+//                by a max pooling from an LDS tile (KIND_POOL blocks).
 //   KIND_DW:     stage 1 is a depthwise convolution (one filter per channel, vector ALU) into the
 //                LDS tile; stage 2 as KIND_FUSED2.  c1.wp / c1.aff then hold the plain depthwise
 //                tables ([channel group][tap] and [channel group][scale, shift] float4).
@@ -225,18 +224,18 @@ struct Variant {
     /* ... with at most 4 input channels packed two per channel slot (PX1 = -2: 2 of 4 slots used) */ \
     X(98, KIND_POOLS, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, -2)          \
     X(99, KIND_POOLS, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, -2)          \
-    /* thin first layers (at most 4 input channels) on the vector ALU, alone or with a max pooling done in registers: \
-       columns are id, kind, -, K, Cin, conv stride, -, -, -, pool window (1 = no pooling), pool stride */ \
-    X(130, KIND_THIN, 32, 3, 3, 2, 0, 0, 0, 3, 2, 0, 0)            \
-    X(131, KIND_THIN, 32, 3, 3, 2, 0, 0, 0, 2, 2, 0, 0)            \
-    X(132, KIND_THIN, 32, 3, 3, 1, 0, 0, 0, 3, 2, 0, 0)            \
-    X(133, KIND_THIN, 32, 3, 3, 1, 0, 0, 0, 2, 2, 0, 0)            \
-    X(134, KIND_THIN, 32, 3, 3, 2, 0, 0, 0, 1, 1, 0, 0)            \
-    X(135, KIND_THIN, 32, 3, 3, 1, 0, 0, 0, 1, 1, 0, 0)            \
-    X(136, KIND_THIN, 32, 3, 4, 1, 0, 0, 0, 3, 2, 0, 0)            \
-    X(137, KIND_THIN, 32, 3, 4, 1, 0, 0, 0, 1, 1, 0, 0)            \
-    X(138, KIND_THIN, 32, 3, 1, 1, 0, 0, 0, 1, 1, 0, 0)            \
-    X(139, KIND_THIN, 32, 3, 4, 2, 0, 0, 0, 3, 2, 0, 0)            \
+    /* thin first layers (at most 4 input channels) on the vector ALU, alone or with a max pooling from an LDS tile: \
+       columns are id, kind, -, K, Cin, -, -, -, -, -, pooling window (0: none), then unused */ \
+    X(130, KIND_THIN, 32, 3, 3, 1, 0, 0, 0, 0, 3, 0, 0)           \
+    X(131, KIND_THIN, 32, 3, 3, 1, 0, 0, 0, 0, 2, 0, 0)           \
+    X(132, KIND_THIN, 32, 3, 3, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(133, KIND_THIN, 32, 3, 4, 1, 0, 0, 0, 0, 3, 0, 0)           \
+    X(134, KIND_THIN, 32, 3, 4, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(135, KIND_THIN, 32, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(136, KIND_THIN, 32, 3, 2, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(137, KIND_THIN, 32, 5, 3, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(138, KIND_THIN, 32, 1, 3, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    X(139, KIND_THIN, 32, 1, 4, 1, 0, 0, 0, 0, 0, 0, 0)           \
     /* conv -> maxpool */                                 \
     X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
     X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)             \
@@ -305,7 +304,6 @@ constexpr int STAGE_UNITS = XL_STAGE_UNITS;      // input units (4 channels x 4 
 constexpr int MAX_W_CHUNK_BYTES = 52 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
 constexpr int PLANAR_SLOTS = 8;     // LDS-direct loads per wave and chunk of a planar input chunk
 constexpr int MAX_THREADS = 512;
-constexpr int THIN_TILE_W = 8;      // output columns per wavefront item of the thin-layer kernel
 constexpr int MAX_ALTERNATIVES = 64;  // candidates per block kept for on-device tuning
 #ifndef XL_MIN_WAVES
 #define XL_MIN_WAVES 2
