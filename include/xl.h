@@ -266,6 +266,32 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors,
 xl_status xl_run_static(xl_plan *plan, const void *const *weights, int nweights, const void *const *tensors,
                         int ntensors, void *stream, int fused, int relayout);
 
+/*
+ * Per-launch timing of one execution mode (paper section 4.1: every measurement is run several times and
+ * averaged, with timers on the GPU side).  Runs the network `reps` times (reps < 1 means 5) like xl_run,
+ * with an event before and after every kernel launch on `stream`, then SYNCHRONISES the stream and writes the
+ * average duration of each launch in microseconds to launch_us[0 .. xl_plan_num_launches(plan, fused) - 1]
+ * (host memory, `cap` entries available; XL_E_GRAPH if cap is too small).  One untimed run comes first.
+ * Tensors and workspace as for xl_run; outputs and workspace intermediates are overwritten.
+ */
+xl_status xl_profile(const xl_plan *plan, const void *const *tensors, int ntensors, void *workspace, void *stream,
+                     int fused, int reps, float *launch_us, int cap);
+
+/*
+ * What this GPU sustains, measured, to put next to the published peaks the roofline fractions are quoted
+ * against (paper section 4.1 lists the peaks of its two GPUs the same way):
+ *   copy_gbs          a plain copy kernel over `bytes` bytes from `src` to `dst` (both DEVICE buffers of at
+ *                     least `bytes` bytes, 16-byte aligned; use more than the 256 MB last-level cache):
+ *                     bytes read + bytes written per second, in GB/s
+ *   mfma_f32_tflops   a loop of independent V_MFMA_F32_32X32X2_F32 operations on registers, every compute unit busy
+ *   mfma_bf16_tflops  the same with V_MFMA_F32_32X32X16_BF16
+ *   valu_f32_tflops   a loop of independent (not packed) v_fma_f32 operations
+ * Any output pointer may be NULL.  `dst` is overwritten (its first 2 MiB also serve the arithmetic loops as a
+ * sink: bytes must be at least 2 MiB).  SYNCHRONISES the stream; allocates nothing.
+ */
+xl_status xl_measure_peaks(void *dst, const void *src, size_t bytes, void *stream, double *copy_gbs,
+                           double *mfma_f32_tflops, double *mfma_bf16_tflops, double *valu_f32_tflops);
+
 /* Number of kernel launches one xl_run issues in the given mode (paper section 2.2, Fig. 3: one
  * kernel per layer unfused, one per fusion block fused). */
 int xl_plan_num_launches(const xl_plan *plan, int fused);

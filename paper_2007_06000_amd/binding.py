@@ -29,7 +29,7 @@ EXPORTS = [
     "xl_plan_create", "xl_plan_destroy", "xl_plan_num_groups", "xl_plan_query", "xl_plan_workspace_bytes",
     "xl_prepare", "xl_run", "xl_tune", "xl_plan_num_launches", "xl_tuner_candidates", "xl_required_extent",
     "xl_strerror", "xl_plan_last_error", "xl_version",
-    "xl_plan_num_candidates", "xl_plan_candidate_info", "xl_plan_select_candidate", "xl_run_static",
+    "xl_plan_num_candidates", "xl_plan_candidate_info", "xl_plan_select_candidate", "xl_run_static", "xl_profile", "xl_measure_peaks",
 ]
 
 
@@ -138,6 +138,11 @@ def lib() -> ctypes.CDLL:
         L.xl_plan_select_candidate.restype = i
         L.xl_run_static.argtypes = [vp, ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, vp, i, i]
         L.xl_run_static.restype = i
+        L.xl_profile.argtypes = [vp, ctypes.POINTER(vp), i, vp, vp, i, i, ctypes.POINTER(ctypes.c_float), i]
+        L.xl_profile.restype = i
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.xl_measure_peaks.argtypes = [vp, vp, ctypes.c_size_t, vp, dp, dp, dp, dp]
+        L.xl_measure_peaks.restype = i
         L.xl_version.argtypes = []
         L.xl_version.restype = ctypes.c_char_p
         _lib = L
@@ -162,6 +167,17 @@ def xl_tuner_candidates(out_size: int) -> List[tuple]:
 
 def xl_required_extent(t: int, k: int, stride: int) -> int:
     return lib().xl_required_extent(t, k, stride)
+
+
+def xl_measure_peaks(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> dict:
+    """Measured copy bandwidth and arithmetic rates of the current device (see include/xl.h)."""
+    v = [ctypes.c_double() for _ in range(4)]
+    st = lib().xl_measure_peaks(ctypes.c_void_p(dst_ptr), ctypes.c_void_p(src_ptr), nbytes, ctypes.c_void_p(stream),
+                                *[ctypes.byref(d) for d in v])
+    if st != XL_OK:
+        raise XlError(st, xl_strerror(st))
+    return {"copy_gbs": v[0].value, "mfma_f32_tflops": v[1].value, "mfma_bf16_tflops": v[2].value,
+            "valu_f32_tflops": v[3].value}
 
 
 class Plan:
@@ -268,6 +284,18 @@ class Plan:
             arr[t] = p
         self._check(lib().xl_run_static(self.handle, warr, self.nweights, arr, self.ntensors, ctypes.c_void_p(stream),
                                         int(fused), int(relayout)))
+
+    def profile(self, tensor_ptrs: Dict[int, int], workspace_ptr: int, stream: int = 0, fused: bool = True,
+                reps: int = 5) -> List[float]:
+        """Average duration of every launch of one mode, in microseconds (synchronises)."""
+        arr = (ctypes.c_void_p * self.ntensors)()
+        for t, p in tensor_ptrs.items():
+            arr[t] = p
+        n = self.num_launches(fused)
+        out = (ctypes.c_float * max(n, 1))()
+        self._check(lib().xl_profile(self.handle, arr, self.ntensors, ctypes.c_void_p(workspace_ptr),
+                                     ctypes.c_void_p(stream), int(fused), int(reps), out, n))
+        return [out[k] for k in range(n)]
 
     def tune(self, tensor_ptrs: Dict[int, int], workspace_ptr: int, stream: int = 0, reps: int = 5):
         arr = (ctypes.c_void_p * self.ntensors)()

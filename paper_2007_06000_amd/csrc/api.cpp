@@ -319,6 +319,88 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors, 
     return XL_OK;
 }
 
+xl_status xl_profile(const xl_plan *plan, const void *const *tensors, int ntensors, void *workspace, void *stream,
+                     int fused, int reps, float *launch_us, int cap)
+{
+    xl_status rc = check_run_args(plan, tensors, ntensors, workspace);
+    if (rc != XL_OK) return rc;
+    if (!launch_us) return XL_E_NULL;
+    const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
+    const int n = (int)steps.size();
+    if (cap < n) return run_fail(plan, XL_E_GRAPH, "launch_us has fewer entries than the mode has launches");
+    if (reps < 1) reps = 5;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    rc = xl_run(plan, tensors, ntensors, workspace, stream, fused);     // untimed: code and filters warm
+    if (rc != XL_OK) return rc;
+    std::vector<hipEvent_t> ev((size_t)reps * (n + 1));
+    size_t made = 0;
+    for (; made < ev.size(); ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) break;
+    if (made < ev.size()) rc = run_fail(plan, XL_E_DEVICE, "cannot create timing events");
+    for (int r = 0; r < reps && rc == XL_OK; ++r) {
+        hipEvent_t *e = &ev[(size_t)r * (n + 1)];
+        (void)hipEventRecord(e[0], s);
+        for (int i = 0; i < n && rc == XL_OK; ++i) {
+            rc = launch_step(plan, steps[i], tensors, ws, s);
+            (void)hipEventRecord(e[i + 1], s);
+        }
+    }
+    if (rc == XL_OK && hipStreamSynchronize(s) != hipSuccess) rc = run_fail(plan, XL_E_LAUNCH, "a kernel failed while profiling");
+    if (rc == XL_OK) {
+        for (int i = 0; i < n; ++i) {
+            double sum = 0;
+            for (int r = 0; r < reps; ++r) {
+                float ms = 0.f;
+                (void)hipEventElapsedTime(&ms, ev[(size_t)r * (n + 1) + i], ev[(size_t)r * (n + 1) + i + 1]);
+                sum += ms;
+            }
+            launch_us[i] = (float)(sum / reps * 1e3);
+        }
+    }
+    for (size_t i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return rc;
+}
+
+xl_status xl_measure_peaks(void *dst, const void *src, size_t bytes, void *stream, double *copy_gbs,
+                           double *mfma_f32_tflops, double *mfma_bf16_tflops, double *valu_f32_tflops)
+{
+    if (!dst || !src) return XL_E_NULL;
+    if (bytes < (2u << 20) || (reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16) return XL_E_ALIGN;
+    int dev = 0, cus = GFX950_CUS;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return XL_E_DEVICE;
+    cus = prop.multiProcessorCount;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return XL_E_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return XL_E_DEVICE;
+    }
+    double *out[4] = {copy_gbs, mfma_f32_tflops, mfma_bf16_tflops, valu_f32_tflops};
+    xl_status rc = XL_OK;
+    for (int what = 0; what < 4 && rc == XL_OK; ++what) {
+        if (!out[what]) continue;
+        double work = 0, best = 0;
+        for (int r = 0; r < 6 && rc == XL_OK; ++r) {        // first launch untimed, then the fastest of 5
+            if (r > 0) (void)hipEventRecord(e0, s);
+            if (xl::launch_peak_probe(what, dst, src, bytes, cus, s, &work) != hipSuccess) rc = XL_E_LAUNCH;
+            if (r > 0) (void)hipEventRecord(e1, s);
+            if (hipStreamSynchronize(s) != hipSuccess) rc = XL_E_LAUNCH;
+            if (r > 0 && rc == XL_OK) {
+                float ms = 0.f;
+                (void)hipEventElapsedTime(&ms, e0, e1);
+                if (ms > 0.f) best = std::max(best, work / (ms * 1e-3));
+            }
+        }
+        *out[what] = what == 0 ? best / 1e9 : best / 1e12;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
+
 // Make candidate `idx` the configuration of step `st`; in the fused path the block's reported tiles follow.
 static void adopt(xl_plan *plan, xl::Step &st, int idx, bool fused)
 {

@@ -1775,6 +1775,94 @@ hipError_t launch_gap(const float *x, float *y, int NC, int HW, hipStream_t s)
 }
 
 // ----------------------------------------------------------------------------
+// Peak probes: what the device sustains on a plain copy and on register-only arithmetic loops
+// ----------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) probe_copy_kernel(f32x4 *__restrict__ dst, const f32x4 *__restrict__ src, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+constexpr int PROBE_ITERS = 4096;
+
+// 4 independent accumulator tiles per wave: the matrix pipe never waits for a result
+__global__ void __launch_bounds__(512) probe_mfma_f32_kernel(float *out, float a0)
+{
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) zero_acc(acc[i]);
+    const float a = a0 + threadIdx.x, b = a0 * 0.5f;
+    for (int it = 0; it < PROBE_ITERS; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += acc[i][j];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+__global__ void __launch_bounds__(512) probe_mfma_bf16_kernel(float *out, float a0)
+{
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) zero_acc(acc[i]);
+    const f32x4 av = {a0, a0 + threadIdx.x, a0, a0}, bv = {a0, a0, a0 * 0.5f, a0};
+    const bf16x8 a = __builtin_bit_cast(bf16x8, av), b = __builtin_bit_cast(bf16x8, bv);
+    for (int it = 0; it < PROBE_ITERS; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += acc[i][j];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// 16 independent chains of multiply-adds per lane
+__global__ void __launch_bounds__(512) probe_valu_kernel(float *out, float a0)
+{
+    float acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = a0 + i + threadIdx.x;
+    const float m = 1.0f + a0 * 1e-7f, c = a0 * 1e-3f;
+    for (int it = 0; it < PROBE_ITERS; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = fmaf(acc[i], m, c);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+hipError_t launch_peak_probe(int what, void *dst, const void *src, size_t bytes, int num_cus, hipStream_t s, double *work)
+{
+    const int wgs = num_cus * 4, threads = 512;         // 2 MiB of sink: wgs * threads floats
+    const double waves = (double)wgs * (threads / 64);
+    switch (what) {
+    case 0:
+        *work = 2.0 * (double)(bytes / 16 * 16);
+        return launch(probe_copy_kernel, dim3(num_cus * 8), dim3(256), 0, s, (f32x4 *)dst, (const f32x4 *)src, bytes / 16);
+    case 1:
+        *work = waves * PROBE_ITERS * 4 * (2.0 * 32 * 32 * 2);
+        return launch(probe_mfma_f32_kernel, dim3(wgs), dim3(threads), 0, s, (float *)dst, 1.0f);
+    case 2:
+        *work = waves * PROBE_ITERS * 4 * (2.0 * 32 * 32 * 16);
+        return launch(probe_mfma_bf16_kernel, dim3(wgs), dim3(threads), 0, s, (float *)dst, 1.0f);
+    case 3:
+        *work = waves * PROBE_ITERS * 16 * 64 * 2.0;
+        return launch(probe_valu_kernel, dim3(wgs), dim3(threads), 0, s, (float *)dst, 1.0f);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ----------------------------------------------------------------------------
 // Depthwise convolution (groups == channels): tables and the per-layer kernel of the unfused path
 // ----------------------------------------------------------------------------
 // [C][1][K][K] -> [channel group][tap] float4, and scale / shift -> [channel group][2] float4

@@ -315,6 +315,9 @@ hipError_t configure_kernels(int max_lds_bytes);      // raises the dynamic-LDS 
 
 hipError_t launch_pack_filter(const float *w, const float *scale, f32x4 *wp, int cout, int cin, int k, int mf,
                               int nkg, int nrt, hipStream_t s, int pairs = 0, int pr = 0);
+// peak probes: 0 = copy (bytes from src to dst), 1 = fp32 matrix loop, 2 = bf16 matrix loop, 3 = fp32 multiply-add loop;
+// `work` receives bytes moved or floating-point operations issued by one launch
+hipError_t launch_peak_probe(int what, void *dst, const void *src, size_t bytes, int num_cus, hipStream_t s, double *work);
 hipError_t launch_pack_thin(const float *w, const float *scale, const float *shift, float *wp, float *aff, int cout,
                             int taps, hipStream_t s);
 hipError_t launch_pack_affine(const float *shift, f32x4 *out, int cout, int mf, int nrt, hipStream_t s);

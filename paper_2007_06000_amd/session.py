@@ -35,6 +35,7 @@ class Session:
         self.workspace = torch.empty((nbytes + 3) // 4, dtype=torch.float32, device=self.dev)
         assert self.workspace.data_ptr() % 256 == 0
         self.plan.prepare(ptrs, self.workspace.data_ptr(), self.stream)
+        self.workspaces = [self.workspace]
         self.tensor_ptrs = {workload.input_id: self.x.data_ptr(), workload.output_id: self.y.data_ptr()}
         if tune:
             self.plan.tune(self.tensor_ptrs, self.workspace.data_ptr(), self.stream)
@@ -44,13 +45,20 @@ class Session:
     def stream(self) -> int:
         return torch.cuda.current_stream(self.dev).cuda_stream
 
-    def run(self, fused: bool = True, x: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None):
+    def add_workspace(self) -> int:
+        """One more prepared workspace (for callers that rotate over several, e.g. cache-cold timing); returns its index."""
+        ws = torch.empty_like(self.workspace)
+        self.plan.prepare(self.weight_ptrs, ws.data_ptr(), self.stream)
+        self.workspaces.append(ws)
+        return len(self.workspaces) - 1
+
+    def run(self, fused: bool = True, x: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None, ws: int = 0):
         ptrs = dict(self.tensor_ptrs)
         if x is not None:
             ptrs[self.workload.input_id] = x.data_ptr()
         if y is not None:
             ptrs[self.workload.output_id] = y.data_ptr()
-        self.plan.run(ptrs, self.workspace.data_ptr(), self.stream, fused)
+        self.plan.run(ptrs, self.workspaces[ws].data_ptr(), self.stream, fused)
         return self.y if y is None else y
 
     def output(self, fused: bool = True) -> np.ndarray:

@@ -21,6 +21,7 @@ namespace xl {
 hipError_t launch_block(int, const BlockParams &, int, size_t, hipStream_t) { return hipSuccess; }
 hipError_t configure_kernels(int) { return hipSuccess; }
 hipError_t launch_pack_filter(const float *, const float *, f32x4 *, int, int, int, int, int, int, hipStream_t, int, int) { return hipSuccess; }
+hipError_t launch_peak_probe(int, void *, const void *, size_t, int, hipStream_t, double *w) { *w = 0; return hipSuccess; }
 hipError_t launch_pack_thin(const float *, const float *, const float *, float *, float *, int, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_pack_affine(const float *, f32x4 *, int, int, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_maxpool(const float *, float *, int, int, int, int, int, int, int, int, int, int, int, hipStream_t) { return hipSuccess; }
@@ -39,6 +40,7 @@ hipError_t hipEventCreate(hipEvent_t *) { return hipErrorNoDevice; }
 hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }
 hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
 hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
+hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
 hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.f; return hipSuccess; }
 }
 
