@@ -95,9 +95,9 @@ typedef struct xl_layer {
 /* A fusion block: `mode` and the layer indices it covers, in graph order.
  *   XL_STRAIGHT: conv -> conv, conv -> maxpool, conv -> global average pooling
  *                (the image must fit one workgroup tile), depthwise conv -> conv
- *   XL_SPLIT:    conv -> {conv, conv} [-> concat [-> maxpool]]; the max pooling (no padding, every
- *                window inside the image) is applied to the concatenated result before it
- *                leaves the chip, so only the pooled tensor is written
+ *   XL_SPLIT:    conv -> {conv, conv} [-> concat [-> maxpool]]; the max pooling (with or without
+ *                padding) is applied to the concatenated result before it leaves the chip, so
+ *                only the pooled tensor is written
  *   XL_MERGE:    conv -> conv -> add(., block input)          (residual block), or
  *                {conv, conv}(block input) -> add -> conv      (two producers, all 1x1)
  *   XL_SINGLE:   any one layer

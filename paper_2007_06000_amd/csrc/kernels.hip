@@ -894,8 +894,8 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 
 // Epilogue of a stage-2 pass whose result is max-pooled before it leaves the chip (KIND_FUSED2P):
 // scale / shift / activation, then into an LDS tile [4-channel group of the pass][row][col][4] of the
-// th x tw stage-2 output tile; positions outside the layer's output extent get -FLT_MAX, so the pooling
-// windows ignore them.  rl0: this wave's first row tile relative to the pass.
+// th x tw stage-2 output tile; positions outside the layer's output extent (ragged last tiles, the padding of
+// the pooling) get -FLT_MAX, so the pooling windows ignore them.  rl0: this wave's first row tile relative to the pass.
 template <int MF, int NRT, int NPT>
 __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
                                            const ConvW &c, float *tile, int oy0, int ox0, int rl0, int rt0, int rt_end,
@@ -911,7 +911,7 @@ __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT
         const int pidx = (pt0 + p) * MF + col;
         const int oy = fdiv(pidx, P.rcp_vw2), ox = pidx - oy * P.vw2;
         const bool valid = oy < P.th && ox < P.tw;
-        const bool inside = oy0 + oy < P.H2 && ox0 + ox < P.W2;
+        const bool inside = oy0 + oy >= 0 && oy0 + oy < P.H2 && ox0 + ox >= 0 && ox0 + ox < P.W2;
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
             if (rt0 + r >= rt_end) continue;
@@ -1023,8 +1023,8 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
     const int n = L / (tiles * P.csplit);
     const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
     // KIND_FUSED2P: th x tw is the stage-2 tile the pooled pth x ptw output tile needs; neighbours overlap
-    const int oy0 = (KIND == KIND_FUSED2P) ? ty * P.pth * P.ps2 : ty * P.th;
-    const int ox0 = (KIND == KIND_FUSED2P) ? tx * P.ptw * P.ps2 : tx * P.tw;
+    const int oy0 = (KIND == KIND_FUSED2P) ? ty * P.pth * P.ps2 - P.pp : ty * P.th;
+    const int ox0 = (KIND == KIND_FUSED2P) ? tx * P.ptw * P.ps2 - P.pp : tx * P.tw;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;

@@ -780,6 +780,7 @@ struct Builder {
         p.P2 = two ? P2 : (b.kind == KIND_POOL ? b.pool_p : 0);
         p.pool_k = b.pool_k;
         p.ps2 = b.kind == KIND_FUSED2P ? b.pool_s : 1;
+        p.pp = b.kind == KIND_FUSED2P ? b.pool_p : 0;
         p.pth = ch.pth;
         p.ptw = ch.ptw;
         p.H2 = b.H2;
@@ -976,12 +977,12 @@ struct Builder {
                 if (Q.op != XL_MAXPOOL || Q.in[0] != sa.root) return fail(XL_E_GRAPH, at + "fifth layer must be a max pooling of the concat");
                 if (!only_consumers(sa.root, {ids[4]})) return fail(XL_E_UNSUPPORTED, at + "the concat has a consumer outside the block");
                 if (pl.storage[sa.root].root != sa.root) return fail(XL_E_UNSUPPORTED, at + "the concat is itself a concat operand");
-                const xl_shape &cs = pl.shapes[sa.root], &qs = pl.shapes[Q.out];
-                if (Q.pad != 0 || (qs.h - 1) * Q.stride + Q.k > cs.h || (qs.w - 1) * Q.stride + Q.k > cs.w)
-                    return fail(XL_E_UNSUPPORTED, at + "the fused max pooling must keep every window inside the image (no padding)");
+                const xl_shape &cs = pl.shapes[sa.root];
+                // windows may hang over the image (padding): the block writes -FLT_MAX there, which a maximum ignores
                 b.kind = KIND_FUSED2P;
                 b.pool_k = Q.k;
                 b.pool_s = Q.stride;
+                b.pool_p = Q.pad;
                 b.H2 = cs.h;
                 b.W2 = cs.w;
                 pooled = Q.out;

@@ -73,8 +73,9 @@ struct BlockParams {
     int coff2[2];
     int s2;                 // stride shared by the stage-2 windows
     int P2;                 // halo of the LDS tile on the top/left = largest stage-2 pad
-    int pool_k;             // KIND_POOL: window size (stride s2, pad P2); KIND_FUSED2P: window size (stride ps2, no padding)
+    int pool_k;             // KIND_POOL: window size (stride s2, pad P2); KIND_FUSED2P: window size (stride ps2, pad pp)
     int ps2;                // KIND_FUSED2P: stride of the pooling after stage 2
+    int pp;                 // KIND_FUSED2P: padding of that pooling (its windows may start above / left of the image)
     int pth, ptw;           // KIND_FUSED2P: tile of the pooled output
     int H2, W2;             // KIND_FUSED2P: extent of the stage-2 output (before pooling)
     int relu_out;           // applied after the shortcut add (merge)

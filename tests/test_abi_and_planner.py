@@ -229,9 +229,9 @@ def test_split_block_followed_by_max_pooling_is_one_launch():
     assert q["stores_fused"] == 2 * 64 * 13 * 13                 # only the pooled tensor is written
     assert q["stores_unfused"] == 2 * (16 + 64) * 27 * 27 + 2 * 64 * 13 * 13
     assert q["mid_h"] == 2 * (q["tile_h"] - 1) + 3 + 2           # pooled tile -> 3x3/2 windows -> 3x3 conv halo
-    # a padded pooling would need -inf padding inside the block: not fused
-    with pytest.raises(B.XlError):
-        B.Plan(W.split_fire_pool(n=1, hw=27, pp=1))
+    # a padded pooling fuses as well: windows that hang over the image see -FLT_MAX there
+    pp = B.Plan(W.split_fire_pool(n=1, hw=27, pp=1))
+    assert pp.num_launches(True) == 1 and pp.query(0)["stores_fused"] == 64 * 14 * 14
 
 
 def test_candidates_of_a_launch_can_be_listed_and_selected():

@@ -244,6 +244,9 @@ def test_conv_then_max_pooling_shapes(wl):
     W.split_fire_pool(n=2, cin=24, hw=14, s=8, e=16),           # last row and column feed no window
     W.split_fire_pool(n=1, cin=72, hw=12, s=48, e=96, pk=2, ps=2),
     W.split_fire_pool(n=3, cin=64, hw=55, s=16, e=64),          # config 5's fire3 + pool
+    W.split_fire_pool(n=2, cin=32, hw=27, pp=1),                # padded pooling: windows start above / left of the image
+    W.split_fire_pool(n=1, cin=40, hw=14, s=16, e=64, pp=1),    # ... and hang over its bottom / right edge
+    W.split_fire_pool(n=2, cin=64, hw=13, s=48, e=96, pk=2, ps=2, pp=1),
 ])
 def test_split_block_with_max_pooling(wl):
     run_both(wl)

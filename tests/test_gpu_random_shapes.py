@@ -29,7 +29,7 @@ def random_workload(rng):
         return W.config(3, n=n, hw=h, cin=cin, s=rng.choice([8, 16, 48]), e=rng.choice([16, 64, 96]))
     if kind == "firepool":
         return W.split_fire_pool(n=n, cin=cin, hw=max(h, 7), s=rng.choice([8, 16, 48]), e=rng.choice([16, 32, 96]),
-                                 pk=rng.choice([2, 3]), ps=2)
+                                 pk=rng.choice([2, 3]), ps=2, pp=rng.choice([0, 0, 1]))
     if kind == "merge":
         return W.config(4, n=n, hw=h, c=rng.choice([16, 32, 64]))
     if kind == "gap":
