@@ -29,7 +29,6 @@
 
 namespace xl {
 
-
 // ----------------------------------------------------------------------------
 // matrix-core wrappers
 // ----------------------------------------------------------------------------
@@ -594,39 +593,9 @@ __device__ __forceinline__ void init_acc(typename MM<MF>::Acc (&acc)[NRT][NPT], 
 
 // Epilogue of a tile to global memory (S5), also used by the single-layer kernel.
 // Pixel p of the tile sits at (p / vw, p % vw); columns >= tw of the virtual row are padding.
-// HAS_SC (merge mode): the shortcut values of one row tile are fetched together before they are
-// used; invalid lanes read element 0.
-// 4 x 4 transpose inside each group of 4 adjacent lanes: on entry lane t of a group holds v[e] =
-// M[e][t] (four channels of its own pixel), on exit v[k] = M[t][k] (its own channel for the four
-// pixels of the group).  Two butterfly steps of cross-lane moves (lane ^ 1, then lane ^ 2).
-__device__ __forceinline__ void quad_transpose(float (&v)[4])
-{
-    const int t = threadIdx.x & 3;
-    auto xor1 = [](float x) {
-        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
-    };
-    auto xor2 = [](float x) {
-        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
-    };
-    const bool odd = t & 1, hi = t & 2;
-    // step 1: 2 x 2 blocks -- lanes t, t^1 and register pairs (0,1), (2,3)
-    const float y01 = xor1(odd ? v[0] : v[1]);
-    const float y23 = xor1(odd ? v[2] : v[3]);
-    const float c0 = odd ? y01 : v[0], c1 = odd ? v[1] : y01;
-    const float d0 = odd ? y23 : v[2], d1 = odd ? v[3] : y23;
-    // step 2: lanes t, t^2 exchange the pair they do not keep
-    const float r0 = xor2(hi ? c0 : d0), r1 = xor2(hi ? c1 : d1);
-    v[0] = hi ? r0 : c0;
-    v[1] = hi ? r1 : c1;
-    v[2] = hi ? d0 : r0;
-    v[3] = hi ? d1 : r1;
-}
-
-// Epilogue into global memory: scale / shift / activation, optional shortcut add, store.
-// When the tile's pixel order keeps every aligned group of 4 pixels in one output row (`wide`), the
-// accumulators are transposed inside groups of 4 lanes so that a lane holds 4 consecutive pixels of
-// one channel and moves them with one 16-byte buffer access; otherwise each lane stores its own
-// pixel's channels one by one.
+// HAS_SC (merge mode): the shortcut values of one row tile are fetched together before they are used.
+// Epilogue into global memory: activation, optional shortcut add, store (the shift is in the accumulators
+// already).
 template <int MF, int NRT, int NPT, bool HAS_SC>
 __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[NRT][NPT], const BlockParams &P,
                                              const ConvW &c, int coff, int n, int oy0, int ox0, int th, int tw, int vw,
@@ -642,117 +611,47 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     const float *__restrict__ scn = HAS_SC ? P.sc + (size_t)n * P.Csc * plane : nullptr;
     asm volatile("" ::: "memory");      // keeps the epilogue's address arithmetic out of the K loop's schedule
 
-    const bool wide = (vw & 3) == 0 || th == 1;
-    if (wide) {
-        // descriptors end with the tensors: whatever a 16-byte access would touch past the end is dropped
-        const unsigned long long ybytes = ((unsigned long long)(P.N - n) * P.Cy - coff) * plane * 4ull;
-        const __amdgpu_buffer_rsrc_t yr = make_rsrc(yn, ybytes);
-        __amdgpu_buffer_rsrc_t sr = yr;
-        if constexpr (HAS_SC) {
-            const unsigned long long sbytes = (unsigned long long)(P.N - n) * P.Csc * plane * 4ull;
-            sr = make_rsrc(scn, sbytes);
-        }
-        const int t = lane & 3;
-        int nvs[NPT];
-        unsigned offs[NPT][NRT][M::NQ];
-        f32x4 sv[NPT][NRT][M::NQ];
-        // addresses first, and every shortcut load in flight before the first one is used
-#pragma unroll
-        for (int p = 0; p < NPT; ++p) {
-            const int pidx = (pt0 + p) * MF + (col & ~3);        // first pixel of this lane's group of 4
-            const int oy = fdiv(pidx, rcp_vw), ox = pidx - oy * vw;
-            const int gy = oy0 + oy, gx = ox0 + ox;
-            nvs[p] = (oy < th && gy < P.Ho) ? min(min(tw - ox, P.Wo - gx), 4) : 0;           // pixels to store
-            const int pix = nvs[p] > 0 ? gy * P.Wo + gx : 0;
-#pragma unroll
-            for (int r = 0; r < NRT; ++r)
-#pragma unroll
-                for (int q = 0; q < M::NQ; ++q) {
-                    const int co = (rt0 + r) * MF + M::quad_row(q, sub) + t;     // the channel this lane ends up with
-                    offs[p][r][q] = (unsigned)((min(co, c.cout - 1) * plane + pix) * 4);
-                    if constexpr (HAS_SC) {
-                        if (rt0 + r < rt_end)
-                            sv[p][r][q] = __builtin_bit_cast(f32x4, (u32x4)__builtin_amdgcn_raw_buffer_load_b128(sr, offs[p][r][q], 0, 0));
-                    }
-                }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int p = 0; p < NPT; ++p) {
-#pragma unroll
-            for (int r = 0; r < NRT; ++r) {
-                if (rt0 + r >= rt_end) continue;
-#pragma unroll
-                for (int q = 0; q < M::NQ; ++q) {
-                    float v[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[e] = acc[r][p][q * 4 + e];
-                        if (c.relu) v[e] = fmaxf(v[e], 0.f);
-                    }
-                    quad_transpose(v);
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        if constexpr (HAS_SC) v[k] += sv[p][r][q][k];
-                        if (relu_out) v[k] = fmaxf(v[k], 0.f);
-                    }
-                    const int nv = (rt0 + r) * MF + M::quad_row(q, sub) + t < c.cout ? nvs[p] : 0;
-                    const unsigned off = offs[p][r][q];
-                    if (nv == 4) {
-                        const f32x4 o = {v[0], v[1], v[2], v[3]};
-                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), yr, off, 0, 0);
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < 3; ++k)
-                            if (k < nv) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[k]), yr, off + 4 * k, 0, 0);
-                    }
-                }
-            }
-        }
-        return;
-    }
-
+    // ---- one 4-byte store per accumulator: a lane keeps its pixel, the channel moves through the scalar
+    // offset of the buffer instruction (the lane half's +4 channels ride in the lane's own offset), so an
+    // element costs one activation and one store, with 32 consecutive pixels of a channel per instruction
+    // half.  A vector instruction costs a SIMD about an eighth of a 32x32x2 matrix operation and the two
+    // do not overlap, so this beats gathering 16-byte rows through cross-lane moves.
+    const unsigned long long ybytes = ((unsigned long long)(P.N - n) * P.Cy - coff) * plane * 4ull;
+    const __amdgpu_buffer_rsrc_t yr = make_rsrc(yn, ybytes);
+    __amdgpu_buffer_rsrc_t sr = yr;
+    if constexpr (HAS_SC) sr = make_rsrc(scn, (unsigned long long)(P.N - n) * P.Csc * plane * 4ull);
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
         const int oy = fdiv(pidx, rcp_vw), ox = pidx - oy * vw;
         const int gy = oy0 + oy, gx = ox0 + ox;
         const bool pv = oy < th && ox < tw && gy < P.Ho && gx < P.Wo;
-        const int pix = pv ? gy * P.Wo + gx : 0;
+        const unsigned voff = (unsigned)((gy * P.Wo + gx + sub * 4 * plane) * 4);
+        if (!pv) continue;
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
             if (rt0 + r >= rt_end) continue;
+            const int cb = __builtin_amdgcn_readfirstlane((rt0 + r) * MF);       // first channel of the row tile (wave-uniform)
+            const bool full = cb + MF <= c.cout;
             float sv[M::NQ * 4];
             if constexpr (HAS_SC) {
 #pragma unroll
                 for (int e = 0; e < M::NQ * 4; ++e) {
-                    const int co = min((rt0 + r) * MF + M::quad_row(e >> 2, sub) + (e & 3), c.cout - 1);
-                    sv[e] = scn[co * plane + pix];
+                    const int cu = cb + M::quad_row(e >> 2, 0) + (e & 3);            // channel of lane half 0
+                    sv[e] = (full || cu + sub * 4 < c.cout)
+                                ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(sr, voff, cu * plane * 4, 0))
+                                : 0.f;
                 }
             }
-            float res[M::NQ * 4];
 #pragma unroll
             for (int e = 0; e < M::NQ * 4; ++e) {
+                const int cu = cb + M::quad_row(e >> 2, 0) + (e & 3);
                 float v = acc[r][p][e];
                 if (c.relu) v = fmaxf(v, 0.f);
                 if constexpr (HAS_SC) v += sv[e];
                 if (relu_out) v = fmaxf(v, 0.f);
-                res[e] = v;
-            }
-            // one mask for the pixel; the per-channel check is only needed in the last, partial row tile
-            const bool full = (rt0 + r + 1) * MF <= c.cout;
-            if (pv) {
-                if (full) {
-#pragma unroll
-                    for (int e = 0; e < M::NQ * 4; ++e)
-                        yn[((rt0 + r) * MF + M::quad_row(e >> 2, sub) + (e & 3)) * plane + pix] = res[e];
-                } else {
-#pragma unroll
-                    for (int e = 0; e < M::NQ * 4; ++e) {
-                        const int co = (rt0 + r) * MF + M::quad_row(e >> 2, sub) + (e & 3);
-                        if (co < c.cout) yn[co * plane + pix] = res[e];
-                    }
-                }
+                if (full || cu + sub * 4 < c.cout)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yr, voff, cu * plane * 4, 0);
             }
         }
     }
