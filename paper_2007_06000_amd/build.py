@@ -18,7 +18,8 @@ LIB = os.path.join(HERE, "libxl.so")
 # (source, object name, extra defines): kernels.hip is compiled twice, the split-bf16 variants on their own
 SOURCES = [("kernels.hip", "kernels", []), ("kernels.hip", "kernels_b3", ["-DXL_TU_B3"]),
            ("plan.cpp", "plan", []), ("api.cpp", "api", []), ("static_run.hip", "static_run", [])]
-HEADERS = [os.path.join(CSRC, "xl_internal.h"), os.path.join(CSRC, "plan.h"), os.path.join(ROOT, "include", "xl.h")]
+HEADERS = [os.path.join(CSRC, "xl_internal.h"), os.path.join(CSRC, "plan.h"), os.path.join(CSRC, "thin_conv.h"),
+           os.path.join(ROOT, "include", "xl.h")]
 
 # packed-fp32 instructions are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

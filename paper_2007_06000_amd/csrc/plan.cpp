@@ -266,7 +266,7 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     c.tiles_x = ceil_div(b.Wo, tw);
                     c.csplit = 1;
                     c.chunk_kg = 1;
-                    c.lds_bytes = pooled ? 2 * 16 * threads * 4 + rows16 * 4 : 0;      // two tiles of 16 channels x one float per lane, the shifts
+                    c.lds_bytes = pooled ? 2 * 8 * threads * 4 : 0;      // two tiles of 8 channels x one float per lane
                     if (c.lds_bytes > pl.lds_budget) {
                         any_lds_reject = true;
                         continue;

@@ -11,8 +11,8 @@
 //     address space; it is a few KB and stays in the scalar cache) and enters v_fmac_f32 as its scalar
 //     operand.  No filter in LDS, no staging through registers;
 //   - a following max pooling (paper Fig. 3b: Layer2 consumes Layer1's output on chip) takes the
-//     convolution outputs of 16 channels at a time from an LDS tile (two tiles alternate, one barrier
-//     per 16 channels): the convolution output never reaches HBM.  Bias and ReLU are applied after the
+//     convolution outputs of 8 channels at a time from an LDS tile (two tiles alternate, one barrier
+//     per 8 channels): the convolution output never reaches HBM.  Bias and ReLU are applied after the
 //     maximum (both are monotonic, so the result is bit-identical to applying them first).  PK is the
 //     pooling window (0: no pooling); which pooled pixels a lane takes does not depend on the channel
 //     chunk and is worked out once.
@@ -24,12 +24,12 @@
 // in, aff: shift as [Cout rounded up to 16] floats; stride, pad, relu, cout), pool_k (0: no pooling),
 // s2 / P2 (stride / padding of the pooling), th x tw (output tile), mh x mw (tile of convolution outputs
 // under it, at most blockDim.x pixels), rcp_mw, rcp_vw2 (for tw), rcp_qrow (for th * tw), tiles_x,
-// tiles_y, nblocks.  LDS: two tiles of 16 x blockDim.x floats, then the shifts (Cout rounded up to 16).
+// tiles_y, nblocks.  LDS: two tiles of THIN_OCB x blockDim.x floats.
 #pragma once
 
 namespace xl {
 
-constexpr int THIN_OCB = 16;        // output channels per LDS tile (per barrier)
+constexpr int THIN_OCB = 8;         // output channels per LDS tile (per barrier)
 
 template <int CIN, int K, int PK>
 __global__ void __launch_bounds__(MAX_THREADS) thin_conv_kernel(const BlockParams P)
@@ -101,8 +101,7 @@ __global__ void __launch_bounds__(MAX_THREADS) thin_conv_kernel(const BlockParam
         constexpr int NI = 4;
         const int ntile = P.th * P.tw;
         const int nitems = OCB * ntile;
-        float *shift_l = lds + 2 * OCB * nthreads;                            // the shifts, for lanes that differ in channel
-        for (int i = tid; i < nchunks * OCB; i += nthreads) shift_l[i] = reinterpret_cast<const float *>(P.c1.aff)[i];
+        const float *shift_v = reinterpret_cast<const float *>(P.c1.aff);     // the shifts, for lanes that differ in channel
         int i_src[NI], i_o[NI];
         unsigned i_dst[NI];
         auto item = [&](int it, int &src, int &o, unsigned &dst) {
@@ -118,7 +117,7 @@ __global__ void __launch_bounds__(MAX_THREADS) thin_conv_kernel(const BlockParam
 #pragma unroll
         for (int k = 0; k < NI; ++k)
             if (tid + k * nthreads >= nitems) i_dst[k] = ~0u;
-        auto pool_store = [&](const float *buf, int ch, int src, int o, unsigned dst) {
+        auto pool_store = [&](const float *buf, int ch, int src, int o, unsigned dst, float sh) {
             const int oc = ch * OCB + o;
             const float *sp = buf + src;
             float m = sp[0];
@@ -127,13 +126,18 @@ __global__ void __launch_bounds__(MAX_THREADS) thin_conv_kernel(const BlockParam
 #pragma unroll
                 for (int v = 0; v < PK; ++v)
                     if (u + v > 0) m = fmaxf(m, sp[u * P.mw + v]);
-            m += shift_l[oc];
+            m += sh;
             if (P.c1.relu) m = fmaxf(m, 0.f);
+            // (the channel differs from lane to lane here: it goes into the lane's own offset, not the scalar one)
             if (oc < cout && dst != ~0u)
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, m), yr, dst, oc * (int)oplane * 4, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, m), yr, dst + (unsigned)(oc * (int)oplane * 4), 0, 0);
         };
         for (int ch = 0; ch < nchunks; ++ch) {
             float *buf = lds + (ch & 1) * OCB * nthreads;
+            // the shifts of this lane's pooled items: requested now, needed after the multiply-adds
+            float sh[NI];
+#pragma unroll
+            for (int k = 0; k < NI; ++k) sh[k] = shift_v[ch * OCB + i_o[k]];
             // two channels at a time: their filter rows arrive with one wait, and the two chains of multiply-adds
             // alternate
             for (int o = 0; o < OCB; o += 2) {
@@ -158,12 +162,12 @@ __global__ void __launch_bounds__(MAX_THREADS) thin_conv_kernel(const BlockParam
             __syncthreads();
 #pragma unroll
             for (int k = 0; k < NI; ++k)
-                if (k * nthreads < nitems) pool_store(buf, ch, i_src[k], i_o[k], i_dst[k]);
+                if (k * nthreads < nitems) pool_store(buf, ch, i_src[k], i_o[k], i_dst[k], sh[k]);
             for (int it = tid + NI * nthreads; it < nitems; it += nthreads) {
                 int src, o;
                 unsigned dst;
                 item(it, src, o, dst);
-                pool_store(buf, ch, src, o, dst);
+                pool_store(buf, ch, src, o, dst, shift_v[ch * OCB + o]);
             }
             // the next chunk goes to the other tile; this one is overwritten two chunks on, after the barrier in between
         }
@@ -176,7 +180,7 @@ __global__ void pack_thin_kernel(const float *__restrict__ w, const float *__res
                                  const float *__restrict__ shift, float *__restrict__ wp, float *__restrict__ aff,
                                  int cout, int taps)
 {
-    const int rows = (cout + THIN_OCB - 1) / THIN_OCB * THIN_OCB;
+    const int rows = (cout + 15) / 16 * 16;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx < rows * taps) {
         const int oc = idx / taps;
