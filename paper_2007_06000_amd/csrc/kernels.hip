@@ -21,6 +21,7 @@
 // of a lane therefore hold 4 consecutive output channels of one pixel, which
 // is exactly one float4 of the LDS tile layout.
 #include <float.h>
+#include <limits.h>
 
 #include <tuple>
 #include <type_traits>
@@ -91,6 +92,15 @@ __device__ __forceinline__ void zero_acc(Acc &a)
 #pragma unroll
     for (int i = 0; i < (int)(sizeof(Acc) / sizeof(float)); ++i) a[i] = 0.f;
 }
+
+// max(v, lo) taken on the bit patterns as signed integers, one instruction with `lo` a scalar operand:
+// lo = 0 is ReLU (a float with the sign set is a negative integer; -0 becomes +0), lo = INT_MIN the identity.
+// So an activation that is switched by a run-time flag costs no compare and no select.
+__device__ __forceinline__ float relu_from(float v, int lo)
+{
+    return __builtin_bit_cast(float, max(__builtin_bit_cast(int, v), lo));
+}
+__device__ __forceinline__ int relu_bound(int on) { return on ? 0 : INT_MIN; }
 
 // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2.
 // Map hardware block id -> logical id so that consecutive logical ids (tiles of
@@ -602,7 +612,6 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
                                              int rt0, int rt_end, int pt0, int relu_out, unsigned rcp_vw)
 {
     typedef MM<MF> M;
-    typedef unsigned u32x4 __attribute__((vector_size(16)));
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
     // per-image element counts fit 30 bits (checked by the planner): 32-bit offsets from uniform bases
@@ -620,6 +629,8 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
     const __amdgpu_buffer_rsrc_t yr = make_rsrc(yn, ybytes);
     __amdgpu_buffer_rsrc_t sr = yr;
     if constexpr (HAS_SC) sr = make_rsrc(scn, (unsigned long long)(P.N - n) * P.Csc * plane * 4ull);
+    const int lo1 = relu_bound(c.relu), lo2 = relu_bound(relu_out);
+    const int lo12 = max(lo1, lo2);
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -632,27 +643,31 @@ __device__ __forceinline__ void store_global(const typename MM<MF>::Acc (&acc)[N
         for (int r = 0; r < NRT; ++r) {
             if (rt0 + r >= rt_end) continue;
             const int cb = __builtin_amdgcn_readfirstlane((rt0 + r) * MF);       // first channel of the row tile (wave-uniform)
-            const bool full = cb + MF <= c.cout;
-            float sv[M::NQ * 4];
-            if constexpr (HAS_SC) {
+            // a row tile that lies wholly below Cout (wave-uniform, and the common case) needs no per-element test
+            auto row_tile = [&](auto checked) {
+                constexpr bool CHECKED = decltype(checked)::value;
+                float sv[M::NQ * 4];
+                if constexpr (HAS_SC) {
+#pragma unroll
+                    for (int e = 0; e < M::NQ * 4; ++e) {
+                        const int cu = cb + M::quad_row(e >> 2, 0) + (e & 3);            // channel of lane half 0
+                        sv[e] = (!CHECKED || cu + sub * 4 < c.cout)
+                                    ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(sr, voff, cu * plane * 4, 0))
+                                    : 0.f;
+                    }
+                }
 #pragma unroll
                 for (int e = 0; e < M::NQ * 4; ++e) {
-                    const int cu = cb + M::quad_row(e >> 2, 0) + (e & 3);            // channel of lane half 0
-                    sv[e] = (full || cu + sub * 4 < c.cout)
-                                ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(sr, voff, cu * plane * 4, 0))
-                                : 0.f;
+                    const int cu = cb + M::quad_row(e >> 2, 0) + (e & 3);
+                    float v;
+                    if constexpr (HAS_SC) v = relu_from(relu_from(acc[r][p][e], lo1) + sv[e], lo2);
+                    else v = relu_from(acc[r][p][e], lo12);
+                    if (!CHECKED || cu + sub * 4 < c.cout)
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yr, voff, cu * plane * 4, 0);
                 }
-            }
-#pragma unroll
-            for (int e = 0; e < M::NQ * 4; ++e) {
-                const int cu = cb + M::quad_row(e >> 2, 0) + (e & 3);
-                float v = acc[r][p][e];
-                if (c.relu) v = fmaxf(v, 0.f);
-                if constexpr (HAS_SC) v += sv[e];
-                if (relu_out) v = fmaxf(v, 0.f);
-                if (full || cu + sub * 4 < c.cout)
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yr, voff, cu * plane * 4, 0);
-            }
+            };
+            if (cb + MF <= c.cout) row_tile(std::false_type{});
+            else row_tile(std::true_type{});
         }
     }
 }
@@ -674,6 +689,7 @@ __device__ __forceinline__ void store_gap(const typename MM<MF>::Acc (&acc)[NRT]
     const int rows_wg = wg_rt * MF;
     if (active) {
         asm volatile("" ::: "memory");
+        const int lo = max(relu_bound(c.relu), relu_bound(P.relu_out));
         float s[NRT][M::NQ * 4];
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
@@ -682,9 +698,7 @@ __device__ __forceinline__ void store_gap(const typename MM<MF>::Acc (&acc)[NRT]
                 float t = 0.f;
 #pragma unroll
                 for (int p = 0; p < NPT; ++p) {
-                    float v = acc[r][p][e];
-                    if (c.relu) v = fmaxf(v, 0.f);
-                    if (P.relu_out) v = fmaxf(v, 0.f);
+                    const float v = relu_from(acc[r][p][e], lo);
                     t += ((pt0 + p) * MF + col < npx) ? v : 0.f;
                 }
                 // lanes of one `sub` hold the MF pixels of this channel: butterfly over the column bits
@@ -734,6 +748,7 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
     const int lane = threadIdx.x & 63;
     const int sub = lane / MF, col = lane % MF;
     asm volatile("" ::: "memory");      // keeps the epilogue's address arithmetic out of the K loop's schedule
+    const int lo1 = relu_bound(c.relu), lo2 = relu_bound(relu_sum);
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -743,6 +758,8 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
 #pragma unroll
         for (int r = 0; r < NRT; ++r) {
             if (rt0 + r >= rt_end) continue;
+            // only a row tile that reaches past Cout (wave-uniform) has channels to blank
+            const bool partial = __builtin_amdgcn_readfirstlane((rt0 + r + 1) * MF) > c.cout;
 #pragma unroll
             for (int q = 0; q < M::NQ; ++q) {
                 const int cb = (rt0 + r) * MF + M::quad_row(q, sub);
@@ -765,14 +782,10 @@ __device__ __forceinline__ void store_mid(const typename MM<MF>::Acc (&acc)[NRT]
                 }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float z = acc[r][p][q * 4 + i];
-                    if (c.relu) z = fmaxf(z, 0.f);
-                    if (add) {
-                        z += old[i];
-                        if (relu_sum) z = fmaxf(z, 0.f);
-                    }
+                    float z = relu_from(acc[r][p][q * 4 + i], lo1);
+                    if (add) z = relu_from(z + old[i], lo2);
                     if (!inside) z = fill;
-                    if (cb + i >= c.cout) z = 0.f;
+                    if (partial && cb + i >= c.cout) z = 0.f;
                     v[i] = z;
                 }
                 if constexpr (PR) {
@@ -805,6 +818,7 @@ __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT
     const int sub = lane / MF, col = lane % MF;
     const int npx = P.th * P.tw;
     asm volatile("" ::: "memory");
+    const int lo = relu_bound(c.relu);
 #pragma unroll
     for (int p = 0; p < NPT; ++p) {
         const int pidx = (pt0 + p) * MF + col;
@@ -820,9 +834,7 @@ __device__ __forceinline__ void store_tile(const typename MM<MF>::Acc (&acc)[NRT
                 f32x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float z = acc[r][p][q * 4 + i];
-                    if (c.relu) z = fmaxf(z, 0.f);
-                    v[i] = inside ? z : -FLT_MAX;
+                    v[i] = inside ? relu_from(acc[r][p][q * 4 + i], lo) : -FLT_MAX;
                 }
                 if (valid) *(f32x4 *)(tile + ((cl >> 2) * npx + oy * P.tw + ox) * 4) = v;
             }
