@@ -42,10 +42,18 @@ TUNE = True                    # xl_tune picks tiles by measurement once, outsid
 def time_steps(fn, steps, warmup, torch):
     """EXACTLY `steps` timed steps between two synchronisations; also the duration of every single step
     from events recorded between them (no synchronisation inside the timed region)."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    for e in ev:            # an event gets its device resources at its first record: not inside the timed region
+        e.record()
     for i in range(warmup):
         fn(i)
     torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    # rehearsal: the timed loop once, untimed and complete with its events, so that whatever the runtime sizes by the
+    # number of launches in flight (the host runs many steps ahead of the device) has its size before the clock starts
+    for i in range(steps):
+        fn(warmup + i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
     for i in range(steps):
@@ -55,7 +63,8 @@ def time_steps(fn, steps, warmup, torch):
     wall = (time.perf_counter() - t0) * 1e3
     each = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
     return {"mean": ev[0].elapsed_time(ev[steps]) / steps, "median": statistics.median(each), "min": min(each),
-            "wall": wall / steps}
+            "max": max(each), "slowest_step": each.index(max(each)), "wall": wall / steps,
+            "slowest5": sorted(((round(t, 3), i) for i, t in enumerate(each)), reverse=True)[:5]}
 
 
 def bound_of(flops, nbytes, mfma_peak):
@@ -65,34 +74,73 @@ def bound_of(flops, nbytes, mfma_peak):
     return ("mfma", t_m) if t_m >= t_h else ("hbm", t_h)
 
 
+def group_layers(plan, wl, g):
+    """Layer indices of block g of the plan (blocks are in graph order; layers outside every declared block are
+    blocks of their own)."""
+    q = plan.query(g)
+    for grp in wl.groups:
+        if grp.layers[0] == q["first_layer"]:
+            return list(grp.layers)
+    return list(range(q["first_layer"], q["first_layer"] + q["nlayers"]))
+
+
+def switched_blocks(plan, wl):
+    return [g for g in range(plan.num_groups) if len(group_layers(plan, wl, g)) > 1 and not plan.block_is_fused(g)]
+
+
 def launch_rows(s, mfma_peak, reps):
-    """Per-launch table of the fused step: xl_profile durations joined with the plan's facts."""
+    """Per-block table of the fused step: xl_profile durations joined with the plan's facts.  A block that
+    xl_tune switched to layer-by-layer execution is several launches; its row sums them."""
     plan, wl = s.plan, s.workload
     us_f = plan.profile(s.tensor_ptrs, s.workspace.data_ptr(), s.stream, True, reps)
     us_u = plan.profile(s.tensor_ptrs, s.workspace.data_ptr(), s.stream, False, reps)
     layer_us = {}
     for l, t in enumerate(us_u):
         layer_us[plan.candidate_info(False, l)["first_layer"]] = t
-    rows = []
+    rows, by_group = [], {}
     for l, t in enumerate(us_f):
         info = plan.candidate_info(True, l)
-        q = plan.query(info["group"])
-        layers = list(range(info["first_layer"], info["first_layer"] + info["nlayers"]))
-        layers = [i for i in wl.groups[info["group"]].layers] if info["group"] < len(wl.groups) else layers
+        g = info["group"]
+        if g in by_group:           # a further layer of a block run layer by layer
+            r = by_group[g]
+            r["us"] += t
+            r["launches"] += 1
+            r["variant"].append(info["variant"])
+            continue
+        q = plan.query(g)
+        layers = group_layers(plan, wl, g)
+        fused = plan.block_is_fused(g) or len(layers) == 1
         bound, t_roof = bound_of(q["flops"], q["bytes_fused"], mfma_peak)
-        rows.append({
-            "launch": l, "layers": f"{wl.layers[layers[0]].name}..{wl.layers[layers[-1]].name}" if len(layers) > 1 else wl.layers[layers[0]].name,
-            "mode": ["single", "straight", "split", "merge"][q["mode"]],
+        r = {
+            "launch": l, "launches": 1,
+            "layers": f"{wl.layers[layers[0]].name}..{wl.layers[layers[-1]].name}" if len(layers) > 1 else wl.layers[layers[0]].name,
+            "mode": ["single", "straight", "split", "merge"][q["mode"]], "runs_fused": fused,
             "us": t, "us_unfused_layers": sum(layer_us.get(i, 0.0) for i in layers),
             "flops": q["flops"], "alg_bytes": q["bytes_fused"], "alg_bytes_unfused": q["bytes_unfused"],
-            "bound": bound, "roofline_us": t_roof * 1e3, "frac": t_roof * 1e3 / t if t > 0 else None,
-            "mfma_frac": q["flops"] / (t * 1e-6) / (mfma_peak * 1e12) if t > 0 else None,
-            "hbm_frac": q["bytes_fused"] / (t * 1e-6) / (HBM_PEAK_GBS * 1e9) if t > 0 else None,
-            "variant": info["variant"], "candidate": info["candidate"], "tile": [info["tile_h"], info["tile_w"]],
+            "bound": bound, "roofline_us": t_roof * 1e3,
+            "variant": [info["variant"]], "candidate": info["candidate"], "tile": [info["tile_h"], info["tile_w"]],
             "threads": info["threads"], "cout_split": info["cout_split"], "lds_bytes": info["lds_bytes"],
-            "redundancy": q["redundancy"],
-        })
+            "redundancy": q["redundancy"] if fused else 1.0,
+        }
+        by_group[g] = r
+        rows.append(r)
+    for r in rows:
+        t = r["us"]
+        r["frac"] = r["roofline_us"] / t if t > 0 else None
+        r["mfma_frac"] = r["flops"] / (t * 1e-6) / (mfma_peak * 1e12) if t > 0 else None
+        r["hbm_frac"] = r["alg_bytes"] / (t * 1e-6) / (HBM_PEAK_GBS * 1e9) if t > 0 else None
+        if len(r["variant"]) == 1:
+            r["variant"] = r["variant"][0]
     return rows, us_u
+
+
+def apply_candidates(plan, saved):
+    """Adopt a saved launch configuration: first which blocks run layer by layer (that fixes the launch list of
+    the fused path), then the candidate of every launch."""
+    for g in range(plan.num_groups):
+        plan.set_block_fused(g, g not in saved["layer_by_layer_blocks"])
+    for fused, launch, cand in saved["candidates"]:
+        plan.select_candidate(bool(fused), launch, cand)
 
 
 def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True, precision=0, candidates=None, fused_only=False,
@@ -101,8 +149,7 @@ def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True, precisi
     x, params = W.make_tensors(wl)
     s = Session(wl, x, params, tune=TUNE and candidates is None, precision=precision)
     if candidates is not None:
-        for fused, launch, cand in candidates:
-            s.plan.select_candidate(bool(fused), launch, cand)
+        apply_candidates(s.plan, candidates)
     mfma_peak = MFMA_BF16_PEAK_TFLOPS / 3.0 if precision else MFMA_FP32_PEAK_TFLOPS
     in_bytes = x.nbytes
     out_bytes = int(np.prod(wl.shapes[wl.output_id])) * 4
@@ -135,7 +182,8 @@ def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True, precisi
     bound = bound_of(flops, bytes_f, mfma_peak)[0] if len(groups) == 1 else "per launch"
     res = {
         "workload": wl.name, "batch": wl.batch,
-        "ms_fused": ms_f, "ms_fused_median": tf["median"], "ms_fused_min": tf["min"],
+        "ms_fused": ms_f, "ms_fused_median": tf["median"], "ms_fused_min": tf["min"], "ms_fused_max": tf["max"],
+        "slowest_step": tf["slowest_step"], "slowest5": tf["slowest5"],
         "ms_unfused": ms_u, "ms_unfused_median": tu["median"], "ms_unfused_min": tu["min"], "wall_ms_fused": tf["wall"],
         "images_per_s": wl.batch / ms_f * 1e3,
         "speedup_vs_unfused": ms_u / ms_f,
@@ -147,6 +195,7 @@ def bench_workload(cfg, steps, warmup, torch, np, W, Session, cold=True, precisi
         "mfma_frac": flops / ms_f / 1e9 / mfma_peak,
         "bound": bound, "roofline_ms": t_roof, "frac": t_roof / ms_f,
         "buffer_sets": sets,
+        "blocks_run_layer_by_layer": [wl.layers[group_layers(s.plan, wl, g)[0]].name for g in switched_blocks(s.plan, wl)],
         "adopted": [{k: s.plan.candidate_info(True, l)[k] for k in ("variant", "candidate", "tile_h", "tile_w", "threads",
                                                                       "cout_split", "lds_bytes")}
                     for l in range(s.plan.num_launches(True))],
@@ -249,7 +298,7 @@ def main():
 
     candidates = None
     if args.load_candidates:
-        candidates = json.load(open(args.load_candidates))["candidates"]
+        candidates = json.load(open(args.load_candidates))
 
     if args.traffic_probe:
         traffic_probe(args.workload, torch, np, W, Session, candidates)
@@ -267,8 +316,9 @@ def main():
         for fused in (1, 0):
             for l in range(s.plan.num_launches(bool(fused))):
                 cands.append([fused, l, s.plan.candidate_info(bool(fused), l)["candidate"]])
-        json.dump({"workload": wl.name, "batch": wl.batch, "precision": args.precision, "candidates": cands},
-                  open(args.save_candidates, "w"))
+        json.dump({"workload": wl.name, "batch": wl.batch, "precision": args.precision,
+                   "layer_by_layer_blocks": switched_blocks(s.plan, wl),
+                   "candidates": cands}, open(args.save_candidates, "w"))
     if profiler_run:
         print(json.dumps({"profiler_run": wl.name, "ms_per_step": res["ms_fused"], "steps": args.steps, "adopted": res["adopted"]}))
         return
@@ -284,6 +334,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 hi+lo operands (3 products), f32 accumulate" if prec else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "launches_per_step": res["launches_fused"],
+                   "blocks_run_layer_by_layer": res["blocks_run_layer_by_layer"],
                    "buffers": "inputs, outputs and workspaces rotate over > 512 MB (cold)" if not args.warm else "single set (warm)",
                    "tiles": ("xl_tune (measured, median of 5)" if TUNE else "cost model") if candidates is None else "from file"},
         "ms_per_step_median": res["ms_fused_median"], "ms_per_step_min": res["ms_fused_min"],
@@ -379,8 +430,7 @@ def traffic_probe(cfg, torch, np, W, Session, candidates):
     x, params = W.make_tensors(wl)
     s = Session(wl, x, params, tune=TUNE and candidates is None)
     if candidates is not None:
-        for fused, launch, cand in candidates:
-            s.plan.select_candidate(bool(fused), launch, cand)
+        apply_candidates(s.plan, candidates)
     torch.empty(12345, dtype=torch.float32, device="cuda").fill_(1.0)     # marker: measured passes start here
     for fused in (True, False):
         for _ in range(3):

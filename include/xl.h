@@ -132,6 +132,8 @@ typedef struct xl_options {
                                Tensors in memory stay fp32.
                                A depthwise first layer stays on the vector ALU in fp32; xl_tune may
                                keep an fp32 kernel for a block where it measures faster. */
+    int keep_blocks_fused;  /* 1: xl_tune never switches a block to layer-by-layer execution (see
+                               xl_plan_set_block_fused)                                            */
 } xl_options;
 #define XL_PRECISION_FP32   0
 #define XL_PRECISION_BF16X3 1
@@ -240,6 +242,10 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
  * repeatedly; call it once, outside any timed region.  Every candidate is timed three times (fastest
  * kept) and the six fastest again `reps` times each (reps < 5 means 5), ranked by their MEDIAN
  * time; ties go to the lower candidate index.  xl_plan_candidate_info(.., -1, ..) names the winner.
+ * Last, a block whose layers run one kernel each in less than 0.95 of the time of its fused kernel
+ * (both medians of this call) is switched to layer-by-layer execution inside the fused path, as by
+ * xl_plan_set_block_fused(.., 0), and every other block is (re)set to fused; options.keep_blocks_fused = 1
+ * leaves that step out.
  */
 xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors,
                   void *workspace, void *stream, int reps);
@@ -334,6 +340,21 @@ xl_status xl_plan_candidate_info(const xl_plan *plan, int fused, int launch, int
 /* Adopts candidate `candidate` for a launch: later xl_run calls use it, and xl_plan_query reports
  * its tiles for the launch's block.  Host only; must not race with xl_run on the same plan. */
 xl_status xl_plan_select_candidate(xl_plan *plan, int fused, int launch, int candidate);
+
+/*
+ * Fused or layer by layer.  Cross-layer reuse pays when the intermediate tensor would otherwise travel
+ * through off-chip memory (paper section 3.1); where it would not -- images of a few hundred pixels at a
+ * batch that cannot fill the chip with whole tiles, a batch of 1 -- the halo recomputation and the
+ * larger workgroups of a fused block (paper section 3.2: the tile size is a trade-off) can cost more than
+ * the reuse saves.  fused = 0 makes xl_run(.., fused = 1) execute the layers of block `group` one kernel each,
+ * exactly as the unfused path does, in the block's place; fused = 1 restores the block's kernel.  Blocks of
+ * one layer ignore the call.  The launch list of the fused path changes with it: xl_plan_num_launches,
+ * the launch indices of the candidate functions and of xl_profile follow the current list.
+ * xl_plan_block_is_fused: 1 if the block (of at least two layers) currently runs as one kernel, else 0.
+ * Not thread-safe against concurrent xl_run on the same plan.  XL_E_GRAPH for an unknown block.
+ */
+xl_status xl_plan_set_block_fused(xl_plan *plan, int group, int fused);
+int xl_plan_block_is_fused(const xl_plan *plan, int group);
 
 /*
  * The paper's tuner search space (section 3.2): square tiles whose size and

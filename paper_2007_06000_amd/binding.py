@@ -30,6 +30,7 @@ EXPORTS = [
     "xl_prepare", "xl_run", "xl_tune", "xl_plan_num_launches", "xl_tuner_candidates", "xl_required_extent",
     "xl_strerror", "xl_plan_last_error", "xl_version",
     "xl_plan_num_candidates", "xl_plan_candidate_info", "xl_plan_select_candidate", "xl_run_static", "xl_profile", "xl_measure_peaks",
+    "xl_plan_set_block_fused", "xl_plan_block_is_fused",
 ]
 
 
@@ -53,7 +54,8 @@ class xl_options(ctypes.Structure):
     _fields_ = [("lds_budget_bytes", ctypes.c_int), ("num_cus", ctypes.c_int),
                 ("force_tile_h", ctypes.c_int), ("force_tile_w", ctypes.c_int),
                 ("force_cout_split", ctypes.c_int), ("paper_tuner_only", ctypes.c_int),
-                ("force_threads", ctypes.c_int), ("precision", ctypes.c_int)]
+                ("force_threads", ctypes.c_int), ("precision", ctypes.c_int),
+                ("keep_blocks_fused", ctypes.c_int)]
 
 
 class xl_group_info(ctypes.Structure):
@@ -136,6 +138,10 @@ def lib() -> ctypes.CDLL:
         L.xl_plan_candidate_info.restype = i
         L.xl_plan_select_candidate.argtypes = [vp, i, i, i]
         L.xl_plan_select_candidate.restype = i
+        L.xl_plan_set_block_fused.argtypes = [vp, i, i]
+        L.xl_plan_set_block_fused.restype = i
+        L.xl_plan_block_is_fused.argtypes = [vp, i]
+        L.xl_plan_block_is_fused.restype = i
         L.xl_run_static.argtypes = [vp, ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, vp, i, i]
         L.xl_run_static.restype = i
         L.xl_profile.argtypes = [vp, ctypes.POINTER(vp), i, vp, vp, i, i, ctypes.POINTER(ctypes.c_float), i]
@@ -261,6 +267,12 @@ class Plan:
 
     def select_candidate(self, fused: bool, launch: int, candidate: int):
         self._check(lib().xl_plan_select_candidate(self.handle, int(fused), launch, candidate))
+
+    def set_block_fused(self, group: int, fused: bool):
+        self._check(lib().xl_plan_set_block_fused(self.handle, group, int(fused)))
+
+    def block_is_fused(self, group: int) -> bool:
+        return bool(lib().xl_plan_block_is_fused(self.handle, group))
 
     def prepare(self, weight_ptrs: Sequence[Optional[int]], workspace_ptr: int, stream: int = 0):
         arr = (ctypes.c_void_p * self.nweights)(*[ctypes.c_void_p(p) if p else None for p in weight_ptrs])

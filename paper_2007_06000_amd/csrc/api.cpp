@@ -131,7 +131,44 @@ size_t xl_plan_workspace_bytes(const xl_plan *plan) { return plan ? plan->worksp
 int xl_plan_num_launches(const xl_plan *plan, int fused)
 {
     if (!plan) return 0;
-    return (int)(fused ? plan->fused_steps.size() : plan->unfused_steps.size());
+    return (int)(fused ? plan->fused_active.size() : plan->unfused_steps.size());
+}
+
+// The launches of one execution mode, in order.
+static std::vector<const xl::Step *> launches_of(const xl_plan *plan, int fused)
+{
+    std::vector<const xl::Step *> v;
+    if (fused) {
+        v.assign(plan->fused_active.begin(), plan->fused_active.end());
+    } else {
+        v.reserve(plan->unfused_steps.size());
+        for (const xl::Step &st : plan->unfused_steps) v.push_back(&st);
+    }
+    return v;
+}
+
+// Fusion block a layer belongs to (-1: none).
+static int group_of_layer(const xl_plan *plan, int layer)
+{
+    for (size_t g = 0; g < plan->groups.size(); ++g)
+        for (int l : plan->groups[g].layers)
+            if (l == layer) return (int)g;
+    return -1;
+}
+
+int xl_plan_block_is_fused(const xl_plan *plan, int group)
+{
+    if (!plan || group < 0 || group >= (int)plan->groups.size()) return 0;
+    return plan->groups[group].layers.size() > 1 && !plan->layerwise[group];
+}
+
+xl_status xl_plan_set_block_fused(xl_plan *plan, int group, int fused)
+{
+    if (!plan) return XL_E_NULL;
+    if (group < 0 || group >= (int)plan->groups.size()) return XL_E_GRAPH;
+    plan->layerwise[group] = (fused || plan->groups[group].layers.size() < 2) ? 0 : 1;
+    xl::refresh_fused_path(*plan);
+    return XL_OK;
 }
 
 // The plan was sized for one device (compute units, LDS): that device must be the current one.
@@ -311,10 +348,16 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors, 
     if (rc != XL_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
-    for (const xl::Step &st : steps) {
-        rc = launch_step(plan, st, tensors, ws, s);
-        if (rc != XL_OK) return rc;
+    if (fused) {
+        for (const xl::Step *st : plan->fused_active) {
+            rc = launch_step(plan, *st, tensors, ws, s);
+            if (rc != XL_OK) return rc;
+        }
+    } else {
+        for (const xl::Step &st : plan->unfused_steps) {
+            rc = launch_step(plan, st, tensors, ws, s);
+            if (rc != XL_OK) return rc;
+        }
     }
     return XL_OK;
 }
@@ -325,7 +368,7 @@ xl_status xl_profile(const xl_plan *plan, const void *const *tensors, int ntenso
     xl_status rc = check_run_args(plan, tensors, ntensors, workspace);
     if (rc != XL_OK) return rc;
     if (!launch_us) return XL_E_NULL;
-    const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
+    const std::vector<const xl::Step *> steps = launches_of(plan, fused);
     const int n = (int)steps.size();
     if (cap < n) return run_fail(plan, XL_E_GRAPH, "launch_us has fewer entries than the mode has launches");
     if (reps < 1) reps = 5;
@@ -342,7 +385,7 @@ xl_status xl_profile(const xl_plan *plan, const void *const *tensors, int ntenso
         hipEvent_t *e = &ev[(size_t)r * (n + 1)];
         (void)hipEventRecord(e[0], s);
         for (int i = 0; i < n && rc == XL_OK; ++i) {
-            rc = launch_step(plan, steps[i], tensors, ws, s);
+            rc = launch_step(plan, *steps[i], tensors, ws, s);
             (void)hipEventRecord(e[i + 1], s);
         }
     }
@@ -401,6 +444,9 @@ xl_status xl_measure_peaks(void *dst, const void *src, size_t bytes, void *strea
     return rc;
 }
 
+// A block leaves the fused path for its layers' own kernels only when those measured this much faster.
+static constexpr float LAYERWISE_MARGIN = 0.95f;
+
 // Make candidate `idx` the configuration of step `st`; in the fused path the block's reported tiles follow.
 static void adopt(xl_plan *plan, xl::Step &st, int idx, bool fused)
 {
@@ -434,9 +480,8 @@ static void adopt(xl_plan *plan, xl::Step &st, int idx, bool fused)
 static const xl::Step *find_launch(const xl_plan *plan, int fused, int launch)
 {
     if (!plan) return nullptr;
-    const std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
-    if (launch < 0 || launch >= (int)steps.size()) return nullptr;
-    return &steps[launch];
+    if (fused) return launch >= 0 && launch < (int)plan->fused_active.size() ? plan->fused_active[launch] : nullptr;
+    return launch >= 0 && launch < (int)plan->unfused_steps.size() ? &plan->unfused_steps[launch] : nullptr;
 }
 
 int xl_plan_num_candidates(const xl_plan *plan, int fused, int launch)
@@ -456,7 +501,7 @@ xl_status xl_plan_candidate_info(const xl_plan *plan, int fused, int launch, int
     if (candidate < 0) candidate = st->adopted;
     const xl::Step &c = st->alts.empty() ? *st : st->alts[candidate];
     memset(out, 0, sizeof *out);
-    out->group = fused ? st->group : -1;
+    out->group = fused ? group_of_layer(plan, st->first_layer) : -1;
     out->first_layer = st->first_layer;
     out->nlayers = st->nlayers;
     out->candidate = candidate;
@@ -485,9 +530,9 @@ xl_status xl_plan_candidate_info(const xl_plan *plan, int fused, int launch, int
 xl_status xl_plan_select_candidate(xl_plan *plan, int fused, int launch, int candidate)
 {
     if (!plan) return XL_E_NULL;
-    std::vector<xl::Step> &steps = fused ? plan->fused_steps : plan->unfused_steps;
-    if (launch < 0 || launch >= (int)steps.size()) return XL_E_GRAPH;
-    xl::Step &st = steps[launch];
+    xl::Step *stp = const_cast<xl::Step *>(find_launch(plan, fused, launch));
+    if (!stp) return XL_E_GRAPH;
+    xl::Step &st = *stp;
     const int n = st.alts.empty() ? 1 : (int)st.alts.size();
     if (candidate < 0 || candidate >= n) return XL_E_GRAPH;
     if (!st.alts.empty()) adopt(plan, st, candidate, fused != 0);
@@ -518,9 +563,24 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
         std::vector<xl::Step> &steps = pass == 0 ? plan->fused_steps : plan->unfused_steps;
         for (xl::Step &st : steps) {
             if (st.type != xl::STEP_BLOCK || st.alts.size() < 2) {
-                // still run the step once so that later blocks time on produced data
-                rc = launch_step(plan, st, tensors, ws, s);
+                // nothing to choose, but the step is timed (the fused-or-not decision below needs it) and later
+                // blocks time on the data it produces
+                std::vector<float> t1;
+                for (int r = 0; r < reps && rc == XL_OK; ++r) {
+                    (void)hipEventRecord(e0, s);
+                    rc = launch_step(plan, st, tensors, ws, s);
+                    (void)hipEventRecord(e1, s);
+                    if (hipEventSynchronize(e1) != hipSuccess) {
+                        if (rc == XL_OK) rc = run_fail(plan, XL_E_LAUNCH, "a kernel failed while tuning");
+                        break;
+                    }
+                    float ms = 0.f;
+                    (void)hipEventElapsedTime(&ms, e0, e1);
+                    t1.push_back(ms);
+                }
                 if (rc != XL_OK) break;
+                std::sort(t1.begin(), t1.end());
+                st.tuned_us = t1[t1.size() / 2] * 1e3f;
                 continue;
             }
             // n timed launches of one candidate, sorted
@@ -566,7 +626,28 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
             }
             if (rc != XL_OK) break;
             adopt(plan, st, best, pass == 0);
+            st.tuned_us = best_ms * 1e3f;
         }
+    }
+    // A block whose layers, one kernel each, were measured clearly faster than its fused kernel runs layer by
+    // layer in the fused path (small images at a batch that cannot fill the chip with whole tiles, a batch
+    // of 1): the tuner only ever trades speed, and the fused path is then never the slower one.  The margin
+    // covers what single-launch timings on warm buffers cannot see (launches of a sequence overlap at their
+    // ends; intermediates that stay in cache here reach HBM in a long pipeline).
+    if (rc == XL_OK && !plan->opts.keep_blocks_fused) {
+        for (const xl::Step &st : plan->fused_steps) {
+            if (st.nlayers < 2 || st.group < 0 || st.tuned_us <= 0.f) continue;
+            const std::vector<int> &ls = plan->groups[st.group].layers;
+            float sum = 0.f;
+            bool all = true;
+            for (const xl::Step &u : plan->unfused_steps)
+                if (std::find(ls.begin(), ls.end(), u.first_layer) != ls.end()) {
+                    all = all && u.tuned_us > 0.f;
+                    sum += u.tuned_us;
+                }
+            plan->layerwise[st.group] = all && sum > 0.f && sum < LAYERWISE_MARGIN * st.tuned_us;
+        }
+        xl::refresh_fused_path(*plan);
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);

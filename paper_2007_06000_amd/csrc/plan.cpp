@@ -1188,7 +1188,30 @@ struct Builder {
 xl_status build_plan(xl_plan &pl, const xl_group *groups, int ngroups)
 {
     Builder b(pl);
-    return b.build(groups, ngroups);
+    const xl_status s = b.build(groups, ngroups);
+    if (s != XL_OK) return s;
+    pl.layerwise.assign(pl.groups.size(), 0);
+    refresh_fused_path(pl);
+    return XL_OK;
+}
+
+// The launches of the fused path: one step per block, except that a block switched to layer-by-layer
+// execution contributes the unfused steps of its layers, in layer order.  (Everything such a block reads
+// from outside is produced before its first layer -- fused_group checks that for the shortcut of a merge
+// block -- so running its layers at the block's position keeps every dependency.)
+void refresh_fused_path(xl_plan &pl)
+{
+    pl.fused_active.clear();
+    for (Step &st : pl.fused_steps) {
+        const bool split = st.nlayers > 1 && st.group >= 0 && st.group < (int)pl.layerwise.size() && pl.layerwise[st.group];
+        if (!split) {
+            pl.fused_active.push_back(&st);
+            continue;
+        }
+        const std::vector<int> &ls = pl.groups[st.group].layers;
+        for (Step &u : pl.unfused_steps)
+            if (std::find(ls.begin(), ls.end(), u.first_layer) != ls.end()) pl.fused_active.push_back(&u);
+    }
 }
 
 }  // namespace xl

@@ -56,6 +56,7 @@ struct Step {
     int adopted = 0;        // index into alts of the configuration this step currently is
     double cost_us = 0;     // the cost model's estimate
     int first_layer = -1, nlayers = 1;
+    float tuned_us = 0.f;   // median duration xl_tune measured for the adopted configuration (0: never timed)
     std::vector<Step> alts;
     std::vector<xl_group_info> alt_info;
 };
@@ -67,6 +68,11 @@ struct GroupPlan {
 
 }  // namespace xl
 
+struct xl_plan;
+namespace xl {
+void refresh_fused_path(xl_plan &pl);
+}
+
 struct xl_plan {
     std::vector<xl_layer> layers;
     std::vector<xl_shape> shapes;
@@ -74,6 +80,11 @@ struct xl_plan {
     std::vector<xl::Storage> storage;
     std::vector<xl::PackedFilter> packed;
     std::vector<xl::Step> fused_steps, unfused_steps;
+    // What xl_run(fused = 1) launches: the step of every block, or -- for a block switched to layer-by-layer
+    // execution (layerwise[block] != 0) -- the unfused steps of its layers.  Pointers into the two lists above,
+    // rebuilt by xl::refresh_fused_path.
+    std::vector<char> layerwise;
+    std::vector<xl::Step *> fused_active;
     size_t workspace_bytes = 0;
     int device = -1;
     int lds_budget = 160 * 1024;

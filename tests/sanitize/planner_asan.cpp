@@ -50,9 +50,9 @@ int main()
     int failures = 0, count = 0;
     while (scanf("%255s", word) == 1) {
         if (strcmp(word, "workload") != 0) { fprintf(stderr, "expected 'workload', got '%s'\n", word); return 2; }
-        int expect, nl, nt, ng, o[8];
-        if (scanf("%255s %d %d %d %d %d %d %d %d %d %d %d %d", name, &expect, &nl, &nt, &ng, &o[0], &o[1], &o[2], &o[3], &o[4],
-                  &o[5], &o[6], &o[7]) != 13) return 2;
+        int expect, nl, nt, ng, o[9];
+        if (scanf("%255s %d %d %d %d %d %d %d %d %d %d %d %d %d", name, &expect, &nl, &nt, &ng, &o[0], &o[1], &o[2], &o[3], &o[4],
+                  &o[5], &o[6], &o[7], &o[8]) != 14) return 2;
         std::vector<xl_shape> shapes(nt);
         std::vector<xl_layer> layers(nl);
         std::vector<std::vector<int>> ids(ng);
@@ -77,6 +77,7 @@ int main()
         memset(&opts, 0, sizeof opts);
         opts.lds_budget_bytes = o[0]; opts.num_cus = o[1]; opts.force_tile_h = o[2]; opts.force_tile_w = o[3];
         opts.force_cout_split = o[4]; opts.paper_tuner_only = o[5]; opts.force_threads = o[6]; opts.precision = o[7];
+        opts.keep_blocks_fused = o[8];
         xl_plan *plan = nullptr;
         const xl_status st = xl_plan_create(layers.data(), nl, shapes.data(), nt, groups.data(), ng, -1, &opts, &plan);
         ++count;
@@ -108,6 +109,20 @@ int main()
             if (xl_prepare(plan, weights.data(), 3 * nl, ws, nullptr) != XL_OK) ++failures;
             if (xl_run(plan, tensors.data(), nt, ws, nullptr, 1) != XL_OK) ++failures;
             if (xl_run(plan, tensors.data(), nt, ws, nullptr, 0) != XL_OK) ++failures;
+            // every block layer by layer and back: the launch list follows, candidates stay addressable
+            const int fused_launches = xl_plan_num_launches(plan, 1);
+            for (int g = 0; g < xl_plan_num_groups(plan); ++g)
+                if (xl_plan_set_block_fused(plan, g, 0) != XL_OK || xl_plan_block_is_fused(plan, g)) ++failures;
+            if (xl_plan_num_launches(plan, 1) != xl_plan_num_launches(plan, 0)) ++failures;
+            for (int l = 0; l < xl_plan_num_launches(plan, 1); ++l) {
+                xl_launch_info li;
+                if (xl_plan_candidate_info(plan, 1, l, -1, &li) != XL_OK || li.nlayers != 1) ++failures;
+            }
+            if (xl_run(plan, tensors.data(), nt, ws, nullptr, 1) != XL_OK) ++failures;
+            for (int g = 0; g < xl_plan_num_groups(plan); ++g)
+                if (xl_plan_set_block_fused(plan, g, 1) != XL_OK) ++failures;
+            if (xl_plan_num_launches(plan, 1) != fused_launches) ++failures;
+            if (xl_plan_set_block_fused(plan, xl_plan_num_groups(plan), 0) != XL_E_GRAPH) ++failures;
             tensors.assign(nt, reinterpret_cast<const void *>(0x2004));
             if (shapes[0].n > 0 && xl_run(plan, tensors.data(), nt, ws, nullptr, 1) != XL_E_ALIGN) ++failures;
         } else {

@@ -301,3 +301,40 @@ def test_shortcut_produced_after_the_first_layer_of_a_merge_block_is_rejected():
     assert e.value.status == B.XL_E_UNSUPPORTED
     p = B.Plan(W.merge_residual_projection(shortcut_first=True))
     assert p.num_launches(True) == 2 and p.num_launches(False) == 4
+
+
+def test_a_block_can_run_layer_by_layer_inside_the_fused_path():
+    """The fused path launches one kernel per block, or -- for a block switched off -- the kernels of its layers
+    (paper section 3.2: the tuner may only trade speed; section 3.1: reuse pays where the intermediate would
+    travel off chip).  The launch list, the candidate functions and the block flags follow the switch."""
+    wl = W.config(5)
+    p = B.Plan(wl)
+    nf, nu = p.num_launches(True), p.num_launches(False)
+    assert nf == 10 and all(p.block_is_fused(g) for g in range(10))
+    fire7 = next(g for g in range(p.num_groups) if "fire7" in wl.layers[wl.groups[g].layers[0]].name)
+    before = [p.candidate_info(True, l) for l in range(nf)]
+    p.set_block_fused(fire7, False)
+    assert not p.block_is_fused(fire7)
+    assert p.num_launches(True) == nf + 2            # squeeze, expand1x1, expand3x3 (the concat costs nothing)
+    now = [p.candidate_info(True, l) for l in range(nf + 2)]
+    pos = next(i for i, c in enumerate(before) if c["group"] == fire7)
+    assert now[:pos] == before[:pos] and now[pos + 3:] == before[pos + 1:]
+    layers = wl.groups[fire7].layers
+    assert [c["first_layer"] for c in now[pos:pos + 3]] == [l for l in layers if wl.layers[l].op != "concat"]
+    assert all(c["group"] == fire7 and c["nlayers"] == 1 for c in now[pos:pos + 3])
+    # they are the unfused path's launches: selecting a candidate here selects it there
+    u = next(l for l in range(nu) if p.candidate_info(False, l)["first_layer"] == layers[0])
+    last = p.num_candidates(True, pos) - 1
+    assert last >= 1 and p.num_candidates(False, u) == last + 1
+    p.select_candidate(True, pos, last)
+    assert p.candidate_info(False, u)["candidate"] == last
+    assert p.query(fire7)["tile_h"] == before[pos]["tile_h"]        # the block's own report is untouched
+    p.set_block_fused(fire7, True)
+    assert [p.candidate_info(True, l) for l in range(nf)] == before
+    one = B.Plan(W.single_conv(2, 8, 9, 9, 8, 3, pad=1))
+    assert not one.block_is_fused(0)                 # a block of one layer has nothing to switch
+    one.set_block_fused(0, False)
+    assert one.num_launches(True) == 1
+    with pytest.raises(B.XlError) as e:
+        p.set_block_fused(p.num_groups, False)
+    assert e.value.status == B.XL_E_GRAPH

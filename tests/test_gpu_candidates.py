@@ -93,3 +93,48 @@ def test_merge_block_with_a_projection_shortcut():
     out, ref, s = run_both(wl)
     assert s.plan.num_launches(True) == 2 and s.plan.num_launches(False) == 4
     run_both(wl, tune=True)
+
+
+@pytest.mark.parametrize("cfg,kw", [(3, {}), (4, {"n": 4}), (5, {"n": 4})])
+def test_blocks_switched_to_layer_by_layer_execution(cfg, kw):
+    """xl_plan_set_block_fused: any mix of fused blocks and blocks run layer by layer gives the network's result
+    (paper section 3.2: the tuner only changes speed)."""
+    import torch
+    from paper_2007_06000_amd.session import Session
+    wl = W.config(cfg, **kw)
+    x, params = W.make_tensors(wl)
+    ref = torch.from_numpy(xlo.forward(wl, x, params)).cuda()
+    s = Session(wl, x, params)
+    ng = s.plan.num_groups
+    for name, off in (("all", set(range(ng))), ("even", set(range(0, ng, 2))), ("odd", set(range(1, ng, 2))), ("none", set())):
+        for g in range(ng):
+            s.plan.set_block_fused(g, g not in off)
+        what = f"{wl.name} layer-by-layer blocks: {name} launches={s.plan.num_launches(True)}"
+        print("[case]", what, flush=True)
+        s.y.fill_(float("nan"))
+        s.run(True)
+        torch.cuda.synchronize()
+        check_on_device(torch, s.y, ref, what)
+    assert s.plan.num_launches(True) == ng
+
+
+def test_tuning_decides_fused_or_layer_by_layer_and_can_be_told_not_to():
+    """After xl_tune a block runs layer by layer only if that measured faster; keep_blocks_fused = 1 pins every
+    block to its kernel.  Either way the result is the oracle's."""
+    import torch
+    from paper_2007_06000_amd.session import Session
+    wl = W.config(4, n=1)           # one image: 16 tiles cannot fill 256 compute units
+    x, params = W.make_tensors(wl)
+    ref = torch.from_numpy(xlo.forward(wl, x, params)).cuda()
+    for keep in (0, 1):
+        s = Session(wl, x, params, tune=True, keep_blocks_fused=keep)
+        what = f"{wl.name} tuned keep_blocks_fused={keep} fused={[s.plan.block_is_fused(g) for g in range(s.plan.num_groups)]}"
+        print("[case]", what, flush=True)
+        if keep:
+            assert s.plan.block_is_fused(0) and s.plan.num_launches(True) == 1
+        else:
+            assert s.plan.num_launches(True) in (1, s.plan.num_launches(False))
+        s.y.fill_(float("nan"))
+        s.run(True)
+        torch.cuda.synchronize()
+        check_on_device(torch, s.y, ref, what)
