@@ -120,6 +120,22 @@ __device__ __forceinline__ int fdiv(int x, unsigned magic)
     return magic ? (int)__umulhi((unsigned)x, magic) : x;
 }
 
+// x / d for any x >= 0 with the same multiplier: the high product is the quotient or one more.
+__device__ __forceinline__ int udiv(int x, int d, unsigned magic)
+{
+    const unsigned q = __umulhi((unsigned)x, magic);
+    return magic ? (int)(q - (q * (unsigned)d > (unsigned)x ? 1u : 0u)) : x;
+}
+
+// x / d for 0 <= x <= 8 (wave counts), d >= 1: compare and count, scalar instructions when x and d are wave-uniform.
+__device__ __forceinline__ int div_upto8(int x, int d)
+{
+    int q = 0;
+#pragma unroll
+    for (int k = 1; k <= 8; ++k) q += (x >= k * d) ? 1 : 0;
+    return q;
+}
+
 // Buffer descriptor over [p, p + bytes) (clamped to 4 GB), raw dword addressing.  Address and size
 // are wave-uniform by construction; reading them through the first lane tells the compiler so --
 // otherwise every buffer access gets a loop over the distinct descriptor values of the wave.
@@ -354,8 +370,8 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
     const int f_nrt = c.nrt * RW, f_wg_rt = g.wg_rt * RW, f_base = g.rt_base * RW;     // in 1 KB rows
     const __amdgpu_buffer_rsrc_t wrsrc = make_rsrc(c.wp, (unsigned long long)nkt * f_nrt * 1024ull);
     const int w_lane = (tid & 63) * 16;
-    const int w_dkt = nwaves_wg / f_wg_rt, w_drl = nwaves_wg - w_dkt * f_wg_rt;       // row step = nwaves rows
-    const int w_kt0 = wave_id / f_wg_rt, w_rl0 = wave_id - w_kt0 * f_wg_rt;
+    const int w_dkt = div_upto8(nwaves_wg, f_wg_rt), w_drl = nwaves_wg - w_dkt * f_wg_rt;       // row step = nwaves rows
+    const int w_kt0 = div_upto8(wave_id, f_wg_rt), w_rl0 = wave_id - w_kt0 * f_wg_rt;
     auto load_w = [&](float *dst, int kg0) {
         const int kts = min(g.chunk_kg * T, nkt - kg0 * T);                     // (K step, tap) rows in this chunk
         const int base = (kg0 * T * f_nrt + f_base) * 1024;                     // byte offset of the chunk's first row
@@ -462,8 +478,11 @@ __device__ __forceinline__ void conv_pass(typename MM<MF>::Acc (&acc)[NRT][NPT],
 #pragma unroll
         for (int i = 0; i < NU; ++i) {
             const int u = i * nthreads + tid;
-            const int gr = u / upg, rem = u - gr * upg;
-            const int r = rem / qpr, q = rem - r * qpr;
+            // (u < 65536; the planner's multipliers cover the tiles that start inside the image and the tx = 0 ones)
+            const int e = xs == 0 ? 0 : 1;
+            const bool known = xs == 0 || xs == P.xs_left;
+            const int gr = known ? fdiv(u, P.rcp_upg[e]) : u / upg, rem = u - gr * upg;
+            const int r = known ? fdiv(rem, P.rcp_qpr[e]) : rem / qpr, q = rem - r * qpr;
             const int cc = xs + 4 * q;                              // first tile column of the unit
             const int gy = iy0 + r, gx = ix0 + cc;
             const bool rowok = gy >= 0 && gy < P.H;
@@ -929,10 +948,11 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
     const int L = logical_block();
     if (L >= P.nblocks) return;
     const int tiles = P.tiles_x * P.tiles_y;
-    const int tile = L % tiles;
-    const int cs = (L / tiles) % P.csplit;
-    const int n = L / (tiles * P.csplit);
-    const int ty = tile / P.tiles_x, tx = tile - ty * P.tiles_x;
+    const int n = udiv(L, tiles * P.csplit, P.rcp_tcs);
+    const int in_image = L - n * tiles * P.csplit;
+    const int cs = udiv(in_image, tiles, P.rcp_tiles);
+    const int tile = in_image - cs * tiles;
+    const int ty = udiv(tile, P.tiles_x, P.rcp_tiles_x), tx = tile - ty * P.tiles_x;
     // KIND_FUSED2P: th x tw is the stage-2 tile the pooled pth x ptw output tile needs; neighbours overlap
     const int oy0 = (KIND == KIND_FUSED2P) ? ty * P.pth * P.ps2 - P.pp : ty * P.th;
     const int ox0 = (KIND == KIND_FUSED2P) ? tx * P.ptw * P.ps2 - P.pp : tx * P.tw;
@@ -961,14 +981,15 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
     PassGeom g1;
     g1.wg_rt = P.waves_r1 * NRT1;
     g1.rt_base = (KIND == KIND_SINGLE) ? cs * g1.wg_rt : 0;
-    g1.wr = wave % P.waves_r1;
+    const int lg_r1 = __builtin_ctz(P.waves_r1);          // wave layouts are powers of two
+    g1.wr = wave & (P.waves_r1 - 1);
     g1.chunk_kg = P.chunk_kg;
     g1.src_w = P.iws;
     g1.gstride = P.in_gstride;
     g1.w_off = P.w_off1;
     g1.buf_stride = P.buf_stride;
     const int rt_end1 = min(P.c1.nrt, g1.rt_base + g1.wg_rt);
-    const int rt0 = g1.rt_base + g1.wr * NRT1, pt0 = (wave / P.waves_r1) * NPT1;
+    const int rt0 = g1.rt_base + g1.wr * NRT1, pt0 = (wave >> lg_r1) * NPT1;
     g1.active = rt0 < rt_end1 && pt0 * MF1 < npx1;
     typename M1::Acc acc[NRT1][NPT1];
     int off1[NPT1];
@@ -989,8 +1010,8 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
 
     if constexpr (KIND == KIND_SINGLE) {
         if (P.gap) {
-            store_gap<MF1, NRT1, NPT1>(acc, P, P.c1, P.coff1, n, npx1, g1.rt_base, g1.wg_rt, g1.wr, wave / P.waves_r1,
-                                       nwaves / P.waves_r1, pt0, g1.active, buf);
+            store_gap<MF1, NRT1, NPT1>(acc, P, P.c1, P.coff1, n, npx1, g1.rt_base, g1.wg_rt, g1.wr, wave >> lg_r1,
+                                       nwaves >> lg_r1, pt0, g1.active, buf);
             return;
         }
         if (g1.active)
@@ -1024,8 +1045,8 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
             const int npo = P.th * P.tw;
             const size_t plane = (size_t)P.Ho * P.Wo;
             for (int it = threadIdx.x; it < ngroups * npo; it += blockDim.x) {
-                const int gq = it / npo, pidx = it - gq * npo;
-                const int oy = pidx / P.tw, ox = pidx - oy * P.tw;
+                const int gq = udiv(it, npo, P.rcp_npo), pidx = it - gq * npo;
+                const int oy = fdiv(pidx, P.rcp_pw), ox = pidx - oy * P.tw;
                 const int gy = oy0 + oy, gx = ox0 + ox;
                 if (gy >= P.Ho || gx >= P.Wo) continue;
                 const float *s = mid + gq * P.mid_gstride + ((oy * P.s2) * P.mw + ox * P.s2) * 4;
@@ -1048,11 +1069,12 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
             // same filter chunks.
             const int sub = lane / MF2, col = lane % MF2;
             const int npt2 = (P.th * P.vw2 + MF2 - 1) / MF2;
-            const int wr2 = wave % P.waves_r2, wp2 = wave / P.waves_r2;
-            const int wg_pt2 = (nwaves / P.waves_r2) * NPT2;
+            const int lg_r2 = __builtin_ctz(P.waves_r2);
+            const int wr2 = wave & (P.waves_r2 - 1), wp2 = wave >> lg_r2;
+            const int wg_pt2 = (nwaves >> lg_r2) * NPT2;
             auto run_conv = [&](auto ks_tag, const ConvW &c, int coff, int chunk_kg2) {
                 constexpr int KS2 = decltype(ks_tag)::value;
-                const int per = (c.nrt + P.csplit - 1) / P.csplit;           // row tiles of this workgroup
+                const int per = udiv(c.nrt + P.csplit - 1, P.csplit, P.rcp_csplit);     // row tiles of this workgroup
                 const int rtb = cs * per, rte = min(c.nrt, rtb + per);
                 PassGeom g2;
                 g2.wg_rt = P.waves_r2 * NRT2;
@@ -1089,8 +1111,8 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                             const int npo = P.pth * P.ptw, npx2 = P.th * P.tw;
                             const size_t plane = (size_t)P.Ho * P.Wo;
                             for (int it = threadIdx.x; it < ngr * npo; it += blockDim.x) {
-                                const int gq = it / npo, pidx = it - gq * npo;
-                                const int py = pidx / P.ptw, px = pidx - py * P.ptw;
+                                const int gq = udiv(it, npo, P.rcp_npo), pidx = it - gq * npo;
+                                const int py = fdiv(pidx, P.rcp_pw), px = pidx - py * P.ptw;
                                 const int gy = ty * P.pth + py, gx = tx * P.ptw + px;
                                 if (gy >= P.Ho || gx >= P.Wo) continue;
                                 const float *sp = buf + (gq * npx2 + (py * P.ps2) * P.tw + px * P.ps2) * 4;

@@ -807,6 +807,26 @@ struct Builder {
         p.rcp_mw = rcp(ch.mw);
         p.rcp_vw2 = rcp(ch.vw2);
         p.rcp_qrow = rcp(p.iws / 4);
+        p.rcp_tiles = rcp(ch.tiles_x * ch.tiles_y);
+        p.rcp_tcs = rcp(ch.tiles_x * ch.tiles_y * ch.csplit);
+        p.rcp_csplit = rcp(ch.csplit);
+        p.rcp_tiles_x = rcp(ch.tiles_x);
+        {
+            const bool pool2 = b.kind == KIND_FUSED2P;
+            const int ph = pool2 ? ch.pth : ch.th, pw = pool2 ? ch.ptw : ch.tw;
+            p.rcp_npo = rcp(ph * pw);
+            p.rcp_pw = rcp(pw);
+            // first input column of the tx = 0 tiles, as block_kernel derives it (output -> intermediate -> input)
+            const int ox0 = pool2 ? -p.pp : 0;
+            const int mx0 = b.kind == KIND_SINGLE ? ox0 : ox0 * p.s2 - p.P2;
+            const int ix0 = mx0 * b.c1.stride - b.c1.pad;
+            p.xs_left = std::max(0, -ix0);
+            for (int e = 0; e < 2; ++e) {
+                const int qpr = (ch.iw - (e ? p.xs_left : 0) + 3) >> 2;
+                p.rcp_qpr[e] = rcp(qpr);
+                p.rcp_upg[e] = rcp(ch.ih * qpr);
+            }
+        }
         p.mid_gstride = ch.mh * ch.mw * 4;
         p.in_gstride = ch.ih * p.iws * 4;
         p.lds_buf_off = ch.mid_floats;

@@ -92,6 +92,13 @@ struct BlockParams {
     int waves_r2;           // stage-2 waves along the row-tile direction
     int vw2;                // stage 2 lays output pixels out in virtual rows of vw2 >= tw columns
     unsigned rcp_mw, rcp_vw2, rcp_qrow;   // 2^32 / d + 1 for d = mw, vw2, iws / 4 (0 when d is 1): x / d = mulhi(x, rcp) for x < 65536
+    // The same multipliers for the other divisors of the index arithmetic (a division by a run-time value costs
+    // about 30 vector instructions, and a vector instruction is paid for in matrix-core time):
+    unsigned rcp_tiles, rcp_tcs, rcp_csplit, rcp_tiles_x;   // d = tiles_x * tiles_y, that times csplit, csplit, tiles_x
+    unsigned rcp_npo, rcp_pw;       // pooling from an LDS tile: d = pooled pixels per tile, pooled pixels per tile row
+    int xs_left;                    // input-tile columns left of the image for the tiles with tx = 0
+    unsigned rcp_qpr[2], rcp_upg[2];// input stager: d = 4-pixel units per tile row / per channel group, for tiles that
+                                    // start inside the image ([0]) and for the tx = 0 tiles ([1])
     int mid_gstride;        // floats between consecutive 4-channel groups of the LDS tile
     int in_gstride;         // same for the staged input
     int lds_buf_off;        // float offset of the two staging buffers in LDS (after the tile)
