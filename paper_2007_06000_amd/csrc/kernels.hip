@@ -1427,6 +1427,8 @@ static BlockKernel select_kernel()
 {
     if constexpr (KIND == KIND_POOLS)
         return pool_stream_kernel<MF1, K1, NRT1, NPT1, (PX1 < 0 ? -PX1 : 4)>;
+    else if constexpr (KIND == KIND_THIN && NPT1 == 2)
+        return thin_conv_pool_kernel<NRT1>;          // Cin; 3x3 stride 2 -> pooling 3x3 stride 2
     else if constexpr (KIND == KIND_THIN)
         return thin_conv_kernel<NRT1, K1, K2B>;      // Cin, K, pooling window
     else
@@ -1548,7 +1550,7 @@ hipError_t launch_pack_filter(const float *w, const float *scale, f32x4 *wp, int
 hipError_t launch_pack_thin(const float *w, const float *scale, const float *shift, float *wp, float *aff, int cout,
                             int taps, hipStream_t s)
 {
-    const int total = (cout + 15) / 16 * 16 * taps;
+    const int total = (cout + 15) / 16 * 16 * thin_row_floats(taps);
     return launch(pack_thin_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w, scale, shift, wp, aff, cout, taps);
 }
 

@@ -243,8 +243,12 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
             if (v.k1 != b.c1.k || v.nrt1 != b.c1.cin || v.k2b != (pooled ? b.pool_k : 0)) continue;
             const double taps = (double)b.c1.cin * b.c1.k * b.c1.k;
             const int rows16 = ceil_div(b.c1.cout, 16) * 16;
-            for (int threads : {256, 512}) {
+            // npt1 = 2: a lane owns the 2x2 block of convolution outputs under one pooled pixel (stride-2 layers only)
+            const bool blocks = v.npt1 == 2;
+            if (blocks && !(pooled && b.c1.stride == 2 && b.pool_s == 2 && b.pool_p == 0)) continue;
+            for (int threads : {128, 192, 256, 512}) {
                 if (pl.opts.force_threads > 0 && pl.opts.force_threads != threads) continue;
+                if (blocks ? threads > 256 : threads < 256) continue;
                 for (auto [th, tw] : tiles) {
                     Choice c;
                     c.v = v;
@@ -253,6 +257,37 @@ static std::vector<Choice> search(const BlockSpec &b, const xl_plan &pl, bool &l
                     c.th = th;
                     c.tw = tw;
                     c.vw2 = tw;
+                    if (blocks) {
+                        // (th + 1) x (tw + 1) lanes: the last row and column of blocks only supply neighbours
+                        c.mh = th + 1;
+                        c.mw = tw + 1;
+                        const int lanes = c.mh * c.mw;
+                        if (lanes > threads || (lanes + 64 <= threads && threads > 128)) continue;      // the smallest workgroup that holds the tile
+                        if (lanes * 10 < threads * 7 && !(th == b.Ho && tw == b.Wo) && !(pl.opts.force_tile_h > 0)) continue;
+                        c.ih = 4 * c.mh + 1;
+                        c.iw = 4 * c.mw + 1;
+                        c.tiles_y = ceil_div(b.Ho, th);
+                        c.tiles_x = ceil_div(b.Wo, tw);
+                        c.csplit = 1;
+                        c.chunk_kg = 1;
+                        c.lds_bytes = 2 * THIN_PCB * 3 * threads * 4;       // two tiles of 4 channels x 3 maxima per lane
+                        if (c.lds_bytes > pl.lds_budget) {
+                            any_lds_reject = true;
+                            continue;
+                        }
+                        c.occ = std::max(1, std::min({pl.lds_per_cu / c.lds_bytes, 2048 / threads, 20 / (threads / 64)}));
+                        const double nwg = (double)c.tiles_x * c.tiles_y * b.N;
+                        // four multiply-adds per filter value, channel and lane, about 2.3 cycles each at full occupancy
+                        const double wave_clk = rows16 * (4.0 * taps + 24.0) * 2.3 + 1500.0;
+                        const double t_alu = nwg * (threads / 64) / (4.0 * pl.num_cus) * wave_clk / 2.4e9;
+                        const double t_mem = (double)b.alg_bytes / 8.0e12;
+                        c.cost = std::max(t_alu, t_mem) + 0.15 * std::min(t_alu, t_mem);
+                        c.flops_exec = (long long)(nwg * threads * rows16 * taps * 8.0);
+                        c.ok = true;
+                        if (!best.ok || c.cost < best.cost) best = c;
+                        per_key[std::make_tuple(v.id, threads, th, tw)] = c;
+                        continue;
+                    }
                     c.mh = pooled ? required_extent(th, b.pool_k, b.pool_s) : th;      // convolution outputs under the tile
                     c.mw = pooled ? required_extent(tw, b.pool_k, b.pool_s) : tw;
                     const int npx = c.mh * c.mw;
@@ -654,9 +689,9 @@ struct Builder {
         p.mf = mf;
         p.pairs = pairs;
         p.pr = pr;
-        if (mf < 0) {       // thin first layer: [Cout rounded up to 16][Cin*K*K] floats and as many shifts
+        if (mf < 0) {       // thin first layer: [Cout rounded up to 16][row of Cin*K*K floats, padded] and as many shifts
             p.nkg = p.nrt = 0;
-            p.bytes = (size_t)ceil_div(L.cout, 16) * 16 * L.cin * L.k * L.k * 4;
+            p.bytes = (size_t)ceil_div(L.cout, 16) * 16 * thin_row_floats(L.cin * L.k * L.k) * 4;
             p.aff_bytes = (size_t)ceil_div(L.cout, 16) * 16 * 4;
         } else if (mf == 0) {      // depthwise: [channel group][tap] float4 and [channel group][scale, shift] float4
             p.nkg = p.nrt = 0;

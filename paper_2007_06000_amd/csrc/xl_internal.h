@@ -244,6 +244,9 @@ struct Variant {
     X(137, KIND_THIN, 32, 5, 3, 1, 0, 0, 0, 0, 0, 0, 0)           \
     X(138, KIND_THIN, 32, 1, 3, 1, 0, 0, 0, 0, 0, 0, 0)           \
     X(139, KIND_THIN, 32, 1, 4, 1, 0, 0, 0, 0, 0, 0, 0)           \
+    /* ... 3x3 stride 2 -> pooling 3x3 stride 2 with a 2x2 block of convolution outputs per lane (column 6 = 2) */ \
+    X(140, KIND_THIN, 32, 3, 3, 2, 0, 0, 0, 0, 3, 0, 0)           \
+    X(141, KIND_THIN, 32, 3, 1, 2, 0, 0, 0, 0, 3, 0, 0)           \
     /* conv -> maxpool */                                 \
     X(36, KIND_POOL, 32, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0)             \
     X(37, KIND_POOL, 32, 1, 2, 1, 0, 0, 0, 0, 0, 0, 0)             \
@@ -312,6 +315,10 @@ constexpr int STAGE_UNITS = XL_STAGE_UNITS;      // input units (4 channels x 4 
 constexpr int MAX_W_CHUNK_BYTES = 52 * 1024;  // filter bytes staged per chunk (LDS-direct loads, no registers)
 constexpr int PLANAR_SLOTS = 8;     // LDS-direct loads per wave and chunk of a planar input chunk
 constexpr int MAX_THREADS = 512;
+// floats per filter row of the thin layout: the taps rounded up to whole 64-byte lines, so that a row is read by
+// aligned 64-byte scalar loads (the scalar cache serves requests, not bytes: a row that straddles lines costs more)
+constexpr int thin_row_floats(int taps) { return (taps + 15) / 16 * 16; }
+constexpr int THIN_PCB = 4;         // thin_conv_pool_kernel: output channels per LDS tile (per barrier)
 constexpr int MAX_ALTERNATIVES = 64;  // candidates per block kept for on-device tuning
 #ifndef XL_MIN_WAVES
 #define XL_MIN_WAVES 2

@@ -138,3 +138,21 @@ def test_tuning_decides_fused_or_layer_by_layer_and_can_be_told_not_to():
         s.run(True)
         torch.cuda.synchronize()
         check_on_device(torch, s.y, ref, what)
+
+
+@pytest.mark.parametrize("wl", [
+    W.conv_pool_generic(3, 3, 37, 41, 24, 3, 0, 2, 3, 2, 0),                 # ragged tiles, Cout not a multiple of 16
+    W.conv_pool_generic(2, 3, 33, 29, 20, 3, 1, 2, 3, 2, 0, relu=False),     # padded convolution, negative values reach the pooling
+    W.conv_pool_generic(2, 1, 40, 40, 7, 3, 0, 2, 3, 2, 0),                  # one input channel, 7 output channels
+    W.conv_pool_generic(1, 3, 11, 11, 5, 3, 2, 2, 3, 2, 0, bn=True),         # tiny image, padding 2, folded BN
+    W.conv_pool_generic(5, 3, 64, 20, 33, 3, 0, 2, 3, 2, 0),                 # tall image: tiles of one column
+], ids=lambda w: w.name)
+def test_every_candidate_of_stem_shaped_blocks(wl):
+    """3x3 stride-2 convolution -> 3x3 stride-2 max pooling on a few input channels: besides the general thin kernel
+    these blocks have the one where a lane owns the 2x2 block of convolution outputs under a pooled pixel."""
+    from paper_2007_06000_amd import binding as B
+    p = B.Plan(wl)
+    variants = {p.candidate_info(True, 0, c)["variant"] for c in range(p.num_candidates(True, 0))}
+    assert variants & {140, 141}, variants
+    assert variants - {140, 141}, variants
+    run_every_candidate(wl)
