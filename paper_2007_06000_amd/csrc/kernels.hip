@@ -1051,12 +1051,24 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                 if (gy >= P.Ho || gx >= P.Wo) continue;
                 const float *s = mid + gq * P.mid_gstride + ((oy * P.s2) * P.mw + ox * P.s2) * 4;
                 f32x4 m = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
-                for (int u = 0; u < P.pool_k; ++u)
-                    for (int v = 0; v < P.pool_k; ++v) {
-                        const f32x4 t = *(const f32x4 *)(s + (u * P.mw + v) * 4);
+                if (P.pool_k == 3) {        // the usual window, unrolled: nine reads in flight together
+                    f32x4 t[9];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
-                    }
+                    for (int u = 0; u < 3; ++u)
+#pragma unroll
+                        for (int v = 0; v < 3; ++v) t[u * 3 + v] = *(const f32x4 *)(s + (u * P.mw + v) * 4);
+#pragma unroll
+                    for (int k = 0; k < 9; ++k)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[k][j]);
+                } else {
+                    for (int u = 0; u < P.pool_k; ++u)
+                        for (int v = 0; v < P.pool_k; ++v) {
+                            const f32x4 t = *(const f32x4 *)(s + (u * P.mw + v) * 4);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
+                        }
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int co = gq * 4 + j;
@@ -1117,12 +1129,24 @@ __global__ void __launch_bounds__(MAX_THREADS, (KIND == KIND_POOL ? 4 : XL_MIN_W
                                 if (gy >= P.Ho || gx >= P.Wo) continue;
                                 const float *sp = buf + (gq * npx2 + (py * P.ps2) * P.tw + px * P.ps2) * 4;
                                 f32x4 m = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
-                                for (int u = 0; u < P.pool_k; ++u)
-                                    for (int v = 0; v < P.pool_k; ++v) {
-                                        const f32x4 t = *(const f32x4 *)(sp + (u * P.tw + v) * 4);
+                                if (P.pool_k == 3) {        // the usual window, unrolled: nine reads in flight together
+                                    f32x4 t[9];
 #pragma unroll
-                                        for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
-                                    }
+                                    for (int u = 0; u < 3; ++u)
+#pragma unroll
+                                        for (int v = 0; v < 3; ++v) t[u * 3 + v] = *(const f32x4 *)(sp + (u * P.tw + v) * 4);
+#pragma unroll
+                                    for (int k = 0; k < 9; ++k)
+#pragma unroll
+                                        for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[k][j]);
+                                } else {
+                                    for (int u = 0; u < P.pool_k; ++u)
+                                        for (int v = 0; v < P.pool_k; ++v) {
+                                            const f32x4 t = *(const f32x4 *)(sp + (u * P.tw + v) * 4);
+#pragma unroll
+                                            for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
+                                        }
+                                }
 #pragma unroll
                                 for (int j = 0; j < 4; ++j) {
                                     const int co = rp * MF2 + gq * 4 + j;
@@ -1364,12 +1388,24 @@ __global__ void __launch_bounds__(MAX_THREADS, 4) pool_stream_kernel(const Block
             const int gy = oy0 + oy, gx = ox0 + ox;
             if (gy >= P.Ho || gx >= P.Wo) continue;
             f32x4 m = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
-            for (int u = 0; u < P.pool_k; ++u)
-                for (int v = 0; v < P.pool_k; ++v) {
-                    const f32x4 t = *(const f32x4 *)(sp + (u * P.mw + v) * 4);
+            if (P.pool_k == 3) {        // the usual window, unrolled: nine reads in flight together
+                f32x4 t[9];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
-                }
+                for (int u = 0; u < 3; ++u)
+#pragma unroll
+                    for (int v = 0; v < 3; ++v) t[u * 3 + v] = *(const f32x4 *)(sp + (u * P.mw + v) * 4);
+#pragma unroll
+                for (int k = 0; k < 9; ++k)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[k][j]);
+            } else {
+                for (int u = 0; u < P.pool_k; ++u)
+                    for (int v = 0; v < P.pool_k; ++v) {
+                        const f32x4 t = *(const f32x4 *)(sp + (u * P.mw + v) * 4);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], t[j]);
+                    }
+            }
             // 32-bit offsets from the image's first element (per-image element counts fit 30 bits: planner)
             const unsigned vo = (unsigned)(((P.coff1 + gq * 4) * (int)oplane + gy * P.Wo + gx) * 4);
             const float mv[4] = {m[0], m[1], m[2], m[3]};     // (a bit cast of a vector element picks element 0)
