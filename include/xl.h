@@ -242,8 +242,8 @@ xl_status xl_run(const xl_plan *plan, const void *const *tensors, int ntensors,
  * repeatedly; call it once, outside any timed region.  Every candidate is timed three times (fastest
  * kept) and the six fastest again `reps` times each (reps < 5 means 5), ranked by their MEDIAN
  * time; ties go to the lower candidate index.  xl_plan_candidate_info(.., -1, ..) names the winner.
- * Last, a block whose layers run one kernel each in less than 0.95 of the time of its fused kernel
- * (both medians of this call) is switched to layer-by-layer execution inside the fused path, as by
+ * Last, a block whose layers, run back to back one kernel each, take less than 0.97 of the time of its fused
+ * kernel (both medians of this call) is switched to layer-by-layer execution inside the fused path, as by
  * xl_plan_set_block_fused(.., 0), and every other block is (re)set to fused; options.keep_blocks_fused = 1
  * leaves that step out.
  */

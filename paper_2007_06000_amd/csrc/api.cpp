@@ -445,7 +445,7 @@ xl_status xl_measure_peaks(void *dst, const void *src, size_t bytes, void *strea
 }
 
 // A block leaves the fused path for its layers' own kernels only when those measured this much faster.
-static constexpr float LAYERWISE_MARGIN = 0.95f;
+static constexpr float LAYERWISE_MARGIN = 0.97f;
 
 // Make candidate `idx` the configuration of step `st`; in the fused path the block's reported tiles follow.
 static void adopt(xl_plan *plan, xl::Step &st, int idx, bool fused)
@@ -629,23 +629,39 @@ xl_status xl_tune(xl_plan *plan, const void *const *tensors, int ntensors, void 
             st.tuned_us = best_ms * 1e3f;
         }
     }
-    // A block whose layers, one kernel each, were measured clearly faster than its fused kernel runs layer by
-    // layer in the fused path (small images at a batch that cannot fill the chip with whole tiles, a batch
-    // of 1): the tuner only ever trades speed, and the fused path is then never the slower one.  The margin
-    // covers what single-launch timings on warm buffers cannot see (launches of a sequence overlap at their
-    // ends; intermediates that stay in cache here reach HBM in a long pipeline).
+    // A block whose layers, one kernel each and back to back, were measured faster than its fused kernel runs
+    // layer by layer in the fused path (small images at a batch that cannot fill the chip with whole tiles, a
+    // batch of 1): the tuner only ever trades speed, and the fused path is then not the slower one.  The margin
+    // covers what timings on warm buffers cannot see (intermediates that stay in cache here reach HBM in a long
+    // pipeline).
     if (rc == XL_OK && !plan->opts.keep_blocks_fused) {
         for (const xl::Step &st : plan->fused_steps) {
             if (st.nlayers < 2 || st.group < 0 || st.tuned_us <= 0.f) continue;
             const std::vector<int> &ls = plan->groups[st.group].layers;
-            float sum = 0.f;
-            bool all = true;
+            std::vector<const xl::Step *> seq;
             for (const xl::Step &u : plan->unfused_steps)
-                if (std::find(ls.begin(), ls.end(), u.first_layer) != ls.end()) {
-                    all = all && u.tuned_us > 0.f;
-                    sum += u.tuned_us;
+                if (std::find(ls.begin(), ls.end(), u.first_layer) != ls.end()) seq.push_back(&u);
+            // the layers as they would run: back to back, one pair of events around the sequence
+            std::vector<float> t;
+            for (int r = 0; r < reps + 1 && rc == XL_OK; ++r) {
+                (void)hipEventRecord(e0, s);
+                for (const xl::Step *u : seq) {
+                    rc = launch_step(plan, *u, tensors, ws, s);
+                    if (rc != XL_OK) break;
                 }
-            plan->layerwise[st.group] = all && sum > 0.f && sum < LAYERWISE_MARGIN * st.tuned_us;
+                (void)hipEventRecord(e1, s);
+                if (hipEventSynchronize(e1) != hipSuccess) {
+                    if (rc == XL_OK) rc = run_fail(plan, XL_E_LAUNCH, "a kernel failed while tuning");
+                    break;
+                }
+                float ms = 0.f;
+                (void)hipEventElapsedTime(&ms, e0, e1);
+                if (r > 0) t.push_back(ms);         // (the first run warms code and caches)
+            }
+            if (rc != XL_OK) break;
+            std::sort(t.begin(), t.end());
+            const float seq_us = t[t.size() / 2] * 1e3f;
+            plan->layerwise[st.group] = !seq.empty() && seq_us < LAYERWISE_MARGIN * st.tuned_us;
         }
         xl::refresh_fused_path(*plan);
     }
