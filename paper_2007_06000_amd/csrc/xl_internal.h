@@ -165,6 +165,10 @@ struct Variant {
     X(8, KIND_SINGLE, 16, 1, 3, 2, 0, 0, 0, 0, 0, 0, 0)            \
     X(9, KIND_SINGLE, 16, 3, 1, 1, 0, 0, 0, 0, 0, 0, 0)            \
     X(10, KIND_SINGLE, 16, 3, 1, 2, 0, 0, 0, 0, 0, 0, 0)           \
+    /* 3x3 layers on small images: 16-pixel tiles, three per wave (13x13 = 169 pixels pad to 176, in 12 slots) */ \
+    X(150, KIND_SINGLE, 16, 3, 1, 3, 0, 0, 0, 0, 0, 0, 0)          \
+    X(151, KIND_SINGLE, 16, 3, 2, 3, 0, 0, 0, 0, 0, 0, 0)          \
+    X(152, KIND_SINGLE, 16, 3, 2, 2, 0, 0, 0, 0, 0, 0, 0)          \
     /* split (fire-like): 1x1 -> {3x3, 1x1} */            \
     X(11, KIND_FUSED2, 32, 1, 1, 1, 32, 2, 1, 3, 1, 0, 0)          \
     X(12, KIND_FUSED2, 32, 1, 2, 1, 32, 2, 1, 3, 1, 0, 0)          \
